@@ -1,0 +1,132 @@
+"""Seeded synthetic inputs (weights, activations, KV caches) for the Ecco hot path.
+
+This module holds no part of the method's arithmetic: it only draws numbers.  It is the one
+piece of code that both the CPU oracle's tests and the HIP path's tests / benchmark may share,
+so it imports nothing from the rest of the package and nothing from the oracle.
+
+Generator: a counter-based PRNG.  Value number ``i`` of stream ``t`` under ``seed`` is
+``mix64(mix64(seed * C0 + t * C1) + (i + 1) * GOLDEN)`` with the splitmix64 finaliser as
+``mix64``.  Uniforms take the top 53 bits; normals are Box-Muller on two streams.  Every
+array is therefore reproducible piecewise (any slice can be regenerated without the rest).
+
+The tensors stand in for the LLaMA / Mistral projection weights and KV caches on which the
+paper measures (Section 5, "Experimental setup"), which are not available here:
+near-Gaussian weights with a small fraction of large outliers, keys with strong per-channel
+scale structure, values without it.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+_GOLDEN = np.uint64(0x9E3779B97F4A7C15)
+_C0 = np.uint64(0xD1342543DE82EF95)
+_C1 = np.uint64(0xA0761D6478BD642F)
+_M1 = np.uint64(0xBF58476D1CE4E5B9)
+_M2 = np.uint64(0x94D049BB133111EB)
+
+GROUP = 128  # values per Ecco group (Section 3.1, "Target Compression Ratio")
+
+
+def _mix64(z: np.ndarray) -> np.ndarray:
+    z = z.astype(np.uint64, copy=True)
+    z ^= z >> np.uint64(30)
+    z *= _M1
+    z ^= z >> np.uint64(27)
+    z *= _M2
+    z ^= z >> np.uint64(31)
+    return z
+
+
+def raw_u64(seed: int, stream: int, start: int, count: int) -> np.ndarray:
+    """``count`` 64-bit words of stream ``stream``, beginning at counter ``start``."""
+    with np.errstate(over="ignore"):
+        key = _mix64(np.array([np.uint64(seed) * _C0 + np.uint64(stream) * _C1], dtype=np.uint64))[0]
+        ctr = np.arange(start + 1, start + 1 + count, dtype=np.uint64)
+        return _mix64(key + ctr * _GOLDEN)
+
+
+def uniform01(seed: int, stream: int, start: int, count: int) -> np.ndarray:
+    """float64 uniforms in [0, 1)."""
+    return (raw_u64(seed, stream, start, count) >> np.uint64(11)).astype(np.float64) * (1.0 / 9007199254740992.0)
+
+
+def normal(seed: int, stream: int, start: int, count: int) -> np.ndarray:
+    """float64 standard normals (Box-Muller on streams 2*stream and 2*stream+1)."""
+    u1 = uniform01(seed, 2 * stream, start, count)
+    u2 = uniform01(seed, 2 * stream + 1, start, count)
+    return np.sqrt(-2.0 * np.log1p(-u1)) * np.cos(2.0 * np.pi * u2)
+
+
+def _chunks(n: int, step: int = 1 << 22):
+    for s in range(0, n, step):
+        yield s, min(step, n - s)
+
+
+def weight_matrix(rows: int, cols: int, sigma: float, outlier_frac: float, outlier_mult: float,
+                  seed: int, row_start: int = 0) -> np.ndarray:
+    """rows x cols fp16: N(0, sigma) with a Bernoulli(outlier_frac) subset multiplied by outlier_mult.
+
+    ``row_start`` lets a caller generate further rows of the same infinite matrix.
+    """
+    n = rows * cols
+    base = row_start * cols
+    out = np.empty(n, dtype=np.float16)
+    for s, c in _chunks(n):
+        z = normal(seed, 0, base + s, c) * sigma
+        if outlier_frac > 0.0:
+            mask = uniform01(seed, 7, base + s, c) < outlier_frac
+            z = np.where(mask, z * outlier_mult, z)
+        out[s:s + c] = z.astype(np.float16)
+    return out.reshape(rows, cols)
+
+
+def activation(batch: int, cols: int, seed: int) -> np.ndarray:
+    """batch x cols fp16, N(0, 1)."""
+    return normal(seed, 0, 0, batch * cols).astype(np.float16).reshape(batch, cols)
+
+
+def kv_cache(batch: int, heads: int, tokens: int, head_dim: int, seed: int, token_start: int = 0):
+    """K and V, each [batch][heads][tokens][head_dim] fp16.
+
+    K = a[h][d] * N(0,1) with a = 10**U(-1,1) (per-channel scales, shared over batch and
+    tokens); V = N(0,1).  ``token_start`` addresses later tokens of the same infinite cache:
+    element (b,h,t,d) depends only on its own coordinates.
+    """
+    a = 10.0 ** (2.0 * uniform01(seed, 20, 0, heads * head_dim) - 1.0)
+    a = a.reshape(1, heads, 1, head_dim)
+    k = np.empty((batch, heads, tokens, head_dim), dtype=np.float16)
+    v = np.empty((batch, heads, tokens, head_dim), dtype=np.float16)
+    big_t = 1 << 20  # counter stride per (b, h): far above any token count used
+    for b in range(batch):
+        for h in range(heads):
+            start = ((b * heads + h) * big_t + token_start) * head_dim
+            zk = normal(seed, 1, start, tokens * head_dim).reshape(tokens, head_dim)
+            zv = normal(seed, 2, start, tokens * head_dim).reshape(tokens, head_dim)
+            k[b, h] = (zk * a[0, h]).astype(np.float16)
+            v[b, h] = zv.astype(np.float16)
+    return k, v
+
+
+# The five workloads of the build's baseline description.  'fit_groups' is how many groups the
+# pattern fit sees at most; seeds for configs 2-5 are this build's choice (only config 1 fixes 0).
+CONFIGS = {
+    "tiny": dict(kind="weight", shapes=[(64, 1024)], sigma=0.02, outlier_frac=1e-3, outlier_mult=10.0,
+                 S=16, seeds=[0], x_seed=100),
+    "proj7b": dict(kind="weight", shapes=[(4096, 4096)], sigma=0.02, outlier_frac=1e-3, outlier_mult=10.0,
+                   S=64, seeds=[1], x_seed=101),
+    "mlp": dict(kind="weight", shapes=[(11008, 4096), (4096, 11008)], sigma=0.02, outlier_frac=1e-3,
+                outlier_mult=10.0, S=64, seeds=[2, 12], x_seed=102),
+    "kv": dict(kind="kv", batch=8, heads=32, head_dim=128, tokens=4096, calib_tokens=512, S=64,
+               seeds=[3], q_seed=103),
+    "proj70b": dict(kind="weight", shapes=[(8192, 28672)], sigma=0.015, outlier_frac=5e-4, outlier_mult=12.0,
+                    S=64, seeds=[4], x_seed=104),
+}
+
+
+def config_weight(name: str, which: int = 0, rows: int | None = None) -> np.ndarray:
+    """The ``which``-th weight matrix of config ``name`` (optionally only its first ``rows`` rows)."""
+    c = CONFIGS[name]
+    r, k = c["shapes"][which]
+    if rows is not None:
+        r = rows
+    return weight_matrix(r, k, c["sigma"], c["outlier_frac"], c["outlier_mult"], c["seeds"][which])

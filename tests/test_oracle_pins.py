@@ -1,0 +1,544 @@
+"""Pins for the CPU oracle: each test ties one oracle routine to something other than itself --
+values the paper prints, closed forms, exact integer arithmetic, brute force on tiny inputs,
+special cases that reduce to textbook routines.  No GPU, no HIP library.
+"""
+from __future__ import annotations
+
+import itertools
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from helpers import half_to_fraction, py_canonical, round_fraction_to_half, stream_bits
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# --------------------------------------------------------------------------------------------
+# what the paper prints (Section 3.1, 3.2, 4.2, 4.3)
+def _constants():
+    out = {}
+    with open(os.path.join(GOLDEN, "paper_constants.txt")) as f:
+        for line in f:
+            line = line.split("#")[0].split()
+            if len(line) == 2:
+                out[line[0]] = int(line[1])
+    return out
+
+
+def test_paper_constants(oracle):
+    c = _constants()
+    assert oracle.BLOCK_BYTES == c["block_bytes"]
+    assert oracle.GROUP == c["group_values"]
+    assert oracle.K == c["indices_per_group"]
+    assert c["decoder_segments"] * c["segment_bits"] == 8 * oracle.BLOCK_BYTES
+    assert c["uncompressed_bytes"] == 2 * oracle.GROUP
+    assert c["uncompressed_bytes"] // c["block_bytes"] == 4  # the 4x ratio
+    # a block really is 64 bytes for 128 values
+    cent = np.zeros((1, 16), np.float16).view(np.uint16)
+    lens = np.full((1, 16), 4, np.uint8)
+    blocks, meta = oracle.encode(cent, lens, np.zeros(256, np.uint16))
+    assert blocks.shape == (2, 64) and meta.shape == (2,)
+
+
+# --------------------------------------------------------------------------------------------
+# fp16 helpers
+def test_h2f_exhaustive_against_numpy(oracle):
+    L = oracle.lib()
+    h = np.arange(65536, dtype=np.uint16)
+    ref = h.view(np.float16).astype(np.float32)
+    got = np.array([L.oracle_h2f(int(v)) for v in h], dtype=np.float32)
+    finite = np.isfinite(ref)
+    assert np.array_equal(got[finite].view(np.uint32), ref[finite].view(np.uint32))
+    assert np.all(np.isnan(got[np.isnan(ref)]))
+    assert np.array_equal(got[np.isinf(ref)], ref[np.isinf(ref)])
+
+
+def test_f2h_roundtrip_and_midpoints(oracle):
+    L = oracle.lib()
+    # round trip on every non-NaN pattern
+    for h in range(65536):
+        if ((h >> 10) & 0x1F) == 31 and (h & 0x3FF):
+            continue
+        assert L.oracle_f2h(L.oracle_h2f(h)) == h
+    # every midpoint between neighbouring positive halves: the tie goes to the even pattern;
+    # one fp32 ulp to either side goes to the nearer one
+    for h in range(0, 0x7BFF):
+        a = np.float32(np.uint16(h).view(np.float16))
+        b = np.float32(np.uint16(h + 1).view(np.float16))
+        mid = np.float32((np.float64(a) + np.float64(b)) / 2)  # exact in fp32
+        even = h if (h & 1) == 0 else h + 1
+        assert L.oracle_f2h(float(mid)) == even
+        assert L.oracle_f2h(float(np.nextafter(mid, np.float32(0)))) == h
+        assert L.oracle_f2h(float(np.nextafter(mid, np.float32(np.inf)))) == h + 1
+        assert L.oracle_f2h(float(-mid)) == (even | 0x8000)
+    # overflow: 65520 is the midpoint between 65504 and 2^16 -> infinity (even), just below -> 65504
+    assert L.oracle_f2h(65520.0) == 0x7C00
+    assert L.oracle_f2h(float(np.nextafter(np.float32(65520.0), np.float32(0)))) == 0x7BFF
+    assert L.oracle_f2h(1e9) == 0x7C00 and L.oracle_f2h(-1e9) == 0xFC00
+
+
+def test_f2h_random_against_numpy(oracle):
+    L = oracle.lib()
+    rng = np.random.default_rng(5)
+    bits = rng.integers(0, 2**32, size=40000, dtype=np.uint64).astype(np.uint32)
+    # concentrate exponents around the fp16 range
+    bits = (bits & np.uint32(0x807FFFFF)) | (rng.integers(95, 146, size=bits.size).astype(np.uint32) << np.uint32(23))
+    f = bits.view(np.float32)
+    with np.errstate(over="ignore"):
+        ref = f.astype(np.float16).view(np.uint16)
+    got = np.array([L.oracle_f2h(float(v)) for v in f], dtype=np.uint16)
+    assert np.array_equal(got, ref)
+
+
+def test_dequant_rule_exact_rational(oracle):
+    """fp32-multiply-then-round == the exact rational product rounded once to fp16."""
+    rng = np.random.default_rng(11)
+    cents = [0x3C00, 0xBC00, 0x0000, 0x3800, 0x3555, 0xB266, 0x2E66, 0x0001, 0x03FF, 0x3BFF, 0x1234, 0x8000]
+    scales = list(rng.integers(0, 0x7C00, size=1500)) + [0, 1, 2, 0x3FF, 0x400, 0x401, 0x7BFF, 0x3C00, 0x0200]
+    for c in cents:
+        fc = half_to_fraction(c)
+        for s in scales:
+            s = int(s)
+            want = round_fraction_to_half(fc * half_to_fraction(s))
+            got = oracle.dequant(c, s)
+            if (want & 0x7FFF) == 0:  # signed zero: sign of the product
+                want = (c ^ s) & 0x8000
+            assert got == want, (hex(c), hex(s), hex(got), hex(want))
+
+
+def test_dequant_all_scales_through_decode(oracle):
+    """All 31744 finite positive scales x 16 centroids, through oracle.decode on raw blocks,
+    against numpy's own fp32 product and fp16 rounding."""
+    cent = np.array([[-1.0, -0.75, -0.52, -0.33, -0.2, -0.1, -0.031, -0.0007, 0.0, 0.011, 0.09, 0.21, 0.37, 0.5, 0.83, 1.0]],
+                    np.float16)
+    lens = np.full((1, 16), 4, np.uint8)
+    scales = np.arange(0, 0x7C00, dtype=np.uint32)
+    n = scales.size
+    nib = np.arange(128) % 16
+    block = (nib[0::2] | (nib[1::2] << 4)).astype(np.uint8)
+    blocks = np.tile(block, (n, 1))
+    meta = scales | (1 << 22)
+    got = oracle.decode(cent.view(np.uint16), lens, blocks, meta)
+    prod = cent.astype(np.float32)[0][nib][None, :] * scales.astype(np.uint16).view(np.float16).astype(np.float32)[:, None]
+    want = prod.astype(np.float16).view(np.uint16)
+    assert np.array_equal(got, want)
+
+
+# --------------------------------------------------------------------------------------------
+# Huffman
+def _kraft(lens):
+    return sum(Fraction(1, 2 ** int(l)) for l in lens)
+
+
+def _brute_best_cost(counts, max_len):
+    """Cheapest sum(count*len) over all length vectors with Kraft sum <= 1 and len <= max_len."""
+    n = len(counts)
+    best = None
+    for lens in itertools.product(range(1, max_len + 1), repeat=n):
+        if _kraft(lens) <= 1:
+            cost = sum(c * l for c, l in zip(counts, lens))
+            if best is None or cost < best:
+                best = cost
+    return best
+
+
+def test_huffman_dyadic_closed_form(oracle):
+    # counts 2^k: the optimal length of a symbol of probability 2^-l is exactly l
+    counts = [64, 32, 16, 8, 4, 2, 1, 1]
+    lens = oracle.huffman_lengths(counts)
+    assert list(lens) == [1, 2, 3, 4, 5, 6, 7, 7]
+    total = sum(counts)
+    entropy = -sum(c / total * np.log2(c / total) for c in counts)
+    assert abs(sum(c * l for c, l in zip(counts, lens)) / total - entropy) < 1e-12
+    lens2 = oracle.limited_lengths(counts, 12)
+    assert list(lens2) == [1, 2, 3, 4, 5, 6, 7, 7]
+    # 16 equiprobable symbols: all lengths 4
+    assert list(oracle.huffman_lengths([5] * 16)) == [4] * 16
+    assert list(oracle.limited_lengths([5] * 16, 12)) == [4] * 16
+
+
+def test_huffman_bruteforce_small_alphabets(oracle):
+    rng = np.random.default_rng(3)
+    for n in (2, 3, 4, 5, 6):
+        for _ in range(12):
+            counts = [int(v) for v in rng.integers(1, 60, size=n)]
+            best = _brute_best_cost(counts, n)  # n-1 is the longest useful length
+            lens = oracle.huffman_lengths(counts)
+            assert _kraft(lens) == 1
+            assert sum(c * int(l) for c, l in zip(counts, lens)) == best
+            lens = oracle.limited_lengths(counts, 12)
+            assert _kraft(lens) == 1
+            assert sum(c * int(l) for c, l in zip(counts, lens)) == best
+
+
+def test_length_limit_bruteforce(oracle):
+    rng = np.random.default_rng(4)
+    for n, max_len in ((4, 2), (5, 3), (6, 3), (6, 4), (5, 4)):
+        for trial in range(10):
+            counts = [int(v) for v in (rng.integers(1, 8, size=n) ** (3 if trial % 2 else 1))]
+            best = _brute_best_cost(counts, max_len)
+            lens = oracle.limited_lengths(counts, max_len)
+            assert max(lens) <= max_len
+            assert _kraft(lens) == 1
+            assert sum(c * int(l) for c, l in zip(counts, lens)) == best, (counts, max_len, lens)
+
+
+def test_length_limit_skewed_16(oracle):
+    # a geometric distribution forces plain Huffman beyond 12 bits; the limited code must stay within 12,
+    # remain complete, and cost no less than the unlimited optimum
+    counts = [3 ** k for k in range(16)]
+    free = oracle.huffman_lengths(counts)
+    lim = oracle.limited_lengths(counts, 12)
+    assert max(free) == 15 and max(lim) == 12
+    assert _kraft(lim) == 1 and _kraft(free) == 1
+    assert sum(c * int(l) for c, l in zip(counts, lim)) >= sum(c * int(l) for c, l in zip(counts, free))
+    # with a loose limit the two costs agree
+    loose = oracle.limited_lengths(counts, 15)
+    assert sum(c * int(l) for c, l in zip(counts, loose)) == sum(c * int(l) for c, l in zip(counts, free))
+    with pytest.raises(ValueError):
+        oracle.limited_lengths([1] * 16, 3)
+
+
+def test_canonical_codes_properties(oracle):
+    rng = np.random.default_rng(9)
+    for _ in range(50):
+        counts = rng.integers(1, 5000, size=16) ** rng.integers(1, 3)
+        lens = oracle.limited_lengths(counts, 12)
+        codes = oracle.canonical_codes(lens)
+        assert list(codes) == py_canonical([int(l) for l in lens])
+        order = sorted(range(16), key=lambda k: (lens[k], k))
+        assert codes[order[0]] == 0
+        strs = [format(int(codes[k]), "b").zfill(int(lens[k])) for k in range(16)]
+        for a in range(16):
+            for b in range(16):
+                if a != b:
+                    assert not strs[b].startswith(strs[a])
+        # left-aligned code values increase in canonical order
+        left = [int(codes[k]) << (12 - int(lens[k])) for k in order]
+        assert left == sorted(left) and len(set(left)) == 16
+        # the last code is all ones (complete code)
+        assert strs[order[-1]] == "1" * int(lens[order[-1]])
+
+
+def test_verify_model_catches_each_violation(oracle):
+    cent = np.tile(np.linspace(-1, 1, 16).astype(np.float16), (2, 1))
+    lens = np.full((2, 16), 4, np.uint8)
+    assert oracle.verify_model(cent.view(np.uint16), lens) == 0
+    bad = cent.copy(); bad[1, 3] = np.float16(np.inf)
+    assert oracle.verify_model(bad.view(np.uint16), lens) == 2
+    bad = cent.copy(); bad[1, 15] = np.float16(1.5)
+    assert oracle.verify_model(bad.view(np.uint16), lens) == 3
+    bad = cent.copy(); bad[0, 5], bad[0, 6] = cent[0, 6], cent[0, 5]
+    assert oracle.verify_model(bad.view(np.uint16), lens) == 4
+    l2 = lens.copy(); l2[0, 0] = 13
+    assert oracle.verify_model(cent.view(np.uint16), l2) == 5
+    l2 = lens.copy(); l2[0, 0] = 3
+    assert oracle.verify_model(cent.view(np.uint16), l2) == 6  # Kraft sum > 1
+    l2 = lens.copy(); l2[1, 0] = 5
+    assert oracle.verify_model(cent.view(np.uint16), l2) == 6  # Kraft sum < 1
+
+
+# --------------------------------------------------------------------------------------------
+# encoder: brute force on tiny inputs, in exact rational arithmetic
+def _hand_model():
+    pats = np.array([
+        np.linspace(-1, 1, 16),
+        np.sign(np.linspace(-1, 1, 16)) * np.linspace(-1, 1, 16) ** 2,
+        np.concatenate([np.linspace(-1, -0.05, 4), np.linspace(-0.03, 0.03, 8), np.linspace(0.05, 1, 4)]),
+        np.linspace(-1, 1, 16) ** 3,
+    ]).astype(np.float16)
+    return np.sort(pats, axis=1)
+
+
+def _brute_group(cent_u16, x_u16):
+    S = cent_u16.shape[0]
+    s = max(int(v) & 0x7FFF for v in x_u16)
+    best = None
+    for p in range(S):
+        r = [half_to_fraction(round_fraction_to_half(half_to_fraction(int(c)) * half_to_fraction(s))) for c in cent_u16[p]]
+        total = Fraction(0)
+        idx = []
+        for v in x_u16:
+            fv = half_to_fraction(int(v))
+            d = [abs(fv - rk) for rk in r]
+            k = min(range(16), key=lambda j: (d[j], j))
+            idx.append(k)
+            total += d[k] ** 2
+        if best is None or total < best[0]:
+            best = (total, p, idx)
+    return s, best[1], best[2], best[0]
+
+
+def test_quantize_group_bruteforce(oracle):
+    cent = _hand_model().view(np.uint16)
+    rng = np.random.default_rng(21)
+    for trial in range(12):
+        kind = trial % 4
+        if kind == 0:
+            x = rng.normal(0, 0.02, 128)
+        elif kind == 1:
+            x = rng.normal(0, 0.02, 128); x[rng.integers(128)] *= 15
+        elif kind == 2:
+            x = rng.uniform(-3, 3, 128)
+        else:
+            x = rng.normal(0, 1, 128) ** 3
+        x16 = x.astype(np.float16).view(np.uint16)
+        s, p, idx, sse = oracle.quantize_group(cent, x16)
+        bs, bp, bidx, btotal = _brute_group(cent, x16)
+        assert s == bs
+        # exact totals of all patterns are well separated relative to fp32 rounding, so the argmin agrees
+        assert p == bp
+        assert list(idx) == bidx
+        assert abs(float(sse[p]) - float(btotal)) <= 1e-5 * float(btotal) + 1e-30
+
+
+def test_quantize_ties_go_to_lowest_index(oracle):
+    # two identical patterns: pattern 0 must win; duplicate centroids: the lower index must win;
+    # a value exactly half-way between two reconstructed values goes to the lower index
+    base = np.array([-1, -0.75, -0.5, -0.25, -0.25, 0, 0, 0.125, 0.25, 0.375, 0.5, 0.5, 0.625, 0.75, 0.875, 1], np.float16)
+    cent = np.stack([base, base]).view(np.uint16)
+    x = np.zeros(128, np.float16)
+    x[0] = 1.0        # scale 1 -> reconstructed values = centroids
+    x[1] = -0.25      # duplicate centroid 3/4 -> 3
+    x[2] = 0.0        # duplicate centroid 5/6 -> 5
+    x[3] = 0.5        # duplicate 10/11 -> 10
+    x[4] = 0.0625     # half-way between 0 (idx 5,6) and 0.125 (idx 7) -> 5
+    x[5] = -0.625     # half-way between -0.75 (1) and -0.5 (2) -> 1
+    x[6] = 0.9375     # half-way between 0.875 (14) and 1 (15) -> 14
+    s, p, idx, sse = oracle.quantize_group(cent, x.view(np.uint16))
+    assert s == 0x3C00 and p == 0
+    assert list(idx[:7]) == [15, 3, 5, 10, 5, 1, 14]
+    assert sse[0] == sse[1]
+    # all-zero group: scale 0, every reconstructed value is zero, index 0, pattern 0
+    s, p, idx, sse = oracle.quantize_group(cent, np.zeros(128, np.uint16))
+    assert s == 0 and p == 0 and not idx.any()
+
+
+def test_sse_tree_order(oracle):
+    """The per-pattern error sum follows the balanced pairwise tree in fp32 (not a left-to-right sum)."""
+    cent = np.zeros((1, 16), np.float16)  # all reconstructed values 0 -> e_i = x_i^2 exactly
+    rng = np.random.default_rng(2)
+    x = (rng.normal(0, 1, 128) * 10.0 ** rng.uniform(-3, 1, 128)).astype(np.float16)
+    _, _, _, sse = oracle.quantize_group(cent.view(np.uint16), x.view(np.uint16))
+    e = x.astype(np.float32) ** 2
+    t = e.copy()
+    while t.size > 1:
+        t = (t[0::2] + t[1::2]).astype(np.float32)
+    assert np.float32(sse[0]) == t[0]
+    exact = sum(Fraction(float(v)) ** 2 for v in x)
+    assert abs(float(sse[0]) - float(exact)) < 1e-5 * float(exact)
+
+
+def test_uniform_special_case_is_absmax_int4(oracle):
+    """S = 1, equidistant centroids, all code lengths 4: Ecco degenerates to symmetric absmax 4-bit
+    round-to-nearest, and the Huffman payload is the raw payload with every nibble bit-reversed."""
+    cent = (-1 + 2 * np.arange(16) / 15.0).astype(np.float16)[None, :]
+    lens = np.full((1, 16), 4, np.uint8)
+    rng = np.random.default_rng(8)
+    x = rng.normal(0, 0.02, (40, 128)).astype(np.float16)
+    blocks, meta = oracle.encode(cent.view(np.uint16), lens, x.view(np.uint16))
+    assert not ((meta >> 22) & 1).any()  # 128 x 4 = 512 bits: fits exactly
+    idx, used = oracle.decode_indices(lens, 1, blocks, meta)
+    assert (used == 512).all()
+    s = np.abs(x.astype(np.float64)).max(axis=1, keepdims=True)
+    t = (x.astype(np.float64) / s + 1) * 7.5
+    near_tie = np.abs(t - np.floor(t) - 0.5) < 0.02  # fp16 rounding of centroids moves the thresholds slightly
+    rtn = np.clip(np.floor(t + 0.5), 0, 15).astype(np.uint8)
+    assert np.array_equal(idx[~near_tie], rtn[~near_tie])
+    assert np.array_equal(meta & 0xFFFF, np.abs(x).max(axis=1).view(np.uint16))
+    # payload: stream nibble i holds the 4-bit canonical code (= index) first bit first
+    for g in range(40):
+        bits = stream_bits(blocks[g]).reshape(128, 4)
+        val = bits[:, 0] * 8 + bits[:, 1] * 4 + bits[:, 2] * 2 + bits[:, 3]
+        assert np.array_equal(val, idx[g])
+    # the same indices in raw mode are a plain little-endian nibble array
+    raw_meta = meta | (1 << 22)
+    packed = (idx[:, 0::2] | (idx[:, 1::2] << 4)).astype(np.uint8)
+    idx2, used2 = oracle.decode_indices(lens, 1, packed, raw_meta)
+    assert np.array_equal(idx2, idx) and (used2 == 512).all()
+
+
+# --------------------------------------------------------------------------------------------
+# encode -> decode
+@pytest.fixture(scope="module")
+def tiny(oracle):
+    from paper_2505_06901_amd import workloads as W
+    w = W.config_weight("tiny")
+    cent, lens, hist, nfit = oracle.fit(w.view(np.uint16), 16, 12, 0)
+    blocks, meta = oracle.encode(cent, lens, w.view(np.uint16))
+    return dict(w=w, cent=cent, lens=lens, hist=hist, nfit=nfit, blocks=blocks, meta=meta)
+
+
+def test_fit_invariants(oracle, tiny):
+    cent, lens, hist = tiny["cent"], tiny["lens"], tiny["hist"]
+    assert tiny["nfit"] == 512
+    assert oracle.verify_model(cent, lens) == 0
+    c = cent.view(np.float16).astype(np.float32)
+    assert (np.diff(c, axis=1) >= 0).all() and np.abs(c).max() <= 1.0
+    assert hist.sum() == 512 * 128
+    assert ((hist.sum(axis=1) % 128) == 0).all()
+    for p in range(16):
+        assert _kraft(lens[p]) == 1
+        if hist[p].sum() == 0:
+            assert (lens[p] == 4).all()
+        else:  # lengths are optimal for the smoothed counts: same cost as plain Huffman when that fits in 12 bits
+            free = oracle.huffman_lengths(hist[p] + 1)
+            if free.max() <= 12:
+                assert ((hist[p] + 1) * lens[p]).sum() == ((hist[p] + 1) * free).sum()
+    # the fit is a pure function of (data, S, seed)
+    cent2, lens2, _, _ = oracle.fit(tiny["w"].view(np.uint16), 16, 12, 0)
+    assert np.array_equal(cent, cent2) and np.array_equal(lens, lens2)
+
+
+def test_roundtrip_indices_and_padding(oracle, tiny):
+    w, cent, lens, blocks, meta = (tiny[k] for k in ("w", "cent", "lens", "blocks", "meta"))
+    x = w.view(np.uint16).reshape(-1, 128)
+    idx, used = oracle.decode_indices(lens, 16, blocks, meta)
+    codes = [py_canonical([int(l) for l in lens[p]]) for p in range(16)]
+    n_raw = 0
+    for g in range(x.shape[0]):
+        s, p, qidx, _ = oracle.quantize_group(cent, x[g])
+        assert (meta[g] & 0xFFFF) == s and ((meta[g] >> 16) & 63) == p and (meta[g] >> 23) == 0
+        assert np.array_equal(idx[g], qidx)           # index-level bit-exact round trip
+        total = int(lens[p][qidx].sum())
+        bits = stream_bits(blocks[g])
+        if (meta[g] >> 22) & 1:
+            n_raw += 1
+            assert total > 512                        # raw only on overflow
+            packed = (qidx[0::2] | (qidx[1::2] << 4)).astype(np.uint8)
+            assert np.array_equal(blocks[g], packed)  # textbook nibble packing
+            assert used[g] == 512
+        else:
+            assert total <= 512 and used[g] == total
+            assert not bits[total:].any()             # padding is zero
+            want = "".join(format(codes[p][k], "b").zfill(int(lens[p][k])) for k in qidx)
+            assert "".join(map(str, bits[:total])) == want
+    assert 0 < n_raw < x.shape[0]
+    # determinism
+    b2, m2 = oracle.encode(cent, lens, w.view(np.uint16))
+    assert np.array_equal(b2, blocks) and np.array_equal(m2, meta)
+
+
+def test_decode_values_and_error(oracle, tiny):
+    w, cent, lens, blocks, meta = (tiny[k] for k in ("w", "cent", "lens", "blocks", "meta"))
+    dec = oracle.decode(cent, lens, blocks, meta)
+    idx, _ = oracle.decode_indices(lens, 16, blocks, meta)
+    p = (meta >> 16) & 63
+    c = cent.view(np.float16).astype(np.float32)[p[:, None], idx]
+    s = (meta & 0xFFFF).astype(np.uint16).view(np.float16).astype(np.float32)[:, None]
+    assert np.array_equal(dec, (c * s).astype(np.float16).view(np.uint16))
+    d = dec.view(np.float16).astype(np.float64).reshape(w.shape)
+    rel = np.linalg.norm(d - w.astype(np.float64)) / np.linalg.norm(w.astype(np.float64))
+    assert rel < 0.15  # 16 non-uniform levels per group: about 10 % relative error on Gaussian data
+    # the group's largest element is always representable as +-scale only if a centroid is +-1; at least it never overshoots
+    assert (np.abs(d.reshape(-1, 128)).max(axis=1) <= s[:, 0] + 1e-12).all()
+
+
+def test_corrupt_input_is_defined(oracle, tiny):
+    rng = np.random.default_rng(17)
+    blocks = rng.integers(0, 256, size=(300, 64), dtype=np.uint8)
+    meta = rng.integers(0, 2**32, size=300, dtype=np.uint64).astype(np.uint32)
+    meta &= np.uint32(0xFF7F7BFF)  # keep the scale finite (clear one exponent bit); everything else arbitrary
+    idx, used = oracle.decode_indices(tiny["lens"], 16, blocks, meta)
+    assert idx.max() < 16
+    idx2, _ = oracle.decode_indices(tiny["lens"], 16, blocks, meta)
+    assert np.array_equal(idx, idx2)
+    # pattern ids above S-1 behave like S-1
+    m2 = (meta & ~np.uint32(0x3F << 16)) | (np.minimum((meta >> 16) & 63, 15) << 16)
+    idx3, _ = oracle.decode_indices(tiny["lens"], 16, blocks, m2)
+    assert np.array_equal(idx, idx3)
+    oracle.decode(tiny["cent"], tiny["lens"], blocks, meta)
+
+
+# --------------------------------------------------------------------------------------------
+# k-means
+def _lloyd_max_gaussian(n_levels, iters=3000):
+    """Lloyd-Max quantiser of N(0,1) from closed-form conditional means (independent of the oracle)."""
+    from scipy.stats import norm
+    lev = np.linspace(-2.5, 2.5, n_levels)
+    for _ in range(iters):
+        t = np.concatenate([[-np.inf], (lev[1:] + lev[:-1]) / 2, [np.inf]])
+        num = norm.pdf(t[:-1]) - norm.pdf(t[1:])
+        den = norm.cdf(t[1:]) - norm.cdf(t[:-1])
+        lev = num / den
+    t = np.concatenate([[-np.inf], (lev[1:] + lev[:-1]) / 2, [np.inf]])
+    p = norm.cdf(t[1:]) - norm.cdf(t[:-1])
+    mse = 1.0 - np.sum(p * lev ** 2)
+    return lev, mse, -(p * np.log2(p)).sum()
+
+
+def test_kmeans_monotone_and_lloyd_max(oracle):
+    from paper_2505_06901_amd import workloads as W
+    v = W.normal(77, 0, 0, 200000).astype(np.float32)
+    cent, obj, it = oracle.kmeans_1d(v, 16, max_iter=200)
+    assert (np.diff(obj) <= 1e-9 * obj[0]).all()          # Lloyd never increases the objective
+    assert (np.diff(cent) > 0).all()
+    lev, mse, ent = _lloyd_max_gaussian(16)
+    assert abs(mse - 0.009497) < 2e-5 and abs(ent - 3.765) < 2e-3  # Max (1960), 16 levels
+    assert np.abs(cent - lev).max() < 0.06
+    assert abs(obj[-1] / v.size - mse) < 0.03 * mse
+    # small case solved by hand: two tight clumps, K = 2 -> the clump means
+    cent, obj, it = oracle.kmeans_1d(np.array([0.0, 0.1, 0.2, 10.0, 10.1, 10.2], np.float32), 2, 25)
+    assert np.allclose(cent, [0.1, 10.1], atol=1e-6)
+
+
+# --------------------------------------------------------------------------------------------
+# consumers
+def test_gemv_unit_vectors_and_ones(oracle, tiny):
+    cent, lens, blocks, meta = (tiny[k] for k in ("cent", "lens", "blocks", "meta"))
+    rows, cols = 64, 1024
+    dec = oracle.decode(cent, lens, blocks, meta).view(np.float16).reshape(rows, cols).astype(np.float64)
+    for j in (0, 1, 127, 128, 555, 1023):
+        x = np.zeros((1, cols), np.float16); x[0, j] = 1.0
+        y = oracle.gemv(cent, lens, blocks, meta, rows, cols, x.view(np.uint16))
+        assert np.array_equal(y[0], dec[:, j])       # exact: one non-zero term
+    x = np.ones((1, cols), np.float16)
+    y = oracle.gemv(cent, lens, blocks, meta, rows, cols, x.view(np.uint16))
+    assert np.allclose(y[0], dec.sum(axis=1), rtol=1e-13, atol=1e-15)
+    from paper_2505_06901_amd import workloads as W
+    xb = W.activation(3, cols, 5)
+    y = oracle.gemv(cent, lens, blocks, meta, rows, cols, xb.view(np.uint16))
+    assert np.allclose(y, xb.astype(np.float64) @ dec.T, rtol=1e-12, atol=1e-14)
+
+
+def test_kv_append_and_attend_special_cases(oracle, tiny):
+    from paper_2505_06901_amd import workloads as W
+    cent, lens = tiny["cent"], tiny["lens"]
+    B, H, T = 2, 3, 6
+    k, v = W.kv_cache(B, H, T, 128, seed=9)
+    kb = np.zeros((B, H, T, 64), np.uint8); km = np.zeros((B, H, T), np.uint32)
+    vb = np.zeros_like(kb); vm = np.zeros_like(km)
+    for t in range(T):
+        seq = np.full(B, t, np.int32)
+        oracle.kv_append(cent, lens, cent, lens, k[:, :, t].view(np.uint16), v[:, :, t].view(np.uint16),
+                         kb, km, vb, vm, seq, B, H, T)
+    # appended blocks equal a bulk encode of the same groups
+    b2, m2 = oracle.encode(cent, lens, k.view(np.uint16))
+    assert np.array_equal(kb.reshape(-1, 64), b2) and np.array_equal(km.reshape(-1), m2)
+    # a full cache (seq_len == T_max) writes nothing
+    before = kb.copy()
+    oracle.kv_append(cent, lens, cent, lens, k[:, :, 0].view(np.uint16), v[:, :, 0].view(np.uint16),
+                     kb, km, vb, vm, np.full(B, T, np.int32), B, H, T)
+    assert np.array_equal(before, kb)
+    vdec = oracle.decode(cent, lens, vb, vm).view(np.float16).astype(np.float64).reshape(B, H, T, 128)
+    kdec = oracle.decode(cent, lens, kb, km).view(np.float16).astype(np.float64).reshape(B, H, T, 128)
+    q = W.activation(B * H, 128, 3).reshape(B, H, 128)
+    # one token: softmax over a single score is 1 -> output is the decoded V_0
+    o = oracle.kv_attend(cent, lens, cent, lens, q.view(np.uint16), kb, km, vb, vm, np.full(B, 1, np.int32), B, H, T)
+    assert np.array_equal(o, vdec[:, :, 0])
+    # q = 0: uniform weights -> mean of the decoded V over the valid tokens
+    o = oracle.kv_attend(cent, lens, cent, lens, np.zeros((B, H, 128), np.uint16), kb, km, vb, vm,
+                         np.array([T, 4], np.int32), B, H, T)
+    assert np.allclose(o[0], vdec[0].mean(axis=1), rtol=1e-13, atol=1e-15)
+    assert np.allclose(o[1], vdec[1, :, :4].mean(axis=1), rtol=1e-13, atol=1e-15)
+    # general case against numpy softmax attention on the decoded tensors
+    o = oracle.kv_attend(cent, lens, cent, lens, q.view(np.uint16), kb, km, vb, vm, np.full(B, T, np.int32), B, H, T)
+    sc = np.einsum("bhd,bhtd->bht", q.astype(np.float64), kdec) / np.sqrt(128.0)
+    pr = np.exp(sc - sc.max(axis=-1, keepdims=True)); pr /= pr.sum(axis=-1, keepdims=True)
+    assert np.allclose(o, np.einsum("bht,bhtd->bhd", pr, vdec), rtol=1e-12, atol=1e-14)
+    # seq_len 0 gives zeros
+    o = oracle.kv_attend(cent, lens, cent, lens, q.view(np.uint16), kb, km, vb, vm, np.zeros(B, np.int32), B, H, T)
+    assert not o.any()
