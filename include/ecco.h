@@ -1,0 +1,158 @@
+/* libecco -- Ecco block codec for MI355X (gfx950): C ABI.
+ *
+ * Ecco (arxiv 2505.06901) stores every group of 128 FP16 weight or KV values in a fixed 64-byte
+ * block: the values are normalised by the group's absolute maximum, quantised to 16 levels against
+ * one of S shared, pre-defined k-means centroid patterns (the pattern of minimum squared error),
+ * and the 4-bit level indices are Huffman coded (Section 3.1 "Compression Target", Section 3.2
+ * "Model Compression").  This library holds the data-parallel hot path: block decode to FP16
+ * (Section 4.2 "Decompressor Design"), decode fused into a batch-1..16 GEMV and into single-query
+ * attention (the consumers of Section 2.1), and the per-group encoder (Section 4.3 "Compressor
+ * Design") for bulk tensors and for appended KV tokens.  The pattern / codebook fit runs on the CPU.
+ *
+ * BLOCK FORMAT (the simplified format this build measures; differences from the paper's
+ * self-contained block are listed in the design doc):
+ *   - group  = 128 consecutive FP16 values.  Matrices: row-major, group g = (row, col/128).
+ *   - block  = 64 bytes of payload per group at byte offset 64*g.  The payload is a bit stream;
+ *              stream bit j (0..511) is bit (j & 7) of byte (j >> 3), i.e. bit (j & 31) of the
+ *              little-endian 32-bit word (j >> 5).
+ *       Huffman mode: the canonical codes of values 0..127 in order, each written first code
+ *              bit (most significant) first, starting at stream bit 0; remaining bits are 0.
+ *       Raw mode (used when the codes need more than 512 bits): value i's 4-bit index sits in
+ *              stream bits 4i..4i+3, least significant bit first (a little-endian nibble array).
+ *   - meta   = one uint32 per group: bits 15:0 scale (FP16 bit pattern of max|x|, sign 0),
+ *              bits 21:16 pattern id, bit 22 raw flag, bits 31:23 zero.
+ *   - model  = S patterns x 16 FP16 centroids in [-1,1], ascending, plus S x 16 code lengths in
+ *              1..12 with Kraft sum exactly 1.  Codes are canonical: symbols ordered by
+ *              (length, symbol); first code 0; next = (previous + 1) << (length growth).
+ *   - value  = fp16_rn( f32(centroid[pattern][index]) * f32(scale) )   (one rounding).
+ *   Decoders never read outside a block: stream bits >= 512 read as 0; a pattern id >= S is
+ *   treated as S-1.  Any 64 bytes + any meta word therefore decode to something defined.
+ *
+ * CONVENTIONS
+ *   - every function returns an ecco_status (0 = ok, negative = error); nothing throws.
+ *   - "host" / "device" in a parameter comment says where the pointer must point.  The library
+ *     never allocates, frees or keeps caller buffers; device work is enqueued on `stream`
+ *     (a hipStream_t passed as void*, NULL = the default stream) and the call returns without
+ *     synchronising.  Argument errors are detected on the host before anything is launched.
+ *   - FP16 travels as uint16_t bit patterns.
+ */
+#ifndef ECCO_H
+#define ECCO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ECCO_GROUP 128
+#define ECCO_BLOCK_BYTES 64
+#define ECCO_K 16
+#define ECCO_MAX_LEN 12
+#define ECCO_MAX_S 64
+
+typedef struct ecco_model ecco_model; /* opaque; owned by the library; host copy + one device copy */
+
+typedef enum {
+    ECCO_OK = 0,
+    ECCO_EINVAL = -1,  /* null pointer, value out of range, model not on a device */
+    ECCO_ESHAPE = -2,  /* size not a multiple of 128, batch outside 1..16, ... */
+    ECCO_EALIGN = -3,  /* pointer not aligned as documented */
+    ECCO_ENOMEM = -4,
+    ECCO_EFORMAT = -5, /* serialized model fails validation */
+    ECCO_EHIP = -6     /* a HIP runtime call failed */
+} ecco_status;
+
+const char* ecco_strerror(int status);
+
+/* ---- model: fit, (de)serialise, upload ------------------------------------------------------ */
+
+/* Section 3.2, offline steps: partition into groups of 128, normalise by the group maximum,
+ * 16-cluster k-means per group, S-cluster k-means over the sorted per-group centroid vectors
+ * (the shared patterns), quantise with pattern selection, and one length-limited canonical Huffman
+ * codebook per pattern from the pooled index counts.  CPU only, deterministic in (data, S, seed).
+ *   data        host, n_values FP16 bit patterns, all finite; n_values % 128 == 0, n_values > 0
+ *   S           1..64 patterns;  max_code_len 4..12
+ *   out         receives a new model (free with ecco_model_free)
+ * Errors: EINVAL (null, S / max_code_len out of range, non-finite data), ESHAPE (n_values). */
+int ecco_fit_patterns(const uint16_t* data, size_t n_values, int S, int max_code_len,
+                      uint64_t seed, ecco_model** out);
+
+/* Builds a model from explicit tables (host): centroids[S*16] FP16 bits, code_lens[S*16].
+ * Validates as ecco_model_load does.  Errors: EINVAL, EFORMAT. */
+int ecco_model_create(const uint16_t* centroids, const uint8_t* code_lens, int S, ecco_model** out);
+
+/* Serialised model: little-endian { u32 magic 'ECC0', u32 version 1, u32 S, u32 K=16,
+ * S*16 u16 centroids, S*16 u8 code lengths }.  save: buf may be NULL to query *written.
+ * load validates: S range, centroids finite, in [-1,1], ascending; lengths 1..12; Kraft sum 1.
+ * Errors: EINVAL (null / cap too small), EFORMAT (validation). */
+int ecco_model_save(const ecco_model* m, void* buf /*host*/, size_t cap, size_t* written);
+int ecco_model_load(const void* buf /*host*/, size_t len, ecco_model** out);
+
+/* Read-only views of the host tables (valid until ecco_model_free). */
+int ecco_model_S(const ecco_model* m);
+const uint16_t* ecco_model_centroids(const ecco_model* m); /* S*16 */
+const uint8_t* ecco_model_code_lens(const ecco_model* m);  /* S*16 */
+
+/* Uploads the decode / encode tables to `device` (Section 4.2: tensor-level metadata is loaded
+ * once, before any compressed load).  Must precede every GPU call below.  Calling it again for the
+ * same device is a no-op; another device moves the tables.  Errors: EINVAL, EHIP, ENOMEM. */
+int ecco_model_to_device(ecco_model* m, int device);
+void ecco_model_free(ecco_model* m);
+
+/* ---- GPU entry points ------------------------------------------------------------------------ */
+
+/* Section 3.2 step 5 + Section 4.3: per group, scale = max|x|; every pattern's centroids times
+ * scale rounded to FP16; each value to the nearest reconstructed value (lowest index on ties);
+ * squared errors summed per pattern in FP32 by the balanced tree (i, i^1), (.., i^2), ...; pattern
+ * of least sum (lowest id on ties); Huffman pack, or raw mode when the codes exceed 512 bits.
+ *   src     device, n_groups*128 FP16, finite          blocks  device, n_groups*64 bytes, 64-byte aligned
+ *   meta    device, n_groups uint32
+ * Errors: EINVAL (null, model not on device), EALIGN, EHIP.  n_groups == 0 is a no-op (pointers may be null). */
+int ecco_encode(const ecco_model* m, const uint16_t* src, size_t n_groups,
+                void* blocks, uint32_t* meta, void* stream);
+
+/* Section 4.2: pattern retrieval, Huffman decode, centroid x scale.  dst: device, n_groups*128 FP16,
+ * 16-byte aligned.  Same errors as ecco_encode. */
+int ecco_decode(const ecco_model* m, const void* blocks, const uint32_t* meta, size_t n_groups,
+                uint16_t* dst, void* stream);
+
+/* Like ecco_decode but writes the 4-bit indices, one per byte (idx: device, n_groups*128 bytes,
+ * 16-byte aligned).  For index-level parity checks. */
+int ecco_decode_indices(const ecco_model* m, const void* blocks, const uint32_t* meta, size_t n_groups,
+                        uint8_t* idx, void* stream);
+
+/* Decode fused into the consuming GEMV (Section 2.1: decode-phase projections are memory-bound
+ * matrix-vector products); the FP16 weights never reach HBM.
+ *   W = rows x cols, stored as rows*(cols/128) blocks, row-major;   x  device, batch x cols FP16
+ *   y  device, batch x rows FP32:  y[b][r] = sum_c W[r][c] * x[b][c]  (FP32 accumulation)
+ *   batch 1..16;  cols % 128 == 0;  cols <= 65536.
+ * Errors: EINVAL, ESHAPE (cols, batch, rows <= 0), EALIGN, EHIP. */
+int ecco_decode_gemv(const ecco_model* m, const void* blocks, const uint32_t* meta,
+                     int rows, int cols, const uint16_t* x, int batch, float* y, void* stream);
+
+/* Section 3.2 "KV Cache Compression", online part: encodes one new token per sequence.
+ *   k_new, v_new   device, [B][H][128] FP16
+ *   k_blocks ...   device caches, [B][H][T_max] blocks / meta words (block (b,h,t) at index (b*H+h)*T_max+t)
+ *   seq_len        device, [B] int32: write position of each sequence; a position outside
+ *                  0..T_max-1 writes nothing.  The caller advances seq_len afterwards.
+ * Pattern selection is the full minimum-squared-error search of ecco_encode (mk for K, mv for V).
+ * Errors: EINVAL, ESHAPE (B, H, T_max <= 0), EALIGN, EHIP. */
+int ecco_kv_append(const ecco_model* mk, const ecco_model* mv,
+                   const uint16_t* k_new, const uint16_t* v_new,
+                   void* k_blocks, uint32_t* k_meta, void* v_blocks, uint32_t* v_meta,
+                   const int32_t* seq_len, int B, int H, int T_max, void* stream);
+
+/* Single-query attention over the compressed caches (Section 2.1): per (b,h), scores
+ * q.K_t / sqrt(128) for t < seq_len[b], softmax, out = sum_t p_t V_t.  No mask beyond seq_len.
+ *   q  device [B][H][128] FP16;  out  device [B][H][128] FP32 (zeros where seq_len[b] <= 0).
+ * seq_len values above T_max are clamped to T_max.  Errors as ecco_kv_append. */
+int ecco_kv_attend(const ecco_model* mk, const ecco_model* mv, const uint16_t* q,
+                   const void* k_blocks, const uint32_t* k_meta, const void* v_blocks, const uint32_t* v_meta,
+                   const int32_t* seq_len, int B, int H, int T_max, float* out, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

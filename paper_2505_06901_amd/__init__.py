@@ -1,0 +1,8 @@
+"""Ecco block codec for MI355X: HIP kernels behind a C ABI (include/ecco.h) and their ctypes binding.
+
+`workloads` (seeded synthetic inputs) is importable on its own; the binding loads libecco.so lazily
+and fails loudly if it has not been built.
+"""
+from .binding import (EccoError, Model, ecco_decode, ecco_decode_gemv, ecco_decode_indices, ecco_encode,  # noqa: F401
+                      ecco_fit_patterns, ecco_kv_append, ecco_kv_attend, ecco_model_create, ecco_model_load,
+                      ecco_model_save, ecco_model_to_device, strerror)

@@ -16,6 +16,8 @@ scale structure, values without it.
 """
 from __future__ import annotations
 
+import os
+
 import numpy as np
 
 _GOLDEN = np.uint64(0x9E3779B97F4A7C15)
@@ -71,12 +73,23 @@ def weight_matrix(rows: int, cols: int, sigma: float, outlier_frac: float, outli
     n = rows * cols
     base = row_start * cols
     out = np.empty(n, dtype=np.float16)
-    for s, c in _chunks(n):
+
+    def fill(sc):
+        s, c = sc
         z = normal(seed, 0, base + s, c) * sigma
         if outlier_frac > 0.0:
             mask = uniform01(seed, 7, base + s, c) < outlier_frac
             z = np.where(mask, z * outlier_mult, z)
         out[s:s + c] = z.astype(np.float16)
+
+    chunks = list(_chunks(n, 1 << 20))
+    if len(chunks) > 1:  # numpy releases the GIL inside its loops: chunks run on a few threads
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as ex:
+            list(ex.map(fill, chunks))
+    else:
+        for sc in chunks:
+            fill(sc)
     return out.reshape(rows, cols)
 
 

@@ -1,0 +1,323 @@
+"""Parity of the HIP path against the CPU oracle, through the C ABI, on one MI355X.
+
+Bars: encoded blocks / meta words and decoded indices bit-exact; dequantised FP16 bit-exact;
+GEMV and attention outputs within rel-L2 1e-3 of the double-precision oracle.
+"""
+from __future__ import annotations
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+import paper_2505_06901_amd as E  # noqa: E402
+from paper_2505_06901_amd import workloads as W  # noqa: E402
+
+REL_L2 = 1e-3
+
+
+@pytest.fixture(scope="module")
+def dev():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    return torch.device("cuda:0")
+
+
+def t16(a, dev):
+    return torch.from_numpy(np.ascontiguousarray(a).view(np.float16)).to(dev)
+
+
+def tu8(a, dev):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.uint8)).to(dev)
+
+
+def ti32(a, dev):
+    return torch.from_numpy(np.ascontiguousarray(a).view(np.int32)).to(dev)
+
+
+def rel_l2(got, want):
+    got = np.asarray(got, np.float64)
+    want = np.asarray(want, np.float64)
+    return np.linalg.norm(got - want) / max(np.linalg.norm(want), 1e-300)
+
+
+def np_blocks(t):
+    return t.cpu().numpy().reshape(-1, 64)
+
+
+def np_meta(t):
+    return t.cpu().numpy().view(np.uint32).reshape(-1)
+
+
+# ---------------------------------------------------------------------------------------------------
+@pytest.fixture(scope="module")
+def tiny(dev, oracle):
+    w = W.config_weight("tiny")
+    m = E.ecco_model_to_device(E.ecco_fit_patterns(w, 16, 12, 0), 0)
+    ob, om = oracle.encode(m.centroids, m.code_lens, w.view(np.uint16))
+    return dict(w=w, m=m, ob=ob, om=om)
+
+
+def test_tiny_encode_bit_exact(dev, oracle, tiny):
+    blocks, meta = E.ecco_encode(tiny["m"], t16(tiny["w"], dev))
+    torch.cuda.synchronize()
+    assert np.array_equal(np_meta(meta), tiny["om"])
+    assert np.array_equal(np_blocks(blocks), tiny["ob"])
+    # determinism: a second run gives the same bytes
+    b2, m2 = E.ecco_encode(tiny["m"], t16(tiny["w"], dev))
+    assert torch.equal(b2, blocks) and torch.equal(m2, meta)
+
+
+def test_tiny_decode_bit_exact(dev, oracle, tiny):
+    m = tiny["m"]
+    blocks, meta = tu8(tiny["ob"], dev), ti32(tiny["om"], dev)
+    idx = E.ecco_decode_indices(m, blocks, meta).cpu().numpy()
+    oidx, _ = oracle.decode_indices(m.code_lens, m.S, tiny["ob"], tiny["om"])
+    assert np.array_equal(idx, oidx)
+    dec = E.ecco_decode(m, blocks, meta).cpu().numpy().view(np.uint16)
+    assert np.array_equal(dec, oracle.decode(m.centroids, m.code_lens, tiny["ob"], tiny["om"]))
+
+
+@pytest.mark.parametrize("batch", [1, 2, 5, 8, 16])
+def test_tiny_gemv(dev, oracle, tiny, batch):
+    m = tiny["m"]
+    x = W.activation(batch, 1024, 100)
+    y = E.ecco_decode_gemv(m, tu8(tiny["ob"], dev), ti32(tiny["om"], dev), 64, 1024, t16(x, dev)).cpu().numpy()
+    want = oracle.gemv(m.centroids, m.code_lens, tiny["ob"], tiny["om"], 64, 1024, x.view(np.uint16))
+    assert y.shape == want.shape
+    assert rel_l2(y, want) <= REL_L2
+    for b in range(batch):
+        assert rel_l2(y[b], want[b]) <= REL_L2
+
+
+def test_gemv_unit_vector_ties_to_decode(dev, oracle, tiny):
+    m = tiny["m"]
+    dec = oracle.decode(m.centroids, m.code_lens, tiny["ob"], tiny["om"]).view(np.float16).reshape(64, 1024)
+    for j in (0, 127, 128, 640, 1023):
+        x = np.zeros((1, 1024), np.float16); x[0, j] = 1
+        y = E.ecco_decode_gemv(m, tu8(tiny["ob"], dev), ti32(tiny["om"], dev), 64, 1024, t16(x, dev)).cpu().numpy()
+        assert np.allclose(y[0], dec[:, j].astype(np.float64), rtol=2e-3, atol=1e-7)
+
+
+# ---------------------------------------------------------------------------------------------------
+def _skewed_model(oracle, S, seed):
+    """Hand-built model whose codebooks reach 12 bits (exercises codes longer than the short table)."""
+    rng = np.random.default_rng(seed)
+    cent = np.sort(rng.uniform(-1, 1, (S, 16)), axis=1)
+    cent[:, 0], cent[:, 15] = -1, 1
+    lens = np.zeros((S, 16), np.uint8)
+    probs = np.zeros((S, 16))
+    for p in range(S):
+        base = 2.2 + 1.2 * rng.random()
+        counts = np.array([int(base ** k) + 1 for k in range(16)], np.uint64)[rng.permutation(16)]
+        lens[p] = oracle.limited_lengths(counts, 12)
+        probs[p] = counts / counts.sum()
+    return cent.astype(np.float16), lens, probs
+
+
+def _skewed_data(cent, probs, n_groups, seed):
+    rng = np.random.default_rng(seed)
+    S = cent.shape[0]
+    p = rng.integers(0, S, n_groups)
+    x = np.zeros((n_groups, 128), np.float64)
+    for g in range(n_groups):
+        idx = rng.choice(16, 128, p=probs[p[g]])
+        idx[rng.integers(128)] = 15  # the +1 centroid is present, so the scale is what we say
+        x[g] = cent[p[g]].astype(np.float64)[idx] * (0.01 + rng.random()) * (1 + 0.002 * rng.standard_normal(128))
+    return x.astype(np.float16)
+
+
+def test_long_codes_all_paths(dev, oracle):
+    S = 7
+    cent, lens, probs = _skewed_model(oracle, S, 1)
+    assert lens.max() == 12
+    m = E.ecco_model_to_device(E.ecco_model_create(cent, lens), 0)
+    n = 256 * 3 + 77  # several workgroups and a ragged tail
+    x = _skewed_data(cent, probs, n, 2)
+    ob, om = oracle.encode(cent.view(np.uint16), lens, x.view(np.uint16))
+    oidx, used = oracle.decode_indices(lens, S, ob, om)
+    long_used = (lens[(om >> 16) & 63][np.arange(n)[:, None], oidx] > 8) & (((om >> 22) & 1) == 0)[:, None]
+    assert long_used.sum() > 200  # codes beyond the 8-bit table really occur in Huffman-mode blocks
+    blocks, meta = E.ecco_encode(m, t16(x, dev))
+    assert np.array_equal(np_meta(meta), om) and np.array_equal(np_blocks(blocks), ob)
+    assert np.array_equal(E.ecco_decode_indices(m, blocks, meta).cpu().numpy(), oidx)
+    assert np.array_equal(E.ecco_decode(m, blocks, meta).cpu().numpy().view(np.uint16),
+                          oracle.decode(cent.view(np.uint16), lens, ob, om))
+    # gemv over the same blocks viewed as a 7-column-group matrix (ragged: 121 rows)
+    rows, cols = n // 7, 7 * 128
+    xb = W.activation(3, cols, 9)
+    y = E.ecco_decode_gemv(m, blocks[: rows * 7], meta[: rows * 7], rows, cols, t16(xb, dev)).cpu().numpy()
+    want = oracle.gemv(cent.view(np.uint16), lens, ob[: rows * 7], om[: rows * 7], rows, cols, xb.view(np.uint16))
+    assert rel_l2(y, want) <= REL_L2
+
+
+def test_corrupt_blocks_decode_like_oracle(dev, oracle):
+    S = 5
+    cent, lens, _ = _skewed_model(oracle, S, 3)
+    m = E.ecco_model_to_device(E.ecco_model_create(cent, lens), 0)
+    rng = np.random.default_rng(4)
+    n = 1000
+    blocks = rng.integers(0, 256, (n, 64), dtype=np.uint8)
+    blocks[::7] = 0xFF
+    blocks[1::7] = 0
+    meta = rng.integers(0, 2**32, n, dtype=np.uint64).astype(np.uint32) & np.uint32(0xFFFFBFFF)  # finite scales
+    oidx, _ = oracle.decode_indices(lens, S, blocks, meta)
+    idx = E.ecco_decode_indices(m, tu8(blocks, dev), ti32(meta, dev)).cpu().numpy()
+    assert np.array_equal(idx, oidx)
+    dec = E.ecco_decode(m, tu8(blocks, dev), ti32(meta, dev)).cpu().numpy().view(np.uint16)
+    assert np.array_equal(dec, oracle.decode(cent.view(np.uint16), lens, blocks, meta))
+
+
+def test_dequant_every_scale(dev, oracle):
+    """All finite positive scales x 16 centroids through raw-mode blocks: FP16 bit-exact (subnormals kept)."""
+    cent = np.array([[-1.0, -0.75, -0.52, -0.33, -0.2, -0.1, -0.031, -0.0007, 0.0, 0.011, 0.09, 0.21, 0.37, 0.5, 0.83, 1.0]],
+                    np.float16)
+    lens = np.full((1, 16), 4, np.uint8)
+    m = E.ecco_model_to_device(E.ecco_model_create(cent, lens), 0)
+    scales = np.arange(0, 0x7C00, dtype=np.uint32)
+    nib = np.arange(128) % 16
+    block = (nib[0::2] | (nib[1::2] << 4)).astype(np.uint8)
+    blocks = np.tile(block, (scales.size, 1))
+    meta = (scales | (1 << 22)).astype(np.uint32)
+    dec = E.ecco_decode(m, tu8(blocks, dev), ti32(meta, dev)).cpu().numpy().view(np.uint16)
+    assert np.array_equal(dec, oracle.decode(cent.view(np.uint16), lens, blocks, meta))
+
+
+def test_edge_cases(dev, oracle, tiny):
+    m = tiny["m"]
+    # empty input: no-ops
+    e16 = torch.empty((0, 128), dtype=torch.float16, device=dev)
+    b, mt = E.ecco_encode(m, e16)
+    assert b.numel() == 0 and mt.numel() == 0
+    assert E.ecco_decode(m, b, mt).numel() == 0
+    # all-zero groups, a lone outlier, the largest finite FP16 values, subnormals
+    x = np.zeros((6, 128), np.float16)
+    x[1, 5] = 3.0
+    x[2] = 65504.0; x[2, ::2] = -65504.0
+    x[3] = np.float16(6e-8); x[3, 7] = np.float16(-1.2e-7)
+    x[4] = np.linspace(-1, 1, 128)
+    x[5, 100] = -0.0
+    ob, om = oracle.encode(m.centroids, m.code_lens, x.view(np.uint16))
+    blocks, meta = E.ecco_encode(m, t16(x, dev))
+    assert np.array_equal(np_meta(meta), om) and np.array_equal(np_blocks(blocks), ob)
+    dec = E.ecco_decode(m, blocks, meta).cpu().numpy().view(np.uint16)
+    assert np.array_equal(dec, oracle.decode(m.centroids, m.code_lens, ob, om))
+    # argument errors come back as statuses
+    with pytest.raises(E.EccoError) as e:
+        E.ecco_decode_gemv(m, blocks, meta, 6, 100, torch.zeros((1, 100), dtype=torch.float16, device=dev))
+    assert e.value.status == -2
+    with pytest.raises(E.EccoError) as e:
+        E.ecco_decode_gemv(m, blocks, meta, 6, 128, torch.zeros((17, 128), dtype=torch.float16, device=dev))
+    assert e.value.status == -2
+    mis = torch.empty(6 * 64 + 64, dtype=torch.uint8, device=dev)[16:16 + 6 * 64]
+    with pytest.raises(E.EccoError) as e:
+        E.ecco_decode(m, mis, meta)
+    assert e.value.status == -3
+
+
+# ---------------------------------------------------------------------------------------------------
+def _kv_setup(dev, oracle, B, H, T, S):
+    k, v = W.kv_cache(B, H, T, 128, seed=3)
+    mk = E.ecco_model_to_device(E.ecco_fit_patterns(k[:, :, : max(8, T // 8)], S, 12, 3), 0)
+    mv = E.ecco_model_to_device(E.ecco_fit_patterns(v[:, :, : max(8, T // 8)], S, 12, 3), 0)
+    return k, v, mk, mv
+
+
+def test_kv_append_matches_oracle(dev, oracle):
+    B, H, T = 3, 5, 9
+    k, v, mk, mv = _kv_setup(dev, oracle, B, H, T, 8)
+    kb = torch.zeros((B, H, T, 64), dtype=torch.uint8, device=dev); km = torch.zeros((B, H, T), dtype=torch.int32, device=dev)
+    vb = torch.zeros_like(kb); vm = torch.zeros_like(km)
+    okb = np.zeros((B, H, T, 64), np.uint8); okm = np.zeros((B, H, T), np.uint32)
+    ovb = np.zeros_like(okb); ovm = np.zeros_like(okm)
+    seq = np.array([0, 4, T], np.int32)  # the last sequence is full: nothing may be written
+    for step in range(5):
+        cur = np.minimum(seq + step, T).astype(np.int32)
+        tok = np.minimum(cur, T - 1)
+        kn = np.stack([k[b, :, tok[b]] for b in range(B)]); vn = np.stack([v[b, :, tok[b]] for b in range(B)])
+        E.ecco_kv_append(mk, mv, t16(kn, dev), t16(vn, dev), kb, km, vb, vm, ti32(cur, dev), B, H, T)
+        oracle.kv_append(mk.centroids, mk.code_lens, mv.centroids, mv.code_lens, kn.view(np.uint16), vn.view(np.uint16),
+                         okb, okm, ovb, ovm, cur, B, H, T)
+    torch.cuda.synchronize()
+    assert np.array_equal(kb.cpu().numpy(), okb) and np.array_equal(km.cpu().numpy().view(np.uint32), okm)
+    assert np.array_equal(vb.cpu().numpy(), ovb) and np.array_equal(vm.cpu().numpy().view(np.uint32), ovm)
+    assert okm[2].sum() == 0 and okm[0, :, :5].all()
+
+
+def test_kv_attend_matches_oracle(dev, oracle):
+    B, H, T = 4, 3, 700  # several 256-token chunks and a ragged tail
+    k, v, mk, mv = _kv_setup(dev, oracle, B, H, T, 16)
+    kb, km = E.ecco_encode(mk, t16(k, dev)); vb, vm = E.ecco_encode(mv, t16(v, dev))
+    q = W.activation(B * H, 128, 103).reshape(B, H, 128)
+    seq = np.array([T, 1, 0, 300], np.int32)
+    out = E.ecco_kv_attend(mk, mv, t16(q, dev), kb, km, vb, vm, ti32(seq, dev), B, H, T).cpu().numpy()
+    want = oracle.kv_attend(mk.centroids, mk.code_lens, mv.centroids, mv.code_lens, q.view(np.uint16),
+                            np_blocks(kb), np_meta(km), np_blocks(vb), np_meta(vm), seq, B, H, T)
+    assert not out[2].any()
+    assert rel_l2(out, want) <= REL_L2
+    for b in (0, 1, 3):
+        for h in range(H):
+            assert rel_l2(out[b, h], want[b, h]) <= REL_L2
+    # one token: the output is the decoded V_0 (up to FP32 rounding of p = 1)
+    vdec = oracle.decode(mv.centroids, mv.code_lens, np_blocks(vb), np_meta(vm)).view(np.float16).reshape(B, H, T, 128)
+    assert np.allclose(out[1], vdec[1, :, 0].astype(np.float64), rtol=1e-6, atol=1e-9)
+
+
+# ---------------------------------------------------------------------------------------------------
+# full-size workloads, checked on samples the oracle computes one by one
+def _full_weight_case(dev, oracle, name, which, rows_limit=None, n_sample=1536, batches=(1,)):
+    c = W.CONFIGS[name]
+    rows, cols = c["shapes"][which]
+    if rows_limit:
+        rows = rows_limit
+    w = W.config_weight(name, which, rows=rows)
+    m = E.ecco_model_to_device(E.ecco_fit_patterns(w, c["S"], 12, c["seeds"][which]), 0)
+    assert oracle.verify_model(m.centroids, m.code_lens) == 0
+    wt = t16(w, dev)
+    blocks, meta = E.ecco_encode(m, wt)
+    dec = E.ecco_decode(m, blocks, meta)
+    idx = E.ecco_decode_indices(m, blocks, meta)
+    torch.cuda.synchronize()
+    gpr = cols // 128
+    rng = np.random.default_rng(1)
+    rsel = np.sort(rng.choice(rows, min(rows, max(4, n_sample // gpr)), replace=False))
+    gsel = (rsel[:, None] * gpr + np.arange(gpr)[None, :]).reshape(-1)
+    wg = w.reshape(-1, 128)[gsel]
+    ob, om = oracle.encode(m.centroids, m.code_lens, wg.view(np.uint16))
+    gsel_t = torch.from_numpy(gsel).to(dev)
+    assert np.array_equal(np_meta(meta[gsel_t]), om)
+    assert np.array_equal(np_blocks(blocks[gsel_t]), ob)
+    oidx, _ = oracle.decode_indices(m.code_lens, m.S, ob, om)
+    assert np.array_equal(idx[gsel_t].cpu().numpy(), oidx)
+    assert np.array_equal(dec[gsel_t].cpu().numpy().view(np.uint16), oracle.decode(m.centroids, m.code_lens, ob, om))
+    # properties that hold at any size: meta reserved bits zero, pattern ids in range, indices in range
+    mu = np_meta(meta)
+    assert (mu >> 23).max() == 0 and ((mu >> 16) & 63).max() < m.S
+    assert int(idx.max()) < 16
+    for batch in batches:
+        x = W.activation(batch, cols, c["x_seed"])
+        y = E.ecco_decode_gemv(m, blocks, meta, rows, cols, t16(x, dev)).cpu().numpy()
+        want = oracle.gemv(m.centroids, m.code_lens, ob, om, len(rsel), cols, x.view(np.uint16))
+        assert rel_l2(y[:, rsel], want) <= REL_L2, (name, batch)
+        # the whole output against FP32 torch on the GPU-decoded weights (property: same matrix, two routes)
+        ref = (x.astype(np.float32) @ dec.float().cpu().numpy().reshape(rows, cols).T)
+        assert rel_l2(y, ref) <= REL_L2
+
+
+def test_full_proj7b(dev, oracle):
+    _full_weight_case(dev, oracle, "proj7b", 0, batches=(1,))
+
+
+def test_full_mlp_up(dev, oracle):
+    _full_weight_case(dev, oracle, "mlp", 0, batches=(1, 8, 16))
+
+
+def test_full_mlp_down(dev, oracle):
+    _full_weight_case(dev, oracle, "mlp", 1, batches=(1, 8, 16))
+
+
+def test_proj70b_row_slab(dev, oracle):
+    # the 70B-class projection at its real row length (224 column groups), first 1024 rows
+    _full_weight_case(dev, oracle, "proj70b", 0, rows_limit=1024, batches=(1,))

@@ -1,0 +1,124 @@
+"""CPU-side checks of libecco: the C ABI loads and exports what include/ecco.h declares, the CPU fit
+meets the model invariants and agrees with the oracle's fit where the paper's steps fix the result,
+models serialise, and argument errors are reported before anything is launched.  No GPU needed."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2505_06901_amd as E
+from paper_2505_06901_amd import binding, workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_header_symbols_exported():
+    text = open(os.path.join(ROOT, "include", "ecco.h")).read()
+    declared = set(re.findall(r"\b(ecco_[a-z_A-Z0-9]+)\s*\(", text))
+    declared -= {"ecco_model", "ecco_status"}  # type names that precede a parenthesis in comments
+    assert declared == set(binding.EXPORTS), declared ^ set(binding.EXPORTS)
+    L = binding.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+    assert binding.strerror(0) == "ok" and "shape" in binding.strerror(-2)
+
+
+@pytest.fixture(scope="module")
+def tiny_model():
+    w = W.config_weight("tiny")
+    return w, E.ecco_fit_patterns(w, 16, 12, 0)
+
+
+def test_fit_invariants_and_oracle_agreement(oracle, tiny_model):
+    w, m = tiny_model
+    cent, lens = m.centroids, m.code_lens
+    assert m.S == 16 and cent.shape == (16, 16)
+    assert oracle.verify_model(cent, lens) == 0          # the oracle's independent verifier
+    ocent, olens, ohist, _ = oracle.fit(w.view(np.uint16), 16, 12, 0)
+    # both follow the same stated steps with the same seed: the shared patterns agree exactly here
+    assert np.array_equal(cent, ocent)
+    # code lengths may differ in ties; the cost on the oracle's counts must be the same (optimal cost is unique)
+    for p in range(16):
+        if ohist[p].sum():
+            assert ((ohist[p] + 1) * lens[p]).sum() == ((ohist[p] + 1) * olens[p]).sum()
+        else:
+            assert (lens[p] == 4).all()
+    m2 = E.ecco_fit_patterns(w, 16, 12, 0)
+    assert np.array_equal(m2.centroids, cent) and np.array_equal(m2.code_lens, lens)
+
+
+def test_fit_respects_length_limit(oracle):
+    # one-sided, very peaked data make rare indices: unlimited Huffman would exceed 6 bits
+    rng = np.random.default_rng(0)
+    x = (rng.standard_t(1.2, size=(400, 128)) * 0.01).astype(np.float16)
+    x = np.clip(x, -60000, 60000)
+    m = E.ecco_fit_patterns(x, 4, 6, 3)
+    assert m.code_lens.max() <= 6
+    assert oracle.verify_model(m.centroids, m.code_lens) == 0
+    m12 = E.ecco_fit_patterns(x, 4, 12, 3)
+    assert oracle.verify_model(m12.centroids, m12.code_lens) == 0
+    assert m12.code_lens.max() > 6
+
+
+def test_fit_subsamples_large_inputs(oracle):
+    w = W.weight_matrix(1100, 8192, 0.02, 1e-3, 10.0, seed=5)  # 70 400 groups > 65 536
+    m = E.ecco_fit_patterns(w, 8, 12, 7)
+    assert oracle.verify_model(m.centroids, m.code_lens) == 0
+
+
+def test_model_roundtrip_and_validation(tiny_model):
+    _, m = tiny_model
+    blob = E.ecco_model_save(m)
+    assert len(blob) == 16 + 16 * 16 * 3
+    m2 = E.ecco_model_load(blob)
+    assert np.array_equal(m2.centroids, m.centroids) and np.array_equal(m2.code_lens, m.code_lens)
+    bad = bytearray(blob); bad[0] ^= 1
+    with pytest.raises(E.EccoError) as e:
+        E.ecco_model_load(bytes(bad))
+    assert e.value.status == -5
+    with pytest.raises(E.EccoError):
+        E.ecco_model_load(blob[:-1])
+    cent, lens = m.centroids, m.code_lens
+    c2 = cent.copy(); c2[3, 4], c2[3, 5] = cent[3, 5] + 1, cent[3, 4]  # unsorted
+    with pytest.raises(E.EccoError):
+        E.ecco_model_create(c2, lens)
+    l2 = lens.copy(); l2[0, 0] += 1                                     # Kraft sum < 1
+    with pytest.raises(E.EccoError):
+        E.ecco_model_create(cent, l2)
+    c3 = cent.copy(); c3[0, 15] = 0x3E00                                # 1.5
+    with pytest.raises(E.EccoError):
+        E.ecco_model_create(c3, lens)
+    c4 = cent.copy(); c4[0, 15] = 0x7C00                                # inf
+    with pytest.raises(E.EccoError):
+        E.ecco_model_create(c4, lens)
+    assert E.ecco_model_create(cent, lens).S == 16
+
+
+def test_argument_errors_without_gpu(tiny_model):
+    w, m = tiny_model
+    L = binding.lib()
+    h = m.handle
+    null = C.c_void_p(0)
+    fake = C.c_void_p(0x1000)   # never dereferenced: the calls must fail before any launch
+    out = C.c_void_p(0)
+    a = w.view(np.uint16)
+    assert L.ecco_fit_patterns(null, 128, 4, 12, 0, C.byref(out)) == -1
+    assert L.ecco_fit_patterns(a.ctypes.data_as(C.c_void_p), 100, 4, 12, 0, C.byref(out)) == -2
+    assert L.ecco_fit_patterns(a.ctypes.data_as(C.c_void_p), 1280, 65, 12, 0, C.byref(out)) == -1
+    assert L.ecco_fit_patterns(a.ctypes.data_as(C.c_void_p), 1280, 4, 13, 0, C.byref(out)) == -1
+    nan = np.full(128, 0x7E00, np.uint16)
+    assert L.ecco_fit_patterns(nan.ctypes.data_as(C.c_void_p), 128, 1, 12, 0, C.byref(out)) == -1
+    # model not on a device -> EINVAL for every GPU entry point
+    assert L.ecco_decode(h, fake, fake, 1, fake, null) == -1
+    assert L.ecco_encode(h, fake, 1, fake, fake, null) == -1
+    assert L.ecco_decode_gemv(h, fake, fake, 1, 128, fake, 1, fake, null) == -1
+    assert L.ecco_kv_append(h, h, fake, fake, fake, fake, fake, fake, fake, 1, 1, 1, null) == -1
+    assert L.ecco_kv_attend(h, h, fake, fake, fake, fake, fake, fake, 1, 1, 1, fake, null) == -1
+    assert L.ecco_decode(null, fake, fake, 1, fake, null) == -1
+    assert L.ecco_decode(h, null, fake, 1, fake, null) == -1
+    assert L.ecco_model_to_device(null, 0) == -1
+    assert L.ecco_model_to_device(h, -1) == -1
