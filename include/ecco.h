@@ -12,15 +12,18 @@
  * BLOCK FORMAT (the simplified format this build measures; differences from the paper's
  * self-contained block are listed in the design doc):
  *   - group  = 128 consecutive FP16 values.  Matrices: row-major, group g = (row, col/128).
- *   - block  = 64 bytes of payload per group at byte offset 64*g.  The payload is a bit stream;
- *              stream bit j (0..511) is bit (j & 7) of byte (j >> 3), i.e. bit (j & 31) of the
- *              little-endian 32-bit word (j >> 5).
+ *   - block  = 64 bytes of payload per group at byte offset 64*g: 16 little-endian 32-bit words
+ *              holding a bit stream; stream bit j (0..511) is bit 31 - (j & 31) of word j >> 5
+ *              (most significant bit of each word first).
  *       Huffman mode: the canonical codes of values 0..127 in order, each written first code
  *              bit (most significant) first, starting at stream bit 0; remaining bits are 0.
  *       Raw mode (used when the codes need more than 512 bits): value i's 4-bit index sits in
- *              stream bits 4i..4i+3, least significant bit first (a little-endian nibble array).
+ *              stream bits 4i..4i+3, most significant bit first.
  *   - meta   = one uint32 per group: bits 15:0 scale (FP16 bit pattern of max|x|, sign 0),
- *              bits 21:16 pattern id, bit 22 raw flag, bits 31:23 zero.
+ *              bits 21:16 pattern id, bit 22 raw flag, bits 31:23 the stream bit at which the
+ *              code of value 64 begins (256 in raw mode).  A decoder reads values 0..63 from
+ *              bit 0 and values 64..127 from that position, so a block is two independent
+ *              chains of 64 values; the encoder writes the position where value 63 ended.
  *   - model  = S patterns x 16 FP16 centroids in [-1,1], ascending, plus S x 16 code lengths in
  *              1..12 with Kraft sum exactly 1.  Codes are canonical: symbols ordered by
  *              (length, symbol); first code 0; next = (previous + 1) << (length growth).

@@ -56,20 +56,24 @@ struct SplitMix {
 };
 
 // ------------------------------------------------------------------------------------------
-// bit stream of one 64-byte block.  Stream bit j is bit (j & 7) of byte (j >> 3); bits at
-// positions >= 512 read as 0 and are never written.
+// bit stream of one 64-byte block: 16 little-endian 32-bit words; stream bit j is bit 31 - (j & 31)
+// of word j >> 5 (most significant bit of each word first).  Bits at positions >= 512 read as 0
+// and are never written.
 inline int get_bit(const uint8_t* blk, int j) {
     if (j >= 8 * ORACLE_BLOCK_BYTES) return 0;
-    return (blk[j >> 3] >> (j & 7)) & 1;
+    int in_word = 31 - (j & 31);                       // bit number inside the 32-bit word
+    return (blk[(j >> 5) * 4 + (in_word >> 3)] >> (in_word & 7)) & 1;  // little-endian byte order
 }
 inline void put_bit(uint8_t* blk, int j, int b) {
-    if (b) blk[j >> 3] = (uint8_t)(blk[j >> 3] | (1u << (j & 7)));
+    int in_word = 31 - (j & 31);
+    if (b) blk[(j >> 5) * 4 + (in_word >> 3)] = (uint8_t)(blk[(j >> 5) * 4 + (in_word >> 3)] | (1u << (in_word & 7)));
 }
 
 struct Meta {
     uint16_t scale;
     int pattern;
     int raw;
+    int mid;  // stream bit at which the code of value 64 begins
 };
 inline Meta unpack_meta(uint32_t m, int S) {
     Meta r;
@@ -77,10 +81,11 @@ inline Meta unpack_meta(uint32_t m, int S) {
     r.pattern = (int)((m >> 16) & 0x3Fu);
     if (r.pattern >= S) r.pattern = S - 1;  // corrupt meta: clamp, never index outside the model
     r.raw = (int)((m >> 22) & 1u);
+    r.mid = (int)(m >> 23);
     return r;
 }
-inline uint32_t pack_meta(uint16_t scale, int pattern, int raw) {
-    return (uint32_t)scale | ((uint32_t)pattern << 16) | ((uint32_t)raw << 22);
+inline uint32_t pack_meta(uint16_t scale, int pattern, int raw, int mid) {
+    return (uint32_t)scale | ((uint32_t)pattern << 16) | ((uint32_t)raw << 22) | ((uint32_t)mid << 23);
 }
 
 }  // namespace
@@ -363,17 +368,18 @@ static void encode_one(const uint16_t* centroids, const uint8_t* lens, const uin
     for (int i = 0; i < G; ++i) total += lens[p * K + idx[i]];
     std::memset(blk, 0, ORACLE_BLOCK_BYTES);
     if (total <= 8 * ORACLE_BLOCK_BYTES) {
-        int pos = 0;
+        int pos = 0, mid = 0;
         for (int i = 0; i < G; ++i) {
+            if (i == G / 2) mid = pos;  // where the second half of the values starts
             int l = lens[p * K + idx[i]];
             uint16_t c = codes[p * K + idx[i]];
             for (int b = l - 1; b >= 0; --b) put_bit(blk, pos++, (c >> b) & 1);  // first bit = top bit of the code
         }
-        *meta = pack_meta(s, p, 0);
-    } else {  // does not fit: plain 4-bit indices, value i in stream bits 4i..4i+3, low bit first
+        *meta = pack_meta(s, p, 0, mid);
+    } else {  // does not fit: plain 4-bit indices, value i in stream bits 4i..4i+3, top bit first
         for (int i = 0; i < G; ++i)
-            for (int b = 0; b < 4; ++b) put_bit(blk, 4 * i + b, (idx[i] >> b) & 1);
-        *meta = pack_meta(s, p, 1);
+            for (int b = 0; b < 4; ++b) put_bit(blk, 4 * i + b, (idx[i] >> (3 - b)) & 1);
+        *meta = pack_meta(s, p, 1, 4 * (G / 2));
     }
 }
 
@@ -389,14 +395,16 @@ void oracle_encode(const uint16_t* centroids, const uint8_t* lens, int S,
 
 // ------------------------------------------------------------------------------------------
 // Decoder, one block: walk the stream one bit at a time; a symbol is recognised as soon as the
-// bits read so far equal one of the 16 codes of the group's pattern.
+// bits read so far equal one of the 16 codes of the group's pattern.  Values 0..63 are read from
+// stream bit 0 on; values 64..127 from the position the meta word gives (for a block written by
+// the encoder that is exactly where value 63 ended).
 static int decode_one(const uint8_t* lens, const uint16_t* codes, int S, const uint8_t* blk, uint32_t m,
                       uint8_t* idx) {
     Meta mt = unpack_meta(m, S);
     if (mt.raw) {
         for (int i = 0; i < G; ++i) {
             int v = 0;
-            for (int b = 0; b < 4; ++b) v |= get_bit(blk, 4 * i + b) << b;
+            for (int b = 0; b < 4; ++b) v |= get_bit(blk, 4 * i + b) << (3 - b);
             idx[i] = (uint8_t)v;
         }
         return 4 * G;
@@ -405,6 +413,7 @@ static int decode_one(const uint8_t* lens, const uint16_t* codes, int S, const u
     const uint16_t* c = codes + mt.pattern * K;
     int pos = 0;
     for (int i = 0; i < G; ++i) {
+        if (i == G / 2) pos = mt.mid;
         uint32_t code = 0;
         int len = 0, sym = -1;
         while (sym < 0 && len < ORACLE_MAX_LEN) {

@@ -14,31 +14,29 @@ constexpr int kMaxLen = ECCO_MAX_LEN;
 constexpr int kMaxS = ECCO_MAX_S;
 constexpr int kBlockWords = ECCO_BLOCK_BYTES / 4;
 
-// Short-code table: a peek of kPeekBits stream bits (first bit in bit 0) selects one byte,
-// (code length << 4) | index; 0 marks a code longer than kPeekBits.  Slot kMaxS is the raw-mode
-// table (length 4, index = low nibble of the peek), so raw blocks take the same code path.
+// Decode table: a peek at the next kPeekBits stream bits (first bit most significant) selects one
+// 32-bit entry per pattern:
+//   bits 31:16  the centroid (FP16 bits) of the index whose code starts the peek
+//   bits 11:8   that index
+//   bits  7:0   the code length; 0 marks a code longer than kPeekBits (resolved through `longtab`)
+// Raw-mode blocks use a 16-entry table per pattern, indexed by the next 4 bits, of the same entry
+// format (length 4), so raw and Huffman blocks run the same instructions with a different shift.
 constexpr int kPeekBits = 8;
-constexpr int kLutSlots = kMaxS + 1;
-constexpr int kRawSlot = kMaxS;
-
-// Pair table for the fused kernels: a peek of kPairBits stream bits selects a 16-bit entry
-//   bits 3:0  first index, bits 7:4 second index (0 when absent),
-//   bits 11:8 stream bits consumed, bits 13:12 number of indices decoded (1 or 2), 0 = long code.
-constexpr int kPairBits = 10;
+constexpr int kPeekEntries = 1 << kPeekBits;
 
 // Device tables, one allocation; offsets in bytes.
 struct DevLayout {
-    static constexpr size_t cent = 0;                                      // half  [kMaxS][16]
-    static constexpr size_t lut8 = cent + kMaxS * kK * 2;                  // u8    [kLutSlots][256]
-    static constexpr size_t longtab = lut8 + kLutSlots * 256;              // u32   [kMaxS][16]
-    static constexpr size_t enc = longtab + kMaxS * kK * 4;                // u32   [kMaxS][16]
-    static constexpr size_t pair = enc + kMaxS * kK * 4;                   // u16   [kLutSlots][1 << kPairBits]
-    static constexpr size_t total = pair + (size_t)kLutSlots * (1u << kPairBits) * 2;
+    static constexpr size_t cent = 0;                                        // half [kMaxS][16]
+    static constexpr size_t enc = cent + kMaxS * kK * 2;                     // u32  [kMaxS][16]
+    static constexpr size_t longtab = enc + kMaxS * kK * 4;                  // u32  [kMaxS][16]
+    static constexpr size_t rawlut = longtab + kMaxS * kK * 4;               // u32  [kMaxS][16]
+    static constexpr size_t lut = rawlut + kMaxS * kK * 4;                   // u32  [kMaxS][256]
+    static constexpr size_t total = lut + (size_t)kMaxS * kPeekEntries * 4;
 };
 
 // longtab entry j (canonical position j): bits 11:0 the code left-aligned in 12 bits,
 // bits 15:12 the index, bits 20:16 the code length.
-// enc entry k: bits 15:0 the code with its bits reversed (first code bit in bit 0), bits 20:16 length.
+// enc entry k: bits 15:0 the code (first code bit most significant), bits 20:16 its length.
 
 }  // namespace ecco
 
@@ -48,6 +46,7 @@ struct ecco_model {
     uint8_t lens[ecco::kMaxS * ecco::kK] = {};
     uint16_t codes[ecco::kMaxS * ecco::kK] = {};  // canonical codes, derived from lens
     int device = -1;
+    int max_len = 0;               // longest code length in the model
     unsigned char* dev = nullptr;  // DevLayout::total bytes on `device`
 };
 

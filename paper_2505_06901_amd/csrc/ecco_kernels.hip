@@ -1,10 +1,15 @@
 // HIP kernels (gfx950) and GPU entry points of libecco.
 //
-// Mapping used throughout: one lane owns one 64-byte block and decodes its 128 indices in order;
-// a wavefront therefore works on 64 blocks at once and all lanes sit at the same index position,
-// whatever their bit positions.  Block payloads are brought into LDS with coalesced 16-byte loads
-// and stored there with a 17-word stride, so that the per-lane word fetches of the bit window hit
-// distinct banks.  The per-pattern decode tables are staged in LDS once per workgroup.
+// Decoder design.  A Huffman stream is serial, so the unit of parallelism is the half block: the
+// meta word says where the code of value 64 begins, hence every block offers two independent
+// chains of 64 values.  One lane owns one chain.  All lanes of a wavefront sit at the same value
+// position (whatever their bit positions), which makes the position-dependent operand of the
+// consumer -- the activation x[i] in the fused GEMV, the query q[i] in attention -- uniform over
+// the wavefront.  Per value a lane does: peek 8 bits of its 64-bit window, one LDS table read that
+// returns code length, index and the centroid as FP16, the consumer's multiply-add, one 64-bit
+// shift.  Raw-mode blocks run the same instructions against a 16-entry table with a 4-bit peek.
+// Block payloads are brought into LDS with coalesced 16-byte loads and kept there with a 17-word
+// stride (word 16 is a zero pad), so per-lane refills of the window hit distinct banks.
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 
@@ -16,26 +21,120 @@ using namespace ecco;
 
 namespace {
 
-constexpr int kThreads = 256;
-constexpr int kStride = kBlockWords + 1;  // LDS words per staged block
+constexpr int kStride = kBlockWords + 1;  // LDS words per staged block (last one is a zero pad)
+constexpr int kHalf = kGroup / 2;         // values per chain
 
 #define ECCO_HIP_CHECK(expr) do { if ((expr) != hipSuccess) return ECCO_EHIP; } while (0)
 
-struct Tables {           // LDS copies of the model's decode tables
-    const uint8_t* lut8;  // [kLutSlots][256]
-    const uint32_t* longtab;  // [S][16]
-    const __half* cent;   // [S][16]
-};
-
-// ---- staging ------------------------------------------------------------------------------------
-// copies `bytes` (multiple of 4) from global to LDS, all threads of the workgroup
-__device__ inline void stage_words(uint32_t* dst, const void* src, int bytes) {
-    const uint32_t* s = static_cast<const uint32_t*>(src);
-    for (int i = threadIdx.x; i < bytes / 4; i += blockDim.x) dst[i] = s[i];
+__device__ __forceinline__ float half_bits_f(uint32_t bits) { return __half2float(__ushort_as_half((unsigned short)bits)); }
+// dequantisation: one exact FP32 product, one rounding to FP16
+__device__ __forceinline__ uint32_t dequant_bits(uint32_t cent_bits, float s) {
+    return __half_as_ushort(__float2half_rn(half_bits_f(cent_bits) * s));
 }
 
-// brings `count` consecutive blocks (starting at block index first) into LDS, stride kStride words
-__device__ inline void stage_payload(uint32_t* lds, const uint4* blocks, size_t first, int count) {
+// ---- LDS tables -------------------------------------------------------------------------------------
+struct Tables {
+    const uint32_t* lut;      // [S][256]
+    const uint32_t* rawlut;   // [S][16]
+    const uint32_t* longtab;  // [S][16]
+    const __half* cent;       // [S][16]
+};
+__host__ __device__ constexpr size_t table_words(int S) { return (size_t)S * (kPeekEntries + kK + kK + kK / 2); }
+
+__device__ inline void stage_words(uint32_t* dst, const void* src, int words) {
+    const uint32_t* s = static_cast<const uint32_t*>(src);
+    for (int i = threadIdx.x; i < words; i += blockDim.x) dst[i] = s[i];
+}
+
+// copies the model's decode tables to LDS at `base`; the caller synchronises afterwards
+__device__ inline Tables stage_tables(uint32_t* base, const unsigned char* dev, int S) {
+    uint32_t* lut = base;
+    uint32_t* rawlut = lut + S * kPeekEntries;
+    uint32_t* longtab = rawlut + S * kK;
+    uint32_t* cent = longtab + S * kK;
+    stage_words(lut, dev + DevLayout::lut, S * kPeekEntries);
+    stage_words(rawlut, dev + DevLayout::rawlut, S * kK);
+    stage_words(longtab, dev + DevLayout::longtab, S * kK);
+    stage_words(cent, dev + DevLayout::cent, S * kK / 2);
+    Tables t;
+    t.lut = lut;
+    t.rawlut = rawlut;
+    t.longtab = longtab;
+    t.cent = reinterpret_cast<const __half*>(cent);
+    return t;
+}
+
+// what one lane needs to decode one chain
+struct Lane {
+    const uint32_t* lut;      // this lane's table (Huffman: 256 entries, raw: 16)
+    uint32_t shift;           // 32 - peek width
+    const uint32_t* longtab;  // pattern's canonical list (codes longer than the peek)
+    const __half* cent;       // pattern's centroids
+    float scale;
+    uint32_t second_start;    // stream bit where value 64 begins
+};
+__device__ __forceinline__ Lane lane_setup(const Tables& T, uint32_t meta, int S) {
+    Lane L;
+    uint32_t p = (meta >> 16) & 0x3Fu;
+    p = p < (uint32_t)S ? p : (uint32_t)(S - 1);
+    const bool raw = (meta >> 22) & 1u;
+    L.lut = raw ? T.rawlut + p * kK : T.lut + p * kPeekEntries;
+    L.shift = raw ? 28u : (uint32_t)(32 - kPeekBits);
+    L.longtab = T.longtab + p * kK;
+    L.cent = T.cent + p * kK;
+    L.scale = half_bits_f(meta & 0xFFFFu);
+    L.second_start = raw ? 4u * kHalf : (meta >> 23);
+    return L;
+}
+
+// ---- the chain decoder ----------------------------------------------------------------------------------
+// Decodes kCount values starting at stream bit `start` of the staged block `w` (16 words + zero pad),
+// calling sink(i, entry) with the table entry of each (length, index, centroid).  The window is
+// left-aligned; it is topped up to more than 32 valid bits every 4 values (every 2 when the model
+// has codes longer than 8 bits: kLong), which covers the longest possible run of codes in between.
+// Words past the block read as zero, so arbitrary bytes decode without touching other memory.
+template <bool kLong, int kCount, class Sink>
+__device__ __forceinline__ void decode_chain(const uint32_t* w, uint32_t start, const Lane& L, Sink&& sink) {
+    const uint32_t* wend = w + kBlockWords;
+    const uint32_t* wp = w + (start >> 5);
+    const uint32_t r = start & 31u;
+    uint64_t win = (((uint64_t)wp[0] << 32) | (uint64_t)wp[1]) << r;
+    int valid = 64 - (int)r;
+    wp += 2;
+    uint32_t next = wp < wend ? *wp : 0u;
+    constexpr int kCheck = kLong ? 2 : 4;
+#pragma unroll
+    for (int i = 0; i < kCount; ++i) {
+        if (i > 0 && i % kCheck == 0) {
+            if (valid <= 32) {
+                win |= (uint64_t)next << (32 - valid);
+                valid += 32;
+                ++wp;
+                next = wp < wend ? *wp : 0u;
+            }
+        }
+        uint32_t e = L.lut[(uint32_t)(win >> 32) >> L.shift];
+        if (kLong) {
+            if ((e & 0xFFu) == 0u) {
+                // code longer than the peek: rank of the next 12 bits among the left-aligned canonical codes
+                const uint32_t v = (uint32_t)(win >> 32) >> (32 - kMaxLen);
+                int rank = 0;
+                for (int j = 1; j < kK; ++j) rank += ((L.longtab[j] & 0xFFFu) <= v) ? 1 : 0;
+                const uint32_t t = L.longtab[rank];
+                const uint32_t idx = (t >> 12) & 15u;
+                e = ((uint32_t)__half_as_ushort(L.cent[idx]) << 16) | (idx << 8) | (t >> 16);
+            }
+        }
+        sink(i, e);
+        const uint32_t len = e & 0xFFu;
+        win <<= len;
+        valid -= (int)len;
+    }
+}
+
+// ---- payload staging ------------------------------------------------------------------------------------
+// `count` consecutive blocks starting at block `first` -> LDS slots 0..count-1
+__device__ inline void stage_linear(uint32_t* lds, const uint4* blocks, size_t first, int count) {
     const uint4* src = blocks + first * 4;
     for (int i = threadIdx.x; i < count * 4; i += blockDim.x) {
         uint4 v = src[i];
@@ -43,116 +142,52 @@ __device__ inline void stage_payload(uint32_t* lds, const uint4* blocks, size_t 
         d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
     }
 }
-
-struct MetaWord {
-    uint32_t scale_bits, pattern, slot;
-};
-__device__ inline MetaWord unpack_meta(uint32_t m, int S) {
-    MetaWord r;
-    r.scale_bits = m & 0xFFFFu;
-    uint32_t p = (m >> 16) & 0x3Fu;
-    r.pattern = p < (uint32_t)S ? p : (uint32_t)(S - 1);
-    r.slot = ((m >> 22) & 1u) ? (uint32_t)kRawSlot : r.pattern;
-    return r;
+__device__ inline void zero_pads(uint32_t* lds, int slots) {
+    for (int i = threadIdx.x; i < slots; i += blockDim.x) lds[i * kStride + kBlockWords] = 0u;
 }
 
-// ---- the decoder --------------------------------------------------------------------------------
-// Walks one staged block, calling sink(i, index) for i = 0..127.  `w` points at the block's 16 words
-// in LDS; words past the block read as zero.  The window always holds more than 32 valid bits
-// before a lookup, so a 12-bit code never runs out of bits.
-template <class Sink>
-__device__ inline void decode_block(const uint32_t* w, const uint8_t* lut, const uint32_t* longtab, Sink&& sink) {
-    uint64_t win = (uint64_t)w[0] | ((uint64_t)w[1] << 32);
-    int valid = 64, next = 2;
-#pragma unroll 16
-    for (int i = 0; i < kGroup; ++i) {
-        uint32_t e = lut[(uint32_t)win & 0xFFu];
-        uint32_t len = e >> 4, sym = e & 15u;
-        if (len == 0) {
-            // code longer than the peek: rank of the 12-bit prefix among the left-aligned canonical codes
-            uint32_t v = __brev((uint32_t)win) >> (32 - kMaxLen);
-            int rank = 0;
-            for (int j = 1; j < kK; ++j) rank += ((longtab[j] & 0xFFFu) <= v) ? 1 : 0;
-            uint32_t t = longtab[rank];
-            sym = (t >> 12) & 15u;
-            len = t >> 16;
-        }
-        sink(i, sym);
-        win >>= len;
-        valid -= (int)len;
-        if (valid <= 32) {
-            uint32_t nw = next < kBlockWords ? w[next] : 0u;
-            ++next;
-            win |= (uint64_t)nw << valid;
-            valid += 32;
-        }
-    }
-}
+// ---- ecco_decode / ecco_decode_indices ---------------------------------------------------------------
+constexpr int kDecThreads = 1024;
+constexpr int kDecBlocks = kDecThreads / 2;  // blocks per tile: two lanes per block
+inline size_t decode_lds_bytes(int S) { return (table_words(S) + (size_t)kDecBlocks * kStride) * 4; }
 
-// dequantisation: one exact FP32 product, one rounding to FP16
-__device__ inline __half dequant(__half c, float s) { return __float2half_rn(__half2float(c) * s); }
-
-__device__ inline float scale_of(uint32_t bits) { return __half2float(__ushort_as_half((unsigned short)bits)); }
-
-// LDS carve-up common to the decode-side kernels
-struct DecodeLds {
-    uint32_t* payload;
-    Tables t;
-};
-__device__ inline DecodeLds setup_decode_lds(unsigned char* smem, const unsigned char* dev, int S, int threads, unsigned char** rest) {
-    DecodeLds d;
-    uint32_t* lut8 = reinterpret_cast<uint32_t*>(smem);
-    uint32_t* longtab = lut8 + kLutSlots * 256 / 4;
-    uint32_t* cent = longtab + kMaxS * kK;
-    uint32_t* payload = cent + kMaxS * kK / 2;
-    stage_words(lut8, dev + DevLayout::lut8, kLutSlots * 256);
-    stage_words(longtab, dev + DevLayout::longtab, S * kK * 4);
-    stage_words(cent, dev + DevLayout::cent, S * kK * 2);
-    d.payload = payload;
-    d.t.lut8 = reinterpret_cast<const uint8_t*>(lut8);
-    d.t.longtab = longtab;
-    d.t.cent = reinterpret_cast<const __half*>(cent);
-    *rest = reinterpret_cast<unsigned char*>(payload + threads * kStride);
-    return d;
-}
-constexpr size_t kDecodeLdsBytes = kLutSlots * 256 + kMaxS * kK * 4 + kMaxS * kK * 2 + (size_t)kThreads * kStride * 4;
-
-// ---- ecco_decode / ecco_decode_indices -----------------------------------------------------------
-template <bool kIndices>
-__global__ __launch_bounds__(kThreads) void decode_kernel(const unsigned char* __restrict__ dev, int S,
-                                                          const uint4* __restrict__ blocks, const uint32_t* __restrict__ meta,
-                                                          size_t n_groups, void* __restrict__ dst) {
-    extern __shared__ __align__(16) unsigned char smem[];
-    unsigned char* rest;
-    DecodeLds L = setup_decode_lds(smem, dev, S, kThreads, &rest);
-    for (size_t first = (size_t)blockIdx.x * kThreads; first < n_groups; first += (size_t)gridDim.x * kThreads) {
+template <bool kLong, bool kIndices>
+__global__ __launch_bounds__(kDecThreads) void decode_kernel(const unsigned char* __restrict__ dev, int S,
+                                                             const uint4* __restrict__ blocks, const uint32_t* __restrict__ meta,
+                                                             size_t n_groups, void* __restrict__ dst) {
+    extern __shared__ __align__(16) uint32_t smem[];
+    const Tables T = stage_tables(smem, dev, S);
+    uint32_t* payload = smem + table_words(S);
+    zero_pads(payload, kDecBlocks);
+    // lane layout: waves 0..7 take the first half of blocks 0..511, waves 8..15 the second half
+    const int slot = threadIdx.x & (kDecBlocks - 1);
+    const int half = threadIdx.x / kDecBlocks;
+    for (size_t first = (size_t)blockIdx.x * kDecBlocks; first < n_groups; first += (size_t)gridDim.x * kDecBlocks) {
         const size_t left = n_groups - first;
-        int count = left < (size_t)kThreads ? (int)left : kThreads;
+        const int count = left < (size_t)kDecBlocks ? (int)left : kDecBlocks;
         __syncthreads();
-        stage_payload(L.payload, blocks, first, count);
+        stage_linear(payload, blocks, first, count);
         __syncthreads();
-        if ((int)threadIdx.x < count) {
-            size_t g = first + threadIdx.x;
-            MetaWord mw = unpack_meta(meta[g], S);
-            const uint32_t* w = L.payload + threadIdx.x * kStride;
+        if (slot < count) {
+            const size_t g = first + slot;
+            const Lane L = lane_setup(T, meta[g], S);
+            const uint32_t* w = payload + slot * kStride;
+            const uint32_t start = half ? L.second_start : 0u;
             if (kIndices) {
-                uint4* out = reinterpret_cast<uint4*>(static_cast<uint8_t*>(dst) + g * kGroup);
+                uint4* out = reinterpret_cast<uint4*>(static_cast<uint8_t*>(dst) + g * kGroup + half * kHalf);
                 uint32_t acc[4] = {0, 0, 0, 0};
-                decode_block(w, L.t.lut8 + mw.slot * 256, L.t.longtab + mw.pattern * kK, [&](int i, uint32_t sym) {
-                    acc[(i >> 2) & 3] |= sym << (8 * (i & 3));
+                decode_chain<kLong, kHalf>(w, start, L, [&](int i, uint32_t e) {
+                    acc[(i >> 2) & 3] |= ((e >> 8) & 15u) << (8 * (i & 3));
                     if ((i & 15) == 15) {
                         out[i >> 4] = make_uint4(acc[0], acc[1], acc[2], acc[3]);
                         acc[0] = acc[1] = acc[2] = acc[3] = 0;
                     }
                 });
             } else {
-                uint4* out = reinterpret_cast<uint4*>(static_cast<uint16_t*>(dst) + g * kGroup);
-                const __half* c = L.t.cent + mw.pattern * kK;
-                const float s = scale_of(mw.scale_bits);
+                uint4* out = reinterpret_cast<uint4*>(static_cast<uint16_t*>(dst) + g * kGroup + half * kHalf);
                 uint32_t acc[4] = {0, 0, 0, 0};
-                decode_block(w, L.t.lut8 + mw.slot * 256, L.t.longtab + mw.pattern * kK, [&](int i, uint32_t sym) {
-                    uint32_t h = __half_as_ushort(dequant(c[sym], s));
-                    acc[(i >> 1) & 3] |= h << (16 * (i & 1));
+                decode_chain<kLong, kHalf>(w, start, L, [&](int i, uint32_t e) {
+                    acc[(i >> 1) & 3] |= dequant_bits(e >> 16, L.scale) << (16 * (i & 1));
                     if ((i & 7) == 7) {
                         out[i >> 3] = make_uint4(acc[0], acc[1], acc[2], acc[3]);
                         acc[0] = acc[1] = acc[2] = acc[3] = 0;
@@ -163,79 +198,94 @@ __global__ __launch_bounds__(kThreads) void decode_kernel(const unsigned char* _
     }
 }
 
-// ---- ecco_decode_gemv, baseline kernel (any batch, one batch row per pass) -------------------------
-// A workgroup owns `rows_per_wg` whole rows.  Column groups are taken in slabs of kSlabGroups; the
-// slab's slice of x sits in LDS with 65 words per group, so lanes working on neighbouring column
-// groups read different banks.  Each lane forms the dot product of its block with x in FP32
-// (centroid x activation, scaled once per block), the per-block results go through LDS and one
-// thread per row adds them in column order.
-constexpr int kSlabGroups = 64;
-constexpr int kXStride = kGroup / 2 + 1;  // words per column group of x in LDS
+// ---- ecco_decode_gemv, batch row by batch row ------------------------------------------------------------
+// Tile = 64 rows x 8 column groups = 512 blocks; 16 wavefronts: wavefront (c, h) decodes half h of
+// column group c for the 64 rows, lane = row.  x[i] is then uniform over the wavefront and comes
+// from scalar registers.  A workgroup (row tile, split k) walks the column tiles k, k + split, ...;
+// each lane keeps the running dot product of its row; the 16 wavefronts are added in LDS in a
+// fixed order.  With split > 1 the per-split sums are added to y with atomics (y zeroed first).
+constexpr int kGemvThreads = 1024;
+constexpr int kTileRows = 64;
+constexpr int kTileGroups = 8;
+constexpr int kTileBlocks = kTileRows * kTileGroups;
+inline size_t gemv_lds_bytes(int S) { return (table_words(S) + (size_t)kTileBlocks * kStride + 16 * 64) * 4; }
 
-__global__ __launch_bounds__(kThreads) void gemv_rows_kernel(const unsigned char* __restrict__ dev, int S,
-                                                             const uint4* __restrict__ blocks, const uint32_t* __restrict__ meta,
-                                                             int rows, int gpr, int rows_per_wg,
-                                                             const uint32_t* __restrict__ x, float* __restrict__ y) {
-    extern __shared__ __align__(16) unsigned char smem[];
-    unsigned char* rest;
-    DecodeLds L = setup_decode_lds(smem, dev, S, kThreads, &rest);
-    uint32_t* xs = reinterpret_cast<uint32_t*>(rest);           // kSlabGroups * kXStride words
-    float* part = reinterpret_cast<float*>(xs + kSlabGroups * kXStride);  // kThreads partial sums
+__global__ void fill_zero_kernel(float* __restrict__ p, size_t n) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0.0f;
+}
 
-    const int row0 = blockIdx.x * rows_per_wg;
-    const int nrows = min(rows_per_wg, rows - row0);
-    float row_acc = 0.0f;  // thread r < nrows accumulates row row0 + r
-    for (int slab = 0; slab < gpr; slab += kSlabGroups) {
-        const int sg = min(kSlabGroups, gpr - slab);  // column groups in this slab
+template <bool kLong>
+__global__ __launch_bounds__(kGemvThreads) void gemv_kernel(const unsigned char* __restrict__ dev, int S,
+                                                            const uint4* __restrict__ blocks, const uint32_t* __restrict__ meta,
+                                                            int rows, int gpr, int split,
+                                                            const uint32_t* __restrict__ x, float* __restrict__ y) {
+    extern __shared__ __align__(16) uint32_t smem[];
+    const Tables T = stage_tables(smem, dev, S);
+    uint32_t* payload = smem + table_words(S);
+    float* part = reinterpret_cast<float*>(payload + kTileBlocks * kStride);
+    zero_pads(payload, kTileBlocks);
+
+    const int row_tile = blockIdx.x / split, k0 = blockIdx.x % split;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int cgl = wave >> 1, half = wave & 1;
+    const int row = min(row_tile * kTileRows + lane, rows - 1);  // lanes past the last row repeat it; their sums are dropped
+    const int col_tiles = (gpr + kTileGroups - 1) / kTileGroups;
+    float total = 0.0f;
+    for (int ct = k0; ct < col_tiles; ct += split) {
         __syncthreads();
-        for (int i = threadIdx.x; i < sg * (kGroup / 2); i += kThreads)
-            xs[(i >> 6) * kXStride + (i & 63)] = x[(size_t)slab * (kGroup / 2) + i];
-        const int total = nrows * sg;  // blocks of this slab, numbered row-major within the slab
-        for (int base = 0; base < total; base += kThreads) {
-            const int count = min(kThreads, total - base);
-            __syncthreads();
-            // stage: block j of the chunk is (row, cg) = divmod(base + j, sg)
-            for (int i = threadIdx.x; i < count * 4; i += kThreads) {
-                int j = base + (i >> 2);
-                size_t g = (size_t)(row0 + j / sg) * gpr + slab + j % sg;
-                uint4 v = blocks[g * 4 + (i & 3)];
-                uint32_t* d = L.payload + (i >> 2) * kStride + (i & 3) * 4;
+        // stage 64 rows x 8 column groups: per row a 512-byte run (or less at the ragged edge)
+        for (int q = threadIdx.x; q < kTileBlocks * 4; q += kGemvThreads) {
+            const int r = q >> 5, c = (q >> 2) & 7, part16 = q & 3;
+            const int gr = min(row_tile * kTileRows + r, rows - 1), gc = ct * kTileGroups + c;
+            if (gc < gpr) {
+                uint4 v = blocks[((size_t)gr * gpr + gc) * 4 + part16];
+                uint32_t* d = payload + (c * kTileRows + r) * kStride + part16 * 4;
                 d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
             }
-            __syncthreads();
-            if ((int)threadIdx.x < count) {
-                int j = base + threadIdx.x;
-                int cg = j % sg;
-                size_t g = (size_t)(row0 + j / sg) * gpr + slab + cg;
-                MetaWord mw = unpack_meta(meta[g], S);
-                const __half* c = L.t.cent + mw.pattern * kK;
-                const uint32_t* xg = xs + cg * kXStride;
-                float acc = 0.0f;
-                uint32_t xp = 0;
-                decode_block(L.payload + threadIdx.x * kStride, L.t.lut8 + mw.slot * 256, L.t.longtab + mw.pattern * kK,
-                             [&](int i, uint32_t sym) {
-                                 if ((i & 1) == 0) xp = xg[i >> 1];
-                                 float xv = __half2float(__ushort_as_half((unsigned short)((i & 1) ? (xp >> 16) : (xp & 0xFFFFu))));
-                                 acc = fmaf(__half2float(c[sym]), xv, acc);
-                             });
-                part[threadIdx.x] = acc * scale_of(mw.scale_bits);
-            }
-            __syncthreads();
-            if ((int)threadIdx.x < nrows) {
-                // blocks of my row inside this chunk: j in [r*sg, (r+1)*sg) intersected with [base, base+count)
-                int lo = max((int)threadIdx.x * sg, base), hi = min(((int)threadIdx.x + 1) * sg, base + count);
-                for (int j = lo; j < hi; ++j) row_acc += part[j - base];
-            }
+        }
+        __syncthreads();
+        const int cg = ct * kTileGroups + cgl;
+        if (cg < gpr) {  // uniform over the wavefront
+            const Lane L = lane_setup(T, meta[(size_t)row * gpr + cg], S);
+            const uint32_t* xw = x + (size_t)cg * (kGroup / 2) + half * (kHalf / 2);
+            uint32_t xs[kHalf / 2];
+#pragma unroll
+            for (int j = 0; j < kHalf / 2; ++j) xs[j] = xw[j];
+            float acc = 0.0f;
+            decode_chain<kLong, kHalf>(payload + (cgl * kTileRows + lane) * kStride, half ? L.second_start : 0u, L,
+                                       [&](int i, uint32_t e) {
+                                           const uint32_t xp = xs[i >> 1];
+                                           const float xv = half_bits_f((i & 1) ? (xp >> 16) : (xp & 0xFFFFu));
+                                           acc = fmaf(half_bits_f(e >> 16), xv, acc);
+                                       });
+            total = fmaf(acc, L.scale, total);
         }
     }
-    if ((int)threadIdx.x < nrows) y[row0 + threadIdx.x] = row_acc;
+    part[wave * 64 + lane] = total;
+    __syncthreads();
+    if (threadIdx.x < 64) {
+        float s = 0.0f;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) s += part[w * 64 + threadIdx.x];
+        const int out_row = row_tile * kTileRows + threadIdx.x;
+        if (out_row < rows) {
+            if (split > 1) atomicAdd(&y[out_row], s); else y[out_row] = s;
+        }
+    }
 }
 
 // ---- encoder ---------------------------------------------------------------------------------------
 // One wavefront per group; lane l holds values 2l and 2l+1.
-constexpr int kEncWaves = kThreads / 64;
+constexpr int kEncThreads = 256;
+constexpr int kEncWaves = kEncThreads / 64;
 
 __device__ inline float wave_xor_add(float v, int mask) { return __fadd_rn(v, __shfl_xor(v, mask)); }
+__device__ inline void wave_lds_fence() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
 
 struct EncLds {
     const __half* cent;     // [S][16]
@@ -244,98 +294,94 @@ struct EncLds {
     uint32_t* bits;         // per wave 16 words
 };
 
-// Encodes the group whose two values of this lane are (x0, x1); lanes 0..15 return one payload word
-// each in *word, lane 0 the meta word in *meta.
+// Encodes the group whose two values of this lane are (hx0, hx1) as FP16 bits; lanes 0..15 return
+// one payload word each in *word, every lane the meta word in *meta.
 __device__ inline void encode_group(const EncLds& E, int S, uint32_t hx0, uint32_t hx1, uint32_t* word, uint32_t* meta) {
     const int lane = threadIdx.x & 63;
     // scale: the largest magnitude, as an FP16 bit pattern
     uint32_t smax = max(hx0 & 0x7FFFu, hx1 & 0x7FFFu);
     for (int m = 1; m < 64; m <<= 1) smax = max(smax, (uint32_t)__shfl_xor((int)smax, m));
-    const float s = scale_of(smax);
-    // reconstructed values of every pattern: fp16(centroid * s) back in FP32
-    for (int i = lane; i < S * kK; i += 64) E.recon[i] = __half2float(__float2half_rn(__half2float(E.cent[i]) * s));
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_s_waitcnt(0xc07f);  // LDS writes of this wave are done before the reads below
-    const float x0 = __half2float(__ushort_as_half((unsigned short)hx0));
-    const float x1 = __half2float(__ushort_as_half((unsigned short)hx1));
+    const float s = half_bits_f(smax);
+    // reconstructed values of every pattern: fp16(centroid * s), kept as FP32
+    for (int i = lane; i < S * kK; i += 64) E.recon[i] = half_bits_f(dequant_bits(__half_as_ushort(E.cent[i]), s));
+    if (lane < kBlockWords) E.bits[lane] = 0;
+    wave_lds_fence();
+    const float x0 = half_bits_f(hx0), x1 = half_bits_f(hx1);
     float best = 0.0f;
     int best_p = 0;
     uint32_t best_idx = 0;
     for (int p = 0; p < S; ++p) {
         const float* r = E.recon + p * kK;
-        float r0 = r[0];
+        const float r0 = r[0];
         float d0 = fabsf(__fsub_rn(x0, r0)), d1 = fabsf(__fsub_rn(x1, r0));
         uint32_t k0 = 0, k1 = 0;
         float q0 = r0, q1 = r0;
 #pragma unroll
         for (int k = 1; k < kK; ++k) {
-            float rk = r[k];
-            float a = fabsf(__fsub_rn(x0, rk)), b = fabsf(__fsub_rn(x1, rk));
-            if (a < d0) { d0 = a; k0 = k; q0 = rk; }
+            const float rk = r[k];
+            const float a = fabsf(__fsub_rn(x0, rk)), b = fabsf(__fsub_rn(x1, rk));
+            if (a < d0) { d0 = a; k0 = k; q0 = rk; }   // strict: the lowest index wins a tie
             if (b < d1) { d1 = b; k1 = k; q1 = rk; }
         }
-        float e0 = __fsub_rn(x0, q0), e1 = __fsub_rn(x1, q1);
+        const float e0 = __fsub_rn(x0, q0), e1 = __fsub_rn(x1, q1);
         float v = __fadd_rn(__fmul_rn(e0, e0), __fmul_rn(e1, e1));  // tree level 0: values 2l and 2l+1
         for (int m = 1; m < 64; m <<= 1) v = wave_xor_add(v, m);    // levels 1..6
         if (p == 0 || v < best) { best = v; best_p = p; best_idx = k0 | (k1 << 4); }
     }
-    // code lengths and codes of the chosen pattern
+    // codes of the chosen pattern, bit positions by an inclusive scan over lanes
     const uint32_t c0 = E.enc[best_p * kK + (best_idx & 15u)], c1 = E.enc[best_p * kK + (best_idx >> 4)];
     const uint32_t l0 = c0 >> 16, l1 = c1 >> 16;
-    uint32_t incl = l0 + l1;  // inclusive scan of bit counts over lanes
+    uint32_t incl = l0 + l1;
     for (int d = 1; d < 64; d <<= 1) {
-        uint32_t o = (uint32_t)__shfl_up((int)incl, d);
+        const uint32_t o = (uint32_t)__shfl_up((int)incl, d);
         if (lane >= d) incl += o;
     }
     const uint32_t total = (uint32_t)__shfl((int)incl, 63);
+    const uint32_t mid = (uint32_t)__shfl((int)incl, 31);  // bits used by values 0..63
     const bool raw = total > 8u * ECCO_BLOCK_BYTES;
-    if (lane < kBlockWords) E.bits[lane] = 0;
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_s_waitcnt(0xc07f);
     if (raw) {
-        // value i in stream bits 4i..4i+3: lane l owns byte l of the payload
-        atomicOr(&E.bits[lane >> 2], (best_idx & 0xFFu) << (8 * (lane & 3)));
+        // value i in stream bits 4i..4i+3, top bit first: lane l owns the byte at stream bits 8l..8l+7
+        atomicOr(&E.bits[lane >> 2], (((best_idx & 15u) << 4) | (best_idx >> 4)) << (24 - 8 * (lane & 3)));
     } else {
-        uint32_t pos = incl - (l0 + l1);
-        uint64_t v = (uint64_t)(c0 & 0xFFFFu) | ((uint64_t)(c1 & 0xFFFFu) << l0);  // up to 24 bits
-        v <<= (pos & 31u);
-        atomicOr(&E.bits[pos >> 5], (uint32_t)v);
-        if ((v >> 32) != 0) atomicOr(&E.bits[(pos >> 5) + 1], (uint32_t)(v >> 32));
+        const uint32_t pos = incl - (l0 + l1);
+        const uint32_t both = ((c0 & 0xFFFFu) << l1) | (c1 & 0xFFFFu);       // l0 + l1 <= 24 bits
+        const uint64_t v = (uint64_t)both << (64 - (l0 + l1) - (pos & 31u));  // left-aligned at stream bit pos
+        atomicOr(&E.bits[pos >> 5], (uint32_t)(v >> 32));
+        if ((uint32_t)v != 0u) atomicOr(&E.bits[(pos >> 5) + 1], (uint32_t)v);
     }
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_s_waitcnt(0xc07f);
+    wave_lds_fence();
     *word = lane < kBlockWords ? E.bits[lane] : 0u;
-    *meta = smax | ((uint32_t)best_p << 16) | (raw ? (1u << 22) : 0u);
-    __builtin_amdgcn_wave_barrier();
+    *meta = smax | ((uint32_t)best_p << 16) | (raw ? (1u << 22) : 0u) | ((raw ? 4u * kHalf : mid) << 23);
+    wave_lds_fence();
 }
 
-constexpr size_t kEncLdsBytes = kMaxS * kK * 2 + kMaxS * kK * 4 + (size_t)kEncWaves * (kMaxS * kK * 4 + kBlockWords * 4);
+constexpr size_t enc_lds_bytes(int S) { return (size_t)S * kK * 2 + (size_t)S * kK * 4 + (size_t)kEncWaves * ((size_t)S * kK * 4 + kBlockWords * 4); }
 
 __device__ inline EncLds setup_enc_lds(unsigned char* smem, const unsigned char* dev, int S) {
     uint32_t* cent = reinterpret_cast<uint32_t*>(smem);
-    uint32_t* enc = cent + kMaxS * kK / 2;
-    float* recon = reinterpret_cast<float*>(enc + kMaxS * kK);
-    uint32_t* bits = reinterpret_cast<uint32_t*>(recon + kEncWaves * kMaxS * kK);
-    stage_words(cent, dev + DevLayout::cent, S * kK * 2);
-    stage_words(enc, dev + DevLayout::enc, S * kK * 4);
+    uint32_t* enc = cent + S * kK / 2;
+    float* recon = reinterpret_cast<float*>(enc + S * kK);
+    uint32_t* bits = reinterpret_cast<uint32_t*>(recon + kEncWaves * S * kK);
+    stage_words(cent, dev + DevLayout::cent, S * kK / 2);
+    stage_words(enc, dev + DevLayout::enc, S * kK);
     __syncthreads();
     const int wave = threadIdx.x >> 6;
     EncLds E;
     E.cent = reinterpret_cast<const __half*>(cent);
     E.enc = enc;
-    E.recon = recon + wave * kMaxS * kK;
+    E.recon = recon + wave * S * kK;
     E.bits = bits + wave * kBlockWords;
     return E;
 }
 
-__global__ __launch_bounds__(kThreads) void encode_kernel(const unsigned char* __restrict__ dev, int S,
-                                                          const uint32_t* __restrict__ src, size_t n_groups,
-                                                          uint32_t* __restrict__ blocks, uint32_t* __restrict__ meta) {
-    extern __shared__ __align__(16) unsigned char smem[];
-    EncLds E = setup_enc_lds(smem, dev, S);
+__global__ __launch_bounds__(kEncThreads) void encode_kernel(const unsigned char* __restrict__ dev, int S,
+                                                             const uint32_t* __restrict__ src, size_t n_groups,
+                                                             uint32_t* __restrict__ blocks, uint32_t* __restrict__ meta) {
+    extern __shared__ __align__(16) unsigned char smem_enc[];
+    EncLds E = setup_enc_lds(smem_enc, dev, S);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     for (size_t g = (size_t)blockIdx.x * kEncWaves + wave; g < n_groups; g += (size_t)gridDim.x * kEncWaves) {
-        uint32_t pair = src[g * (kGroup / 2) + lane];
+        const uint32_t pair = src[g * (kGroup / 2) + lane];
         uint32_t word, mw;
         encode_group(E, S, pair & 0xFFFFu, pair >> 16, &word, &mw);
         if (lane < kBlockWords) blocks[g * kBlockWords + lane] = word;
@@ -343,24 +389,24 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(const unsigned char* _
     }
 }
 
-// grid: B*H*2 wavefronts; even = K, odd = V
-__global__ __launch_bounds__(kThreads) void kv_append_kernel(const unsigned char* __restrict__ dev_k, int Sk,
-                                                             const unsigned char* __restrict__ dev_v, int Sv,
-                                                             const uint32_t* __restrict__ k_new, const uint32_t* __restrict__ v_new,
-                                                             uint32_t* __restrict__ k_blocks, uint32_t* __restrict__ k_meta,
-                                                             uint32_t* __restrict__ v_blocks, uint32_t* __restrict__ v_meta,
-                                                             const int32_t* __restrict__ seq_len, int B, int H, int T_max) {
-    extern __shared__ __align__(16) unsigned char smem[];
+// grid: (ceil(B*H / 4), 2); y = 0 encodes K, y = 1 encodes V
+__global__ __launch_bounds__(kEncThreads) void kv_append_kernel(const unsigned char* __restrict__ dev_k, int Sk,
+                                                                const unsigned char* __restrict__ dev_v, int Sv,
+                                                                const uint32_t* __restrict__ k_new, const uint32_t* __restrict__ v_new,
+                                                                uint32_t* __restrict__ k_blocks, uint32_t* __restrict__ k_meta,
+                                                                uint32_t* __restrict__ v_blocks, uint32_t* __restrict__ v_meta,
+                                                                const int32_t* __restrict__ seq_len, int B, int H, int T_max) {
+    extern __shared__ __align__(16) unsigned char smem_enc[];
     const bool is_v = blockIdx.y != 0;  // uniform per workgroup, so each workgroup stages one model
     const int S = is_v ? Sv : Sk;
-    EncLds E = setup_enc_lds(smem, is_v ? dev_v : dev_k, S);
+    EncLds E = setup_enc_lds(smem_enc, is_v ? dev_v : dev_k, S);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int bh = blockIdx.x * kEncWaves + wave;
     if (bh >= B * H) return;
     const int t = seq_len[bh / H];
     if (t < 0 || t >= T_max) return;
     const uint32_t* src = (is_v ? v_new : k_new) + (size_t)bh * (kGroup / 2);
-    uint32_t pair = src[lane];
+    const uint32_t pair = src[lane];
     uint32_t word, mw;
     encode_group(E, S, pair & 0xFFFFu, pair >> 16, &word, &mw);
     const size_t g = (size_t)bh * T_max + t;
@@ -371,12 +417,21 @@ __global__ __launch_bounds__(kThreads) void kv_append_kernel(const unsigned char
 }
 
 // ---- single-query attention over compressed K / V ----------------------------------------------------
-// One workgroup per (sequence, head); tokens in chunks of 256, one token per lane.  Scores come from
-// decoding K with q held in LDS (all lanes read the same q element at the same time).  Softmax is
-// kept online: running maximum m, running denominator l, running output o rescaled per chunk.
-// V blocks are decoded into an LDS tile [token][128] (129-word rows), then thread (d-pair, quarter)
-// adds p_t * V_t over a quarter of the chunk's tokens.
-constexpr int kVRow = kGroup / 2 + 1;
+// One workgroup per (sequence, head), one token per lane (both chains of its block one after the
+// other).  The sequence is walked in spans of kSpan tokens.  Per span: the K tables are staged and
+// the scores q.K_t / sqrt(128) are formed (q sits in LDS; all lanes read the same element at the
+// same time) and kept in LDS; the span's maximum updates the running softmax (maximum, denominator,
+// rescale of what has been accumulated); then the V tables replace the K tables and every lane adds
+// p_t * V_t into its own 128 FP32 accumulators (static register per value position, nothing shared).
+// At the end the accumulators of the 256 lanes are added through LDS.  Only one model's tables are
+// resident at a time, which keeps S = 64 for both K and V within 160 KB of LDS.
+constexpr int kAttnThreads = 256;
+constexpr int kSpan = 8192;
+constexpr int kRedStride = 33;
+static_assert(kAttnThreads * kRedStride <= kAttnThreads * kStride + kSpan - 256, "reduction scratch must fit");
+inline size_t attn_lds_bytes(int Sk, int Sv) {
+    return (table_words(std::max(Sk, Sv)) + (size_t)kAttnThreads * kStride + kSpan + kGroup + 16) * 4;
+}
 
 __device__ inline float wg_reduce(float v, float* scratch, bool is_max) {
     for (int m = 1; m < 64; m <<= 1) {
@@ -387,120 +442,111 @@ __device__ inline float wg_reduce(float v, float* scratch, bool is_max) {
     if ((threadIdx.x & 63) == 0) scratch[threadIdx.x >> 6] = v;
     __syncthreads();
     float r = scratch[0];
-    for (int w = 1; w < kThreads / 64; ++w) r = is_max ? fmaxf(r, scratch[w]) : r + scratch[w];
+    for (int w = 1; w < kAttnThreads / 64; ++w) r = is_max ? fmaxf(r, scratch[w]) : r + scratch[w];
     return r;
 }
 
-struct AttnLds {
-    Tables tk, tv;
-    uint32_t* payload;
-    uint32_t* vtile;
-    float* q;
-    float* p;
-    float* scratch;
-};
-constexpr size_t kAttnTableBytes = kLutSlots * 256 + kMaxS * kK * 4 + kMaxS * kK * 2;
-constexpr size_t kAttnLdsBytes = 2 * kAttnTableBytes + (size_t)kThreads * kStride * 4 + (size_t)kThreads * kVRow * 4 +
-                                 kGroup * 4 + kThreads * 4 + 64;
-
-__device__ inline Tables stage_tables(uint32_t* base, const unsigned char* dev, int S) {
-    uint32_t* lut8 = base;
-    uint32_t* longtab = lut8 + kLutSlots * 256 / 4;
-    uint32_t* cent = longtab + kMaxS * kK;
-    stage_words(lut8, dev + DevLayout::lut8, kLutSlots * 256);
-    stage_words(longtab, dev + DevLayout::longtab, S * kK * 4);
-    stage_words(cent, dev + DevLayout::cent, S * kK * 2);
-    Tables t;
-    t.lut8 = reinterpret_cast<const uint8_t*>(lut8);
-    t.longtab = longtab;
-    t.cent = reinterpret_cast<const __half*>(cent);
-    return t;
-}
-
-__global__ __launch_bounds__(kThreads) void kv_attend_kernel(const unsigned char* __restrict__ dev_k, int Sk,
-                                                             const unsigned char* __restrict__ dev_v, int Sv,
-                                                             const uint16_t* __restrict__ q,
-                                                             const uint4* __restrict__ k_blocks, const uint32_t* __restrict__ k_meta,
-                                                             const uint4* __restrict__ v_blocks, const uint32_t* __restrict__ v_meta,
-                                                             const int32_t* __restrict__ seq_len, int H, int T_max,
-                                                             float* __restrict__ out) {
-    extern __shared__ __align__(16) unsigned char smem[];
-    AttnLds A;
-    uint32_t* base = reinterpret_cast<uint32_t*>(smem);
-    A.tk = stage_tables(base, dev_k, Sk);
-    A.tv = stage_tables(base + kAttnTableBytes / 4, dev_v, Sv);
-    A.payload = base + 2 * kAttnTableBytes / 4;
-    A.vtile = A.payload + kThreads * kStride;
-    A.q = reinterpret_cast<float*>(A.vtile + kThreads * kVRow);
-    A.p = A.q + kGroup;
-    A.scratch = A.p + kThreads;
+template <bool kLongK, bool kLongV>
+__global__ __launch_bounds__(kAttnThreads) void kv_attend_kernel(const unsigned char* __restrict__ dev_k, int Sk,
+                                                                 const unsigned char* __restrict__ dev_v, int Sv,
+                                                                 const uint16_t* __restrict__ q,
+                                                                 const uint4* __restrict__ k_blocks, const uint32_t* __restrict__ k_meta,
+                                                                 const uint4* __restrict__ v_blocks, const uint32_t* __restrict__ v_meta,
+                                                                 const int32_t* __restrict__ seq_len, int H, int T_max,
+                                                                 float* __restrict__ out) {
+    extern __shared__ __align__(16) uint32_t smem[];
+    const int Smax = max(Sk, Sv);
+    uint32_t* payload = smem + table_words(Smax);
+    float* scores = reinterpret_cast<float*>(payload + kAttnThreads * kStride);
+    float* qs = scores + kSpan;
+    float* scratch = qs + kGroup;
+    zero_pads(payload, kAttnThreads);
 
     const int bh = blockIdx.x;
     const int T = min(seq_len[bh / H], T_max);
-    if (threadIdx.x < kGroup) A.q[threadIdx.x] = __half2float(__ushort_as_half(q[(size_t)bh * kGroup + threadIdx.x]));
-    const int dp = threadIdx.x & 63, quarter = threadIdx.x >> 6;  // output pair (2dp, 2dp+1), token quarter
-    float o0 = 0.0f, o1 = 0.0f, run_max = -INFINITY, run_den = 0.0f;
+    if (threadIdx.x < kGroup) qs[threadIdx.x] = half_bits_f(q[(size_t)bh * kGroup + threadIdx.x]);
+    float o[kGroup];
+#pragma unroll
+    for (int i = 0; i < kGroup; ++i) o[i] = 0.0f;
+    float run_max = -INFINITY, run_den = 0.0f;
     const float inv_sqrt_d = 0.08838834764831845f;  // 1 / sqrt(128)
-    for (int t0 = 0; t0 < T; t0 += kThreads) {
-        const int count = min(kThreads, T - t0);
-        const size_t first = (size_t)bh * T_max + t0;
+    for (int s0 = 0; s0 < T; s0 += kSpan) {
+        const int span = min(kSpan, T - s0);
+        // ---- scores of the span
         __syncthreads();
-        stage_payload(A.payload, k_blocks, first, count);
-        __syncthreads();
-        float score = -INFINITY;
-        if ((int)threadIdx.x < count) {
-            MetaWord mw = unpack_meta(k_meta[first + threadIdx.x], Sk);
-            const __half* c = A.tk.cent + mw.pattern * kK;
-            // the softmax is sensitive to the scores (keys with large per-channel scales), so K takes the
-            // exact dequantisation rule, FP16 rounding included
-            const float s = scale_of(mw.scale_bits);
-            float acc = 0.0f;
-            decode_block(A.payload + threadIdx.x * kStride, A.tk.lut8 + mw.slot * 256, A.tk.longtab + mw.pattern * kK,
-                         [&](int i, uint32_t sym) { acc = fmaf(__half2float(dequant(c[sym], s)), A.q[i], acc); });
-            score = acc * inv_sqrt_d;
+        const Tables TK = stage_tables(smem, dev_k, Sk);
+        float my_max = -INFINITY;
+        for (int t0 = 0; t0 < span; t0 += kAttnThreads) {
+            const int count = min(kAttnThreads, span - t0);
+            const size_t first = (size_t)bh * T_max + s0 + t0;
+            __syncthreads();
+            stage_linear(payload, k_blocks, first, count);
+            __syncthreads();
+            if ((int)threadIdx.x < count) {
+                const Lane L = lane_setup(TK, k_meta[first + threadIdx.x], Sk);
+                const uint32_t* w = payload + threadIdx.x * kStride;
+                // the softmax is sensitive to the scores (keys with large per-channel scales), so K takes the
+                // exact dequantisation rule, FP16 rounding included
+                float acc = 0.0f;
+                decode_chain<kLongK, kHalf>(w, 0u, L, [&](int i, uint32_t e) { acc = fmaf(half_bits_f(dequant_bits(e >> 16, L.scale)), qs[i], acc); });
+                decode_chain<kLongK, kHalf>(w, L.second_start, L,
+                                            [&](int i, uint32_t e) { acc = fmaf(half_bits_f(dequant_bits(e >> 16, L.scale)), qs[kHalf + i], acc); });
+                const float sc = acc * inv_sqrt_d;
+                scores[t0 + threadIdx.x] = sc;
+                my_max = fmaxf(my_max, sc);
+            }
         }
-        const float chunk_max = wg_reduce(score, A.scratch, true);
-        const float new_max = fmaxf(run_max, chunk_max);
-        const float p = ((int)threadIdx.x < count) ? __expf(score - new_max) : 0.0f;
-        const float chunk_den = wg_reduce(p, A.scratch, false);
+        // ---- running softmax
+        const float new_max = fmaxf(run_max, wg_reduce(my_max, scratch, true));
+        float my_den = 0.0f;
+        for (int t = threadIdx.x; t < span; t += kAttnThreads) {  // each lane touches only its own tokens
+            const float p = __expf(scores[t] - new_max);
+            scores[t] = p;
+            my_den += p;
+        }
         const float rescale = (run_max == -INFINITY) ? 0.0f : __expf(run_max - new_max);
-        run_den = run_den * rescale + chunk_den;
+        run_den = run_den * rescale + wg_reduce(my_den, scratch, false);
         run_max = new_max;
-        o0 *= rescale;
-        o1 *= rescale;
-        A.p[threadIdx.x] = p;
+#pragma unroll
+        for (int i = 0; i < kGroup; ++i) o[i] *= rescale;
+        // ---- weighted sum of V
         __syncthreads();
-        stage_payload(A.payload, v_blocks, first, count);
-        __syncthreads();
-        if ((int)threadIdx.x < count) {
-            MetaWord mw = unpack_meta(v_meta[first + threadIdx.x], Sv);
-            const __half* c = A.tv.cent + mw.pattern * kK;
-            const float s = scale_of(mw.scale_bits);
-            uint32_t* row = A.vtile + threadIdx.x * kVRow;
-            uint32_t lo = 0;
-            decode_block(A.payload + threadIdx.x * kStride, A.tv.lut8 + mw.slot * 256, A.tv.longtab + mw.pattern * kK,
-                         [&](int i, uint32_t sym) {
-                             uint32_t h = __half_as_ushort(dequant(c[sym], s));
-                             if (i & 1) row[i >> 1] = lo | (h << 16); else lo = h;
-                         });
-        }
-        __syncthreads();
-        for (int t = quarter; t < count; t += kThreads / 64) {
-            uint32_t v = A.vtile[t * kVRow + dp];
-            float pt = A.p[t];
-            o0 = fmaf(pt, __half2float(__ushort_as_half((unsigned short)(v & 0xFFFFu))), o0);
-            o1 = fmaf(pt, __half2float(__ushort_as_half((unsigned short)(v >> 16))), o1);
+        const Tables TV = stage_tables(smem, dev_v, Sv);
+        for (int t0 = 0; t0 < span; t0 += kAttnThreads) {
+            const int count = min(kAttnThreads, span - t0);
+            const size_t first = (size_t)bh * T_max + s0 + t0;
+            __syncthreads();
+            stage_linear(payload, v_blocks, first, count);
+            __syncthreads();
+            if ((int)threadIdx.x < count) {
+                const Lane L = lane_setup(TV, v_meta[first + threadIdx.x], Sv);
+                const uint32_t* w = payload + threadIdx.x * kStride;
+                const float p = scores[t0 + threadIdx.x];
+                decode_chain<kLongV, kHalf>(w, 0u, L, [&](int i, uint32_t e) { o[i] = fmaf(p, half_bits_f(dequant_bits(e >> 16, L.scale)), o[i]); });
+                decode_chain<kLongV, kHalf>(w, L.second_start, L,
+                                            [&](int i, uint32_t e) { o[kHalf + i] = fmaf(p, half_bits_f(dequant_bits(e >> 16, L.scale)), o[kHalf + i]); });
+            }
         }
     }
-    // combine the four token quarters
-    __syncthreads();
-    float* red = reinterpret_cast<float*>(A.vtile);
-    red[quarter * kGroup + 2 * dp] = o0;
-    red[quarter * kGroup + 2 * dp + 1] = o1;
-    __syncthreads();
-    if (threadIdx.x < kGroup) {
-        float v = red[threadIdx.x] + red[kGroup + threadIdx.x] + red[2 * kGroup + threadIdx.x] + red[3 * kGroup + threadIdx.x];
-        out[(size_t)bh * kGroup + threadIdx.x] = T > 0 ? v / run_den : 0.0f;
+    // ---- add the 256 lanes' accumulators: four passes of 32 values through LDS
+    float* red = reinterpret_cast<float*>(payload);      // 256 x 33 floats: the payload area and the start of `scores`
+    float* partial = scores + kSpan - 256;               // 8 x 32 partial sums, clear of `red`
+    const int col = threadIdx.x & 31, part = threadIdx.x >> 5;
+#pragma unroll
+    for (int pass = 0; pass < 4; ++pass) {
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 32; ++j) red[threadIdx.x * kRedStride + j] = o[pass * 32 + j];
+        __syncthreads();
+        float s = 0.0f;
+        for (int l = 0; l < 32; ++l) s += red[(part * 32 + l) * kRedStride + col];
+        partial[part * 32 + col] = s;
+        __syncthreads();
+        if (threadIdx.x < 32) {
+            float v = 0.0f;
+            for (int k = 0; k < 8; ++k) v += partial[k * 32 + threadIdx.x];
+            out[(size_t)bh * kGroup + pass * 32 + threadIdx.x] = T > 0 ? v / run_den : 0.0f;
+        }
     }
 }
 
@@ -511,15 +557,20 @@ inline int model_ready(const ecco_model* m) { return (m && m->dev && m->device >
 
 template <class K>
 int allow_lds(K kernel, size_t bytes) {
-    static_assert(sizeof(K) == sizeof(void*), "kernel pointer");
     if (bytes > 64 * 1024)
         ECCO_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
     return ECCO_OK;
 }
 
-int grid_for(size_t work_items, int per_wg, int cap) {
-    size_t g = (work_items + per_wg - 1) / per_wg;
-    return (int)std::min<size_t>(std::max<size_t>(g, 1), (size_t)cap);
+int cu_count(int device) {
+    static int cached[16] = {0};
+    if (device < 0 || device >= 16) return 256;
+    if (!cached[device]) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || n <= 0) n = 256;
+        cached[device] = n;
+    }
+    return cached[device];
 }
 
 }  // namespace
@@ -531,9 +582,10 @@ int ecco_encode(const ecco_model* m, const uint16_t* src, size_t n_groups, void*
     if (n_groups == 0) return ECCO_OK;  // nothing to do; pointers may be null
     if (!src || !blocks || !meta) return ECCO_EINVAL;
     if (!aligned(blocks, 64) || !aligned(src, 4) || !aligned(meta, 4)) return ECCO_EALIGN;
-    int grid = grid_for(n_groups, kEncWaves, 1 << 16);
-    hipLaunchKernelGGL(encode_kernel, dim3(grid), dim3(kThreads), kEncLdsBytes, static_cast<hipStream_t>(stream), m->dev, m->S,
-                       reinterpret_cast<const uint32_t*>(src), n_groups, static_cast<uint32_t*>(blocks), meta);
+    const size_t wgs = (n_groups + kEncWaves - 1) / kEncWaves;
+    const int grid = (int)std::min<size_t>(wgs, (size_t)cu_count(m->device) * 16);
+    hipLaunchKernelGGL(encode_kernel, dim3(grid), dim3(kEncThreads), enc_lds_bytes(m->S), static_cast<hipStream_t>(stream), m->dev,
+                       m->S, reinterpret_cast<const uint32_t*>(src), n_groups, static_cast<uint32_t*>(blocks), meta);
     ECCO_HIP_CHECK(hipGetLastError());
     return ECCO_OK;
 }
@@ -544,15 +596,20 @@ static int decode_common(const ecco_model* m, const void* blocks, const uint32_t
     if (n_groups == 0) return ECCO_OK;  // nothing to do; pointers may be null
     if (!blocks || !meta || !dst) return ECCO_EINVAL;
     if (!aligned(blocks, 64) || !aligned(dst, 16) || !aligned(meta, 4)) return ECCO_EALIGN;
-    int grid = grid_for(n_groups, kThreads, 1 << 14);
-    if (indices)
-        hipLaunchKernelGGL(decode_kernel<true>, dim3(grid), dim3(kThreads), kDecodeLdsBytes, static_cast<hipStream_t>(stream),
-                           m->dev, m->S, static_cast<const uint4*>(blocks), meta, n_groups, dst);
-    else
-        hipLaunchKernelGGL(decode_kernel<false>, dim3(grid), dim3(kThreads), kDecodeLdsBytes, static_cast<hipStream_t>(stream),
-                           m->dev, m->S, static_cast<const uint4*>(blocks), meta, n_groups, dst);
-    ECCO_HIP_CHECK(hipGetLastError());
-    return ECCO_OK;
+    const size_t tiles = (n_groups + kDecBlocks - 1) / kDecBlocks;
+    const int grid = (int)std::min<size_t>(tiles, (size_t)cu_count(m->device) * 4);
+    const size_t lds = decode_lds_bytes(m->S);
+    const bool lng = m->max_len > kPeekBits;
+    auto launch = [&](auto kernel) -> int {
+        int rc = allow_lds(kernel, lds);
+        if (rc != ECCO_OK) return rc;
+        hipLaunchKernelGGL(kernel, dim3(grid), dim3(kDecThreads), lds, static_cast<hipStream_t>(stream), m->dev, m->S,
+                           static_cast<const uint4*>(blocks), meta, n_groups, dst);
+        ECCO_HIP_CHECK(hipGetLastError());
+        return ECCO_OK;
+    };
+    if (indices) return lng ? launch(decode_kernel<true, true>) : launch(decode_kernel<false, true>);
+    return lng ? launch(decode_kernel<true, false>) : launch(decode_kernel<false, false>);
 }
 
 int ecco_decode(const ecco_model* m, const void* blocks, const uint32_t* meta, size_t n_groups, uint16_t* dst, void* stream) {
@@ -569,17 +626,31 @@ int ecco_decode_gemv(const ecco_model* m, const void* blocks, const uint32_t* me
     if (model_ready(m) != ECCO_OK) return ECCO_EINVAL;
     if (rows <= 0 || cols <= 0 || cols % kGroup != 0 || cols > 65536 || batch < 1 || batch > 16) return ECCO_ESHAPE;
     if (!aligned(blocks, 64) || !aligned(x, 4) || !aligned(y, 4) || !aligned(meta, 4)) return ECCO_EALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
     const int gpr = cols / kGroup;
-    // rows per workgroup: about two chunks of 256 blocks, at least one row
-    int rows_per_wg = std::max(1, std::min(kThreads, (2 * kThreads) / gpr));
-    int grid = (rows + rows_per_wg - 1) / rows_per_wg;
-    size_t lds = kDecodeLdsBytes + (size_t)kSlabGroups * kXStride * 4 + kThreads * 4;
-    int rc = allow_lds(gemv_rows_kernel, lds);
+    const int row_tiles = (rows + kTileRows - 1) / kTileRows;
+    const int col_tiles = (gpr + kTileGroups - 1) / kTileGroups;
+    // split the column tiles of a row tile over several workgroups until the chip is covered
+    const int cus = cu_count(m->device);
+    int split = std::max(1, std::min(col_tiles, (cus + row_tiles - 1) / row_tiles));
+    const size_t lds = gemv_lds_bytes(m->S);
+    const bool lng = m->max_len > kPeekBits;
+    int rc = lng ? allow_lds(gemv_kernel<true>, lds) : allow_lds(gemv_kernel<false>, lds);
     if (rc != ECCO_OK) return rc;
+    if (split > 1) {
+        const size_t n = (size_t)batch * rows;
+        hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)std::min<size_t>((n + 255) / 256, 1024)), dim3(256), 0, st, y, n);
+        ECCO_HIP_CHECK(hipGetLastError());
+    }
     for (int b = 0; b < batch; ++b) {
-        hipLaunchKernelGGL(gemv_rows_kernel, dim3(grid), dim3(kThreads), lds, static_cast<hipStream_t>(stream), m->dev, m->S,
-                           static_cast<const uint4*>(blocks), meta, rows, gpr, rows_per_wg,
-                           reinterpret_cast<const uint32_t*>(x + (size_t)b * cols), y + (size_t)b * rows);
+        const uint32_t* xb = reinterpret_cast<const uint32_t*>(x + (size_t)b * cols);
+        float* yb = y + (size_t)b * rows;
+        if (lng)
+            hipLaunchKernelGGL(gemv_kernel<true>, dim3(row_tiles * split), dim3(kGemvThreads), lds, st, m->dev, m->S,
+                               static_cast<const uint4*>(blocks), meta, rows, gpr, split, xb, yb);
+        else
+            hipLaunchKernelGGL(gemv_kernel<false>, dim3(row_tiles * split), dim3(kGemvThreads), lds, st, m->dev, m->S,
+                               static_cast<const uint4*>(blocks), meta, rows, gpr, split, xb, yb);
         ECCO_HIP_CHECK(hipGetLastError());
     }
     return ECCO_OK;
@@ -593,8 +664,9 @@ int ecco_kv_append(const ecco_model* mk, const ecco_model* mv, const uint16_t* k
     if (B <= 0 || H <= 0 || T_max <= 0) return ECCO_ESHAPE;
     if (!aligned(k_blocks, 64) || !aligned(v_blocks, 64) || !aligned(k_new, 4) || !aligned(v_new, 4)) return ECCO_EALIGN;
     dim3 grid((B * H + kEncWaves - 1) / kEncWaves, 2);
-    hipLaunchKernelGGL(kv_append_kernel, grid, dim3(kThreads), kEncLdsBytes, static_cast<hipStream_t>(stream), mk->dev, mk->S,
-                       mv->dev, mv->S, reinterpret_cast<const uint32_t*>(k_new), reinterpret_cast<const uint32_t*>(v_new),
+    hipLaunchKernelGGL(kv_append_kernel, grid, dim3(kEncThreads), enc_lds_bytes(std::max(mk->S, mv->S)),
+                       static_cast<hipStream_t>(stream), mk->dev, mk->S, mv->dev, mv->S,
+                       reinterpret_cast<const uint32_t*>(k_new), reinterpret_cast<const uint32_t*>(v_new),
                        static_cast<uint32_t*>(k_blocks), k_meta, static_cast<uint32_t*>(v_blocks), v_meta, seq_len, B, H, T_max);
     ECCO_HIP_CHECK(hipGetLastError());
     return ECCO_OK;
@@ -607,13 +679,19 @@ int ecco_kv_attend(const ecco_model* mk, const ecco_model* mv, const uint16_t* q
     if (model_ready(mk) != ECCO_OK || model_ready(mv) != ECCO_OK || mk->device != mv->device) return ECCO_EINVAL;
     if (B <= 0 || H <= 0 || T_max <= 0) return ECCO_ESHAPE;
     if (!aligned(k_blocks, 64) || !aligned(v_blocks, 64) || !aligned(q, 2) || !aligned(out, 4)) return ECCO_EALIGN;
-    int rc = allow_lds(kv_attend_kernel, kAttnLdsBytes);
-    if (rc != ECCO_OK) return rc;
-    hipLaunchKernelGGL(kv_attend_kernel, dim3(B * H), dim3(kThreads), kAttnLdsBytes, static_cast<hipStream_t>(stream), mk->dev,
-                       mk->S, mv->dev, mv->S, q, static_cast<const uint4*>(k_blocks), k_meta, static_cast<const uint4*>(v_blocks),
-                       v_meta, seq_len, H, T_max, out);
-    ECCO_HIP_CHECK(hipGetLastError());
-    return ECCO_OK;
+    const size_t lds = attn_lds_bytes(mk->S, mv->S);
+    const bool lk = mk->max_len > kPeekBits, lv = mv->max_len > kPeekBits;
+    auto launch = [&](auto kernel) -> int {
+        int rc = allow_lds(kernel, lds);
+        if (rc != ECCO_OK) return rc;
+        hipLaunchKernelGGL(kernel, dim3(B * H), dim3(kAttnThreads), lds, static_cast<hipStream_t>(stream), mk->dev, mk->S, mv->dev,
+                           mv->S, q, static_cast<const uint4*>(k_blocks), k_meta, static_cast<const uint4*>(v_blocks), v_meta,
+                           seq_len, H, T_max, out);
+        ECCO_HIP_CHECK(hipGetLastError());
+        return ECCO_OK;
+    };
+    if (lk) return lv ? launch(kv_attend_kernel<true, true>) : launch(kv_attend_kernel<true, false>);
+    return lv ? launch(kv_attend_kernel<false, true>) : launch(kv_attend_kernel<false, false>);
 }
 
 }  // extern "C"

@@ -49,21 +49,16 @@ void derive_codes(ecco_model* m) {
             m->codes[p * kK + order[j]] = (uint16_t)code;
         }
     }
+    m->max_len = 0;
+    for (int i = 0; i < m->S * kK; ++i) m->max_len = std::max<int>(m->max_len, m->lens[i]);
 }
 
-static uint32_t reverse_bits(uint32_t v, int n) {
-    uint32_t r = 0;
-    for (int i = 0; i < n; ++i) r |= ((v >> i) & 1u) << (n - 1 - i);
-    return r;
-}
-
-// First symbol whose code is a prefix of the stream bits in `peek` (first stream bit in bit 0),
-// looking at `avail` bits only.  Returns the index or -1.
-static int match_prefix(const ecco_model* m, int p, uint32_t peek, int avail, int* len) {
+// Index whose code is a prefix of the top bits of `peek` (a kPeekBits-bit value, first stream bit
+// most significant), or -1 when that code is longer than the peek.
+static int match_prefix(const ecco_model* m, int p, uint32_t peek, int* len) {
     for (int k = 0; k < kK; ++k) {
         int l = m->lens[p * kK + k];
-        if (l > avail) continue;
-        if ((peek & ((1u << l) - 1u)) == reverse_bits(m->codes[p * kK + k], l)) {
+        if (l <= kPeekBits && (peek >> (kPeekBits - l)) == m->codes[p * kK + k]) {
             *len = l;
             return k;
         }
@@ -74,15 +69,11 @@ static int match_prefix(const ecco_model* m, int p, uint32_t peek, int avail, in
 void build_device_image(const ecco_model* m, unsigned char* img) {
     std::memset(img, 0, DevLayout::total);
     std::memcpy(img + DevLayout::cent, m->cent, sizeof(uint16_t) * m->S * kK);
-    uint8_t* lut8 = img + DevLayout::lut8;
-    uint32_t* longtab = reinterpret_cast<uint32_t*>(img + DevLayout::longtab);
     uint32_t* enc = reinterpret_cast<uint32_t*>(img + DevLayout::enc);
-    uint16_t* pair = reinterpret_cast<uint16_t*>(img + DevLayout::pair);
+    uint32_t* longtab = reinterpret_cast<uint32_t*>(img + DevLayout::longtab);
+    uint32_t* rawlut = reinterpret_cast<uint32_t*>(img + DevLayout::rawlut);
+    uint32_t* lut = reinterpret_cast<uint32_t*>(img + DevLayout::lut);
     for (int p = 0; p < m->S; ++p) {
-        for (uint32_t v = 0; v < 256; ++v) {
-            int l = 0, k = match_prefix(m, p, v, kPeekBits, &l);
-            lut8[p * 256 + v] = (k < 0) ? 0 : (uint8_t)((l << 4) | k);
-        }
         int order[kK];
         canonical_order(&m->lens[p * kK], order);
         for (int j = 0; j < kK; ++j) {
@@ -90,23 +81,14 @@ void build_device_image(const ecco_model* m, unsigned char* img) {
             longtab[p * kK + j] = ((uint32_t)m->codes[p * kK + k] << (kMaxLen - l)) | ((uint32_t)k << 12) | ((uint32_t)l << 16);
         }
         for (int k = 0; k < kK; ++k) {
-            int l = m->lens[p * kK + k];
-            enc[p * kK + k] = reverse_bits(m->codes[p * kK + k], l) | ((uint32_t)l << 16);
+            enc[p * kK + k] = (uint32_t)m->codes[p * kK + k] | ((uint32_t)m->lens[p * kK + k] << 16);
+            rawlut[p * kK + k] = ((uint32_t)m->cent[p * kK + k] << 16) | ((uint32_t)k << 8) | 4u;
         }
-        for (uint32_t v = 0; v < (1u << kPairBits); ++v) {
-            int l1 = 0, k1 = match_prefix(m, p, v, kPairBits, &l1);
-            uint16_t e = 0;
-            if (k1 >= 0) {
-                int l2 = 0, k2 = match_prefix(m, p, v >> l1, kPairBits - l1, &l2);
-                if (k2 >= 0) e = (uint16_t)(k1 | (k2 << 4) | ((l1 + l2) << 8) | (2 << 12));
-                else e = (uint16_t)(k1 | (l1 << 8) | (1 << 12));
-            }
-            pair[(size_t)p * (1u << kPairBits) + v] = e;
+        for (uint32_t v = 0; v < (uint32_t)kPeekEntries; ++v) {
+            int l = 0, k = match_prefix(m, p, v, &l);
+            lut[p * kPeekEntries + v] = (k < 0) ? 0u : (((uint32_t)m->cent[p * kK + k] << 16) | ((uint32_t)k << 8) | (uint32_t)l);
         }
     }
-    for (uint32_t v = 0; v < 256; ++v) lut8[kRawSlot * 256 + v] = (uint8_t)((4 << 4) | (v & 15));
-    for (uint32_t v = 0; v < (1u << kPairBits); ++v)
-        pair[(size_t)kRawSlot * (1u << kPairBits) + v] = (uint16_t)((v & 0xFF) | (8 << 8) | (2 << 12));
 }
 
 }  // namespace ecco

@@ -110,13 +110,22 @@ def kv_cache(batch: int, heads: int, tokens: int, head_dim: int, seed: int, toke
     k = np.empty((batch, heads, tokens, head_dim), dtype=np.float16)
     v = np.empty((batch, heads, tokens, head_dim), dtype=np.float16)
     big_t = 1 << 20  # counter stride per (b, h): far above any token count used
-    for b in range(batch):
-        for h in range(heads):
-            start = ((b * heads + h) * big_t + token_start) * head_dim
-            zk = normal(seed, 1, start, tokens * head_dim).reshape(tokens, head_dim)
-            zv = normal(seed, 2, start, tokens * head_dim).reshape(tokens, head_dim)
-            k[b, h] = (zk * a[0, h]).astype(np.float16)
-            v[b, h] = zv.astype(np.float16)
+
+    def fill(bh):
+        b, h = divmod(bh, heads)
+        start = ((b * heads + h) * big_t + token_start) * head_dim
+        zk = normal(seed, 1, start, tokens * head_dim).reshape(tokens, head_dim)
+        zv = normal(seed, 2, start, tokens * head_dim).reshape(tokens, head_dim)
+        k[b, h] = (zk * a[0, h]).astype(np.float16)
+        v[b, h] = zv.astype(np.float16)
+
+    if batch * heads * tokens >= 4096:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as ex:
+            list(ex.map(fill, range(batch * heads)))
+    else:
+        for bh in range(batch * heads):
+            fill(bh)
     return k, v
 
 

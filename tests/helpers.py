@@ -48,8 +48,18 @@ def round_fraction_to_half(v: Fraction) -> int:
 
 
 def stream_bits(block_u8: np.ndarray) -> np.ndarray:
-    """512 stream bits of one 64-byte block: stream bit j = bit (j & 7) of byte (j >> 3)."""
-    return np.unpackbits(np.asarray(block_u8, np.uint8), bitorder="little")
+    """512 stream bits of one 64-byte block: 16 little-endian words, most significant bit of each first."""
+    words = np.asarray(block_u8, np.uint8).view("<u4")
+    return ((words[:, None] >> np.arange(31, -1, -1, dtype=np.uint32)[None, :]) & 1).astype(np.uint8).reshape(-1)
+
+
+def pack_raw(idx: np.ndarray) -> np.ndarray:
+    """Raw-mode payload of 128 indices: value i in stream bits 4i..4i+3, top bit first."""
+    idx = np.asarray(idx, np.uint32).reshape(16, 8)
+    words = np.zeros(16, np.uint32)
+    for j in range(8):
+        words |= idx[:, j] << np.uint32(28 - 4 * j)
+    return words.astype("<u4").view(np.uint8)
 
 
 def py_canonical(lens):

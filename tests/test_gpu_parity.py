@@ -14,6 +14,7 @@ torch = pytest.importorskip("torch")
 
 import paper_2505_06901_amd as E  # noqa: E402
 from paper_2505_06901_amd import workloads as W  # noqa: E402
+from helpers import pack_raw  # noqa: E402
 
 REL_L2 = 1e-3
 
@@ -178,8 +179,7 @@ def test_dequant_every_scale(dev, oracle):
     m = E.ecco_model_to_device(E.ecco_model_create(cent, lens), 0)
     scales = np.arange(0, 0x7C00, dtype=np.uint32)
     nib = np.arange(128) % 16
-    block = (nib[0::2] | (nib[1::2] << 4)).astype(np.uint8)
-    blocks = np.tile(block, (scales.size, 1))
+    blocks = np.tile(pack_raw(nib), (scales.size, 1))
     meta = (scales | (1 << 22)).astype(np.uint32)
     dec = E.ecco_decode(m, tu8(blocks, dev), ti32(meta, dev)).cpu().numpy().view(np.uint16)
     assert np.array_equal(dec, oracle.decode(cent.view(np.uint16), lens, blocks, meta))
@@ -292,9 +292,12 @@ def _full_weight_case(dev, oracle, name, which, rows_limit=None, n_sample=1536, 
     oidx, _ = oracle.decode_indices(m.code_lens, m.S, ob, om)
     assert np.array_equal(idx[gsel_t].cpu().numpy(), oidx)
     assert np.array_equal(dec[gsel_t].cpu().numpy().view(np.uint16), oracle.decode(m.centroids, m.code_lens, ob, om))
-    # properties that hold at any size: meta reserved bits zero, pattern ids in range, indices in range
+    # properties that hold at any size: pattern ids in range, second-chain start within the block and
+    # equal to 256 exactly for raw blocks, indices in range
     mu = np_meta(meta)
-    assert (mu >> 23).max() == 0 and ((mu >> 16) & 63).max() < m.S
+    assert ((mu >> 16) & 63).max() < m.S
+    israw = ((mu >> 22) & 1) == 1
+    assert ((mu >> 23)[israw] == 256).all() and (mu >> 23).max() < 512 - 64
     assert int(idx.max()) < 16
     for batch in batches:
         x = W.activation(batch, cols, c["x_seed"])

@@ -11,7 +11,7 @@ from fractions import Fraction
 import numpy as np
 import pytest
 
-from helpers import half_to_fraction, py_canonical, round_fraction_to_half, stream_bits
+from helpers import half_to_fraction, pack_raw, py_canonical, round_fraction_to_half, stream_bits
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
@@ -118,8 +118,7 @@ def test_dequant_all_scales_through_decode(oracle):
     scales = np.arange(0, 0x7C00, dtype=np.uint32)
     n = scales.size
     nib = np.arange(128) % 16
-    block = (nib[0::2] | (nib[1::2] << 4)).astype(np.uint8)
-    blocks = np.tile(block, (n, 1))
+    blocks = np.tile(pack_raw(nib), (n, 1))
     meta = scales | (1 << 22)
     got = oracle.decode(cent.view(np.uint16), lens, blocks, meta)
     prod = cent.astype(np.float32)[0][nib][None, :] * scales.astype(np.uint16).view(np.float16).astype(np.float32)[:, None]
@@ -334,7 +333,7 @@ def test_sse_tree_order(oracle):
 
 def test_uniform_special_case_is_absmax_int4(oracle):
     """S = 1, equidistant centroids, all code lengths 4: Ecco degenerates to symmetric absmax 4-bit
-    round-to-nearest, and the Huffman payload is the raw payload with every nibble bit-reversed."""
+    round-to-nearest, and the Huffman payload is the raw payload bit for bit."""
     cent = (-1 + 2 * np.arange(16) / 15.0).astype(np.float16)[None, :]
     lens = np.full((1, 16), 4, np.uint8)
     rng = np.random.default_rng(8)
@@ -349,15 +348,16 @@ def test_uniform_special_case_is_absmax_int4(oracle):
     rtn = np.clip(np.floor(t + 0.5), 0, 15).astype(np.uint8)
     assert np.array_equal(idx[~near_tie], rtn[~near_tie])
     assert np.array_equal(meta & 0xFFFF, np.abs(x).max(axis=1).view(np.uint16))
-    # payload: stream nibble i holds the 4-bit canonical code (= index) first bit first
+    # payload: stream nibble i holds the 4-bit canonical code (= index), first bit first ...
     for g in range(40):
         bits = stream_bits(blocks[g]).reshape(128, 4)
         val = bits[:, 0] * 8 + bits[:, 1] * 4 + bits[:, 2] * 2 + bits[:, 3]
         assert np.array_equal(val, idx[g])
-    # the same indices in raw mode are a plain little-endian nibble array
+        # ... which is bit for bit the raw-mode payload of the same indices
+        assert np.array_equal(blocks[g], pack_raw(idx[g]))
+    assert ((meta >> 23) == 256).all()  # value 64 starts at bit 256
     raw_meta = meta | (1 << 22)
-    packed = (idx[:, 0::2] | (idx[:, 1::2] << 4)).astype(np.uint8)
-    idx2, used2 = oracle.decode_indices(lens, 1, packed, raw_meta)
+    idx2, used2 = oracle.decode_indices(lens, 1, blocks, raw_meta)
     assert np.array_equal(idx2, idx) and (used2 == 512).all()
 
 
@@ -401,18 +401,18 @@ def test_roundtrip_indices_and_padding(oracle, tiny):
     n_raw = 0
     for g in range(x.shape[0]):
         s, p, qidx, _ = oracle.quantize_group(cent, x[g])
-        assert (meta[g] & 0xFFFF) == s and ((meta[g] >> 16) & 63) == p and (meta[g] >> 23) == 0
+        assert (meta[g] & 0xFFFF) == s and ((meta[g] >> 16) & 63) == p
         assert np.array_equal(idx[g], qidx)           # index-level bit-exact round trip
         total = int(lens[p][qidx].sum())
         bits = stream_bits(blocks[g])
         if (meta[g] >> 22) & 1:
             n_raw += 1
             assert total > 512                        # raw only on overflow
-            packed = (qidx[0::2] | (qidx[1::2] << 4)).astype(np.uint8)
-            assert np.array_equal(blocks[g], packed)  # textbook nibble packing
-            assert used[g] == 512
+            assert np.array_equal(blocks[g], pack_raw(qidx))  # plain nibble packing
+            assert used[g] == 512 and (meta[g] >> 23) == 256
         else:
             assert total <= 512 and used[g] == total
+            assert (meta[g] >> 23) == int(lens[p][qidx[:64]].sum())  # where value 64 starts
             assert not bits[total:].any()             # padding is zero
             want = "".join(format(codes[p][k], "b").zfill(int(lens[p][k])) for k in qidx)
             assert "".join(map(str, bits[:total])) == want
