@@ -24,14 +24,23 @@ constexpr int kBlockWords = ECCO_BLOCK_BYTES / 4;
 constexpr int kPeekBits = 8;
 constexpr int kPeekEntries = 1 << kPeekBits;
 
-// Device tables, one allocation; offsets in bytes.
+// Device memory of a model, one allocation, in 32-bit words:
+//   compact tables  [enc S x 16][centroids S x 8][longtab S x 16]   (a few KB; kernels expand them in LDS)
+//   workspace       partial sums of split fused-GEMV launches and their arrival counters
+// The decode table itself (S x 256 entries) is never stored in global memory: every workgroup
+// builds it in LDS from `enc` and the centroids, which costs less than fetching 64 KB per workgroup.
+constexpr int kWsCounters = 1024;
+constexpr size_t kWsFloats = 16 * 64 * 512;  // batch 16 x 64 rows x (row tiles x split <= 512)
 struct DevLayout {
-    static constexpr size_t cent = 0;                                        // half [kMaxS][16]
-    static constexpr size_t enc = cent + kMaxS * kK * 2;                     // u32  [kMaxS][16]
-    static constexpr size_t longtab = enc + kMaxS * kK * 4;                  // u32  [kMaxS][16]
-    static constexpr size_t rawlut = longtab + kMaxS * kK * 4;               // u32  [kMaxS][16]
-    static constexpr size_t lut = rawlut + kMaxS * kK * 4;                   // u32  [kMaxS][256]
-    static constexpr size_t total = lut + (size_t)kMaxS * kPeekEntries * 4;
+    int S;
+    constexpr size_t enc() const { return 0; }
+    constexpr size_t cent() const { return (size_t)S * kK; }
+    constexpr size_t longtab() const { return cent() + (size_t)S * kK / 2; }
+    constexpr size_t table_words() const { return longtab() + (size_t)S * kK; }
+    constexpr size_t ws_counter() const { return (table_words() + 63) / 64 * 64; }
+    constexpr size_t ws_partial() const { return ws_counter() + kWsCounters; }
+    constexpr size_t image_words() const { return ws_partial(); }  // what the host image holds (workspace excluded)
+    constexpr size_t total_bytes() const { return (ws_partial() + kWsFloats) * 4; }
 };
 
 // longtab entry j (canonical position j): bits 11:0 the code left-aligned in 12 bits,
@@ -47,7 +56,7 @@ struct ecco_model {
     uint16_t codes[ecco::kMaxS * ecco::kK] = {};  // canonical codes, derived from lens
     int device = -1;
     int max_len = 0;               // longest code length in the model
-    unsigned char* dev = nullptr;  // DevLayout::total bytes on `device`
+    uint32_t* dev = nullptr;       // DevLayout{S}.total_bytes() on `device`
 };
 
 namespace ecco {
@@ -55,8 +64,8 @@ namespace ecco {
 // validation shared by create / load; returns ECCO_OK or ECCO_EFORMAT
 int validate_tables(const uint16_t* cent, const uint8_t* lens, int S);
 void derive_codes(ecco_model* m);
-// fills a host image of the device tables (DevLayout::total bytes)
-void build_device_image(const ecco_model* m, unsigned char* img);
+// fills a host image of the device tables (DevLayout{S}.image_words() words; counters zero)
+void build_device_image(const ecco_model* m, uint32_t* img);
 
 // host-side half conversion helpers (compiler-provided _Float16 arithmetic)
 inline float half_bits_to_float(uint16_t h) {

@@ -39,29 +39,83 @@ struct Tables {
     const uint32_t* longtab;  // [S][16]
     const __half* cent;       // [S][16]
 };
-__host__ __device__ constexpr size_t table_words(int S) { return (size_t)S * (kPeekEntries + kK + kK + kK / 2); }
+__host__ __device__ constexpr size_t table_words(int S) { return (size_t)S * (kPeekEntries + kK + kK + kK / 2); }  // LDS words of a model's decode tables
 
-__device__ inline void stage_words(uint32_t* dst, const void* src, int words) {
-    const uint32_t* s = static_cast<const uint32_t*>(src);
-    for (int i = threadIdx.x; i < words; i += blockDim.x) dst[i] = s[i];
+// copies `words` (a multiple of 4; both sides 16-byte aligned) from global memory to LDS with all
+// threads of the workgroup, four 16-byte loads in flight per thread
+__device__ inline void stage_vec(uint32_t* dst, const uint32_t* __restrict__ src, int words) {
+    const uint4* s = reinterpret_cast<const uint4*>(src);
+    uint4* d = reinterpret_cast<uint4*>(dst);
+    const int n = words >> 2, step = blockDim.x;
+    for (int i = threadIdx.x; i < n; i += 4 * step) {
+        uint4 v0, v1, v2, v3;
+        const int i1 = i + step, i2 = i + 2 * step, i3 = i + 3 * step;
+        v0 = s[i];
+        if (i1 < n) v1 = s[i1];
+        if (i2 < n) v2 = s[i2];
+        if (i3 < n) v3 = s[i3];
+        d[i] = v0;
+        if (i1 < n) d[i1] = v1;
+        if (i2 < n) d[i2] = v2;
+        if (i3 < n) d[i3] = v3;
+    }
 }
 
-// copies the model's decode tables to LDS at `base`; the caller synchronises afterwards
-__device__ inline Tables stage_tables(uint32_t* base, const unsigned char* dev, int S) {
+// Building the decode tables of a model in LDS from the compact tables in global memory.  Item
+// (p, k) is index k of pattern p: its code of length l <= 8 is the prefix of 2^(8-l) consecutive
+// 8-bit peeks, which all get the entry (centroid, index, length); a longer code marks its single
+// 8-bit prefix with 0.  The two global loads of an item are split from the LDS writes so that a
+// kernel can issue them first, put its payload loads behind them, and build the tables while the
+// payload is still on its way.
+struct TableItem {
+    uint32_t enc, cent;
+};
+__device__ __forceinline__ TableItem load_table_item(const uint32_t* __restrict__ dev, int S, int t) {
+    const DevLayout D{S};
+    TableItem it;
+    it.enc = dev[D.enc() + t];
+    it.cent = reinterpret_cast<const uint16_t*>(dev + D.cent())[t];
+    return it;
+}
+__device__ __forceinline__ void build_table_item(uint32_t* base, int S, int t, TableItem it) {
     uint32_t* lut = base;
     uint32_t* rawlut = lut + S * kPeekEntries;
-    uint32_t* longtab = rawlut + S * kK;
-    uint32_t* cent = longtab + S * kK;
-    stage_words(lut, dev + DevLayout::lut, S * kPeekEntries);
-    stage_words(rawlut, dev + DevLayout::rawlut, S * kK);
-    stage_words(longtab, dev + DevLayout::longtab, S * kK);
-    stage_words(cent, dev + DevLayout::cent, S * kK / 2);
-    Tables t;
-    t.lut = lut;
-    t.rawlut = rawlut;
-    t.longtab = longtab;
-    t.cent = reinterpret_cast<const __half*>(cent);
-    return t;
+    const uint32_t code = it.enc & 0xFFFFu, len = it.enc >> 16, k = (uint32_t)t & (kK - 1);
+    const uint32_t value = (it.cent << 16) | (k << 8);
+    rawlut[t] = value | 4u;
+    uint32_t* row = lut + (t / kK) * kPeekEntries;
+    if (len > (uint32_t)kPeekBits) {
+        row[code >> (len - kPeekBits)] = 0u;  // several long codes may share this prefix: same value
+    } else {
+        const uint32_t entry = value | len, n = 1u << (kPeekBits - len);
+        uint32_t* dst = row + (code << (kPeekBits - len));
+        if (n >= 4) {
+            // neighbouring items start their runs at different offsets: all rows begin on the same LDS
+            // bank and equal-length codes are a multiple of the run length apart, so without the
+            // rotation the 64 items of a wavefront would write to a handful of banks at a time
+            const uint4 v = make_uint4(entry, entry, entry, entry);
+            const uint32_t rot = ((uint32_t)t + ((uint32_t)t >> 4) + (code >> 2)) * 4u;
+            for (uint32_t j = 0; j < n; j += 4) *reinterpret_cast<uint4*>(dst + ((j + rot) & (n - 1))) = v;
+        } else {
+            for (uint32_t j = 0; j < n; ++j) dst[j] = entry;
+        }
+    }
+}
+__device__ __forceinline__ Tables table_pointers(uint32_t* base, int S) {
+    Tables tb;
+    tb.lut = base;
+    tb.rawlut = base + S * kPeekEntries;
+    tb.longtab = base + S * (kPeekEntries + kK);
+    tb.cent = reinterpret_cast<const __half*>(base + S * (kPeekEntries + 2 * kK));
+    return tb;
+}
+// the whole job with all threads of the workgroup; the caller synchronises afterwards
+__device__ inline Tables stage_tables(uint32_t* base, const uint32_t* __restrict__ dev, int S) {
+    const DevLayout D{S};
+    for (int t = threadIdx.x; t < S * kK; t += blockDim.x) build_table_item(base, S, t, load_table_item(dev, S, t));
+    stage_vec(base + S * (kPeekEntries + kK), dev + D.longtab(), S * kK);
+    stage_vec(base + S * (kPeekEntries + 2 * kK), dev + D.cent(), S * kK / 2);
+    return table_pointers(base, S);
 }
 
 // what one lane needs to decode one chain
@@ -103,9 +157,12 @@ __device__ __forceinline__ void decode_chain(const uint32_t* w, uint32_t start, 
     wp += 2;
     uint32_t next = wp < wend ? *wp : 0u;
     constexpr int kCheck = kLong ? 2 : 4;
+    uint32_t used = 0;  // sum of the entries since the last check; its low byte is the number of bits consumed
 #pragma unroll
     for (int i = 0; i < kCount; ++i) {
         if (i > 0 && i % kCheck == 0) {
+            valid -= (int)(used & 0xFFu);
+            used = 0;
             if (valid <= 32) {
                 win |= (uint64_t)next << (32 - valid);
                 valid += 32;
@@ -126,9 +183,8 @@ __device__ __forceinline__ void decode_chain(const uint32_t* w, uint32_t start, 
             }
         }
         sink(i, e);
-        const uint32_t len = e & 0xFFu;
-        win <<= len;
-        valid -= (int)len;
+        used += e;  // lengths add up in the low byte (at most 4 x 12), the rest is ignored
+        win <<= (e & 0xFFu);
     }
 }
 
@@ -152,7 +208,7 @@ constexpr int kDecBlocks = kDecThreads / 2;  // blocks per tile: two lanes per b
 inline size_t decode_lds_bytes(int S) { return (table_words(S) + (size_t)kDecBlocks * kStride) * 4; }
 
 template <bool kLong, bool kIndices>
-__global__ __launch_bounds__(kDecThreads) void decode_kernel(const unsigned char* __restrict__ dev, int S,
+__global__ __launch_bounds__(kDecThreads) void decode_kernel(const uint32_t* __restrict__ dev, int S,
                                                              const uint4* __restrict__ blocks, const uint32_t* __restrict__ meta,
                                                              size_t n_groups, void* __restrict__ dst) {
     extern __shared__ __align__(16) uint32_t smem[];
@@ -201,57 +257,103 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(const unsigned char
 // ---- ecco_decode_gemv, batch row by batch row ------------------------------------------------------------
 // Tile = 64 rows x 8 column groups = 512 blocks; 16 wavefronts: wavefront (c, h) decodes half h of
 // column group c for the 64 rows, lane = row.  x[i] is then uniform over the wavefront and comes
-// from scalar registers.  A workgroup (row tile, split k) walks the column tiles k, k + split, ...;
-// each lane keeps the running dot product of its row; the 16 wavefronts are added in LDS in a
-// fixed order.  With split > 1 the per-split sums are added to y with atomics (y zeroed first).
+// from scalar registers.  A workgroup (row tile, split k) walks the column tiles k, k + split, ...
+// (the next tile's payload is already in flight while the current one is decoded); each lane keeps
+// the running dot product of its row; the 16 wavefronts are added in LDS in a fixed order.  With
+// split > 1 every workgroup leaves its 64 sums in the model's workspace and the last one to arrive
+// (an arrival counter per row tile) adds them in split order and writes y: one launch, no atomics
+// on y, and the same bits on every run.
 constexpr int kGemvThreads = 1024;
 constexpr int kTileRows = 64;
 constexpr int kTileGroups = 8;
 constexpr int kTileBlocks = kTileRows * kTileGroups;
-inline size_t gemv_lds_bytes(int S) { return (table_words(S) + (size_t)kTileBlocks * kStride + 16 * 64) * 4; }
+constexpr int kMaxWsTiles = (int)(kWsFloats / 16 / kTileRows);  // row tiles x split that fit the workspace
+inline size_t gemv_lds_bytes(int S) { return (table_words(S) + (size_t)kTileBlocks * kStride + 16 * 64 + 4) * 4; }
 
-__global__ void fill_zero_kernel(float* __restrict__ p, size_t n) {
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0.0f;
+// The payload of a tile is fetched by the first kLoaders threads (wavefronts 0..7), four 16-byte
+// pieces each; the other wavefronts build the decode tables meanwhile.  Loads of one wavefront
+// return in issue order, so keeping the two jobs in different wavefronts lets the table build
+// proceed while the payload is still on its way from HBM.
+constexpr int kLoaders = 512;
+constexpr int kPiecesPerLoader = kTileBlocks * 4 / kLoaders;
+struct TileLoad {
+    uint4 v[kPiecesPerLoader];
+};
+// this thread's pieces of tile (row_tile, ct); pieces outside the matrix are zero
+__device__ __forceinline__ TileLoad load_tile(const uint4* __restrict__ blocks, int rows, int gpr, int row_tile, int ct) {
+    TileLoad t;
+#pragma unroll
+    for (int j = 0; j < kPiecesPerLoader; ++j) {
+        const int q = threadIdx.x + j * kLoaders;
+        const int r = q >> 5, c = (q >> 2) & 7, piece = q & 3;
+        const int gr = min(row_tile * kTileRows + r, rows - 1), gc = ct * kTileGroups + c;
+        t.v[j] = gc < gpr ? blocks[((size_t)gr * gpr + gc) * 4 + piece] : make_uint4(0, 0, 0, 0);
+    }
+    return t;
+}
+__device__ __forceinline__ void store_tile(uint32_t* payload, const TileLoad& t) {
+#pragma unroll
+    for (int j = 0; j < kPiecesPerLoader; ++j) {
+        const int q = threadIdx.x + j * kLoaders;
+        const int r = q >> 5, c = (q >> 2) & 7, piece = q & 3;
+        uint32_t* d = payload + (c * kTileRows + r) * kStride + piece * 4;
+        d[0] = t.v[j].x; d[1] = t.v[j].y; d[2] = t.v[j].z; d[3] = t.v[j].w;
+    }
 }
 
 template <bool kLong>
-__global__ __launch_bounds__(kGemvThreads) void gemv_kernel(const unsigned char* __restrict__ dev, int S,
+__global__ __launch_bounds__(kGemvThreads) void gemv_kernel(const uint32_t* __restrict__ dev, int S,
                                                             const uint4* __restrict__ blocks, const uint32_t* __restrict__ meta,
                                                             int rows, int gpr, int split,
-                                                            const uint32_t* __restrict__ x, float* __restrict__ y) {
+                                                            const uint32_t* __restrict__ x, float* __restrict__ y,
+                                                            float* __restrict__ ws_partial, int* __restrict__ ws_counter) {
     extern __shared__ __align__(16) uint32_t smem[];
-    const Tables T = stage_tables(smem, dev, S);
-    uint32_t* payload = smem + table_words(S);
-    float* part = reinterpret_cast<float*>(payload + kTileBlocks * kStride);
-    zero_pads(payload, kTileBlocks);
-
     const int row_tile = blockIdx.x / split, k0 = blockIdx.x % split;
+    const int col_tiles = (gpr + kTileGroups - 1) / kTileGroups;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const bool loader = wave < kLoaders / 64;
     const int cgl = wave >> 1, half = wave & 1;
     const int row = min(row_tile * kTileRows + lane, rows - 1);  // lanes past the last row repeat it; their sums are dropped
-    const int col_tiles = (gpr + kTileGroups - 1) / kTileGroups;
+    uint32_t* payload = smem + table_words(S);
+    float* part = reinterpret_cast<float*>(payload + kTileBlocks * kStride);
+    TileLoad pre;
+    if (loader) {
+        pre = load_tile(blocks, rows, gpr, row_tile, k0);
+    } else {
+        for (int t = threadIdx.x - kLoaders; t < S * kK; t += kGemvThreads - kLoaders) build_table_item(smem, S, t, load_table_item(dev, S, t));
+        if (kLong) {
+            const DevLayout D{S};
+            for (int i = threadIdx.x - kLoaders; i < S * kK; i += kGemvThreads - kLoaders) smem[S * (kPeekEntries + kK) + i] = dev[D.longtab() + i];
+            for (int i = threadIdx.x - kLoaders; i < S * kK / 2; i += kGemvThreads - kLoaders) smem[S * (kPeekEntries + 2 * kK) + i] = dev[D.cent() + i];
+        }
+    }
+    // the meta word is fetched after the table build: it comes from HBM and would hold up the (cached)
+    // table loads issued behind it
+    uint32_t mw_next = (k0 * kTileGroups + cgl < gpr) ? meta[(size_t)row * gpr + k0 * kTileGroups + cgl] : 0u;
+    const Tables T = table_pointers(smem, S);
+    zero_pads(payload, kTileBlocks);
     float total = 0.0f;
     for (int ct = k0; ct < col_tiles; ct += split) {
-        __syncthreads();
-        // stage 64 rows x 8 column groups: per row a 512-byte run (or less at the ragged edge)
-        for (int q = threadIdx.x; q < kTileBlocks * 4; q += kGemvThreads) {
-            const int r = q >> 5, c = (q >> 2) & 7, part16 = q & 3;
-            const int gr = min(row_tile * kTileRows + r, rows - 1), gc = ct * kTileGroups + c;
-            if (gc < gpr) {
-                uint4 v = blocks[((size_t)gr * gpr + gc) * 4 + part16];
-                uint32_t* d = payload + (c * kTileRows + r) * kStride + part16 * 4;
-                d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
-            }
-        }
-        __syncthreads();
+        __syncthreads();  // the previous tile has been consumed
+        if (loader) store_tile(payload, pre);
         const int cg = ct * kTileGroups + cgl;
-        if (cg < gpr) {  // uniform over the wavefront
-            const Lane L = lane_setup(T, meta[(size_t)row * gpr + cg], S);
+        const bool active = cg < gpr;  // uniform over the wavefront
+        const uint32_t mw = mw_next;
+        uint32_t xs[kHalf / 2];
+        if (active) {
             const uint32_t* xw = x + (size_t)cg * (kGroup / 2) + half * (kHalf / 2);
-            uint32_t xs[kHalf / 2];
 #pragma unroll
             for (int j = 0; j < kHalf / 2; ++j) xs[j] = xw[j];
+        }
+        if (ct + split < col_tiles) {
+            const int ncg = (ct + split) * kTileGroups + cgl;
+            mw_next = ncg < gpr ? meta[(size_t)row * gpr + ncg] : 0u;
+            if (loader) pre = load_tile(blocks, rows, gpr, row_tile, ct + split);
+        }
+        __syncthreads();
+        if (active) {
+            const Lane L = lane_setup(T, mw, S);
             float acc = 0.0f;
             decode_chain<kLong, kHalf>(payload + (cgl * kTileRows + lane) * kStride, half ? L.second_start : 0u, L,
                                        [&](int i, uint32_t e) {
@@ -264,13 +366,35 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_kernel(const unsigned char*
     }
     part[wave * 64 + lane] = total;
     __syncthreads();
+    float s = 0.0f;
     if (threadIdx.x < 64) {
-        float s = 0.0f;
 #pragma unroll
         for (int w = 0; w < 16; ++w) s += part[w * 64 + threadIdx.x];
-        const int out_row = row_tile * kTileRows + threadIdx.x;
-        if (out_row < rows) {
-            if (split > 1) atomicAdd(&y[out_row], s); else y[out_row] = s;
+    }
+    const int out_row = row_tile * kTileRows + (int)threadIdx.x;
+    if (split == 1) {
+        if (threadIdx.x < 64 && out_row < rows) y[out_row] = s;
+        return;
+    }
+    // Several workgroups share this row tile: publish, count arrivals, the last one adds up.  The eight
+    // L2 caches of the chip are not coherent with each other inside a kernel, so the partial sums and the
+    // counter travel as device-scope atomics (they bypass L2); ordering comes from completion: the
+    // stores of a wavefront are waited for before its lane 0 bumps the counter, and the reader's loads
+    // are issued only after its own counter update has returned.  No cache-wide flush is involved.
+    if (threadIdx.x < 64) {
+        __hip_atomic_store(&ws_partial[((size_t)row_tile * split + k0) * kTileRows + threadIdx.x], s, __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // waits until the stores above have completed
+        int seen = 0;
+        if (threadIdx.x == 0) seen = __hip_atomic_fetch_add(&ws_counter[row_tile], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        seen = __builtin_amdgcn_readfirstlane(seen);
+        if (seen == split - 1) {
+            float sum = 0.0f;
+            for (int k = 0; k < split; ++k)
+                sum += __hip_atomic_load(&ws_partial[((size_t)row_tile * split + k) * kTileRows + threadIdx.x], __ATOMIC_RELAXED,
+                                         __HIP_MEMORY_SCOPE_AGENT);
+            if (out_row < rows) y[out_row] = sum;
+            if (threadIdx.x == 0) __hip_atomic_store(&ws_counter[row_tile], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // ready for the next launch
         }
     }
 }
@@ -357,13 +481,14 @@ __device__ inline void encode_group(const EncLds& E, int S, uint32_t hx0, uint32
 
 constexpr size_t enc_lds_bytes(int S) { return (size_t)S * kK * 2 + (size_t)S * kK * 4 + (size_t)kEncWaves * ((size_t)S * kK * 4 + kBlockWords * 4); }
 
-__device__ inline EncLds setup_enc_lds(unsigned char* smem, const unsigned char* dev, int S) {
+__device__ inline EncLds setup_enc_lds(unsigned char* smem, const uint32_t* dev, int S) {
+    const DevLayout D{S};
     uint32_t* cent = reinterpret_cast<uint32_t*>(smem);
     uint32_t* enc = cent + S * kK / 2;
     float* recon = reinterpret_cast<float*>(enc + S * kK);
     uint32_t* bits = reinterpret_cast<uint32_t*>(recon + kEncWaves * S * kK);
-    stage_words(cent, dev + DevLayout::cent, S * kK / 2);
-    stage_words(enc, dev + DevLayout::enc, S * kK);
+    stage_vec(cent, dev + D.cent(), S * kK / 2);
+    stage_vec(enc, dev + D.enc(), S * kK);
     __syncthreads();
     const int wave = threadIdx.x >> 6;
     EncLds E;
@@ -374,7 +499,7 @@ __device__ inline EncLds setup_enc_lds(unsigned char* smem, const unsigned char*
     return E;
 }
 
-__global__ __launch_bounds__(kEncThreads) void encode_kernel(const unsigned char* __restrict__ dev, int S,
+__global__ __launch_bounds__(kEncThreads) void encode_kernel(const uint32_t* __restrict__ dev, int S,
                                                              const uint32_t* __restrict__ src, size_t n_groups,
                                                              uint32_t* __restrict__ blocks, uint32_t* __restrict__ meta) {
     extern __shared__ __align__(16) unsigned char smem_enc[];
@@ -390,8 +515,8 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const unsigned char
 }
 
 // grid: (ceil(B*H / 4), 2); y = 0 encodes K, y = 1 encodes V
-__global__ __launch_bounds__(kEncThreads) void kv_append_kernel(const unsigned char* __restrict__ dev_k, int Sk,
-                                                                const unsigned char* __restrict__ dev_v, int Sv,
+__global__ __launch_bounds__(kEncThreads) void kv_append_kernel(const uint32_t* __restrict__ dev_k, int Sk,
+                                                                const uint32_t* __restrict__ dev_v, int Sv,
                                                                 const uint32_t* __restrict__ k_new, const uint32_t* __restrict__ v_new,
                                                                 uint32_t* __restrict__ k_blocks, uint32_t* __restrict__ k_meta,
                                                                 uint32_t* __restrict__ v_blocks, uint32_t* __restrict__ v_meta,
@@ -447,8 +572,8 @@ __device__ inline float wg_reduce(float v, float* scratch, bool is_max) {
 }
 
 template <bool kLongK, bool kLongV>
-__global__ __launch_bounds__(kAttnThreads) void kv_attend_kernel(const unsigned char* __restrict__ dev_k, int Sk,
-                                                                 const unsigned char* __restrict__ dev_v, int Sv,
+__global__ __launch_bounds__(kAttnThreads) void kv_attend_kernel(const uint32_t* __restrict__ dev_k, int Sk,
+                                                                 const uint32_t* __restrict__ dev_v, int Sv,
                                                                  const uint16_t* __restrict__ q,
                                                                  const uint4* __restrict__ k_blocks, const uint32_t* __restrict__ k_meta,
                                                                  const uint4* __restrict__ v_blocks, const uint32_t* __restrict__ v_meta,
@@ -633,24 +758,23 @@ int ecco_decode_gemv(const ecco_model* m, const void* blocks, const uint32_t* me
     // split the column tiles of a row tile over several workgroups until the chip is covered
     const int cus = cu_count(m->device);
     int split = std::max(1, std::min(col_tiles, (cus + row_tiles - 1) / row_tiles));
+    while (split > 1 && (row_tiles * split > kMaxWsTiles || row_tiles > kWsCounters)) --split;
     const size_t lds = gemv_lds_bytes(m->S);
     const bool lng = m->max_len > kPeekBits;
     int rc = lng ? allow_lds(gemv_kernel<true>, lds) : allow_lds(gemv_kernel<false>, lds);
     if (rc != ECCO_OK) return rc;
-    if (split > 1) {
-        const size_t n = (size_t)batch * rows;
-        hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)std::min<size_t>((n + 255) / 256, 1024)), dim3(256), 0, st, y, n);
-        ECCO_HIP_CHECK(hipGetLastError());
-    }
-    for (int b = 0; b < batch; ++b) {
+    const DevLayout D{m->S};
+    float* ws_partial = reinterpret_cast<float*>(m->dev + D.ws_partial());
+    int* ws_counter = reinterpret_cast<int*>(m->dev + D.ws_counter());
+    for (int b = 0; b < batch; ++b) {  // launches on one stream run in order, so they can share the workspace
         const uint32_t* xb = reinterpret_cast<const uint32_t*>(x + (size_t)b * cols);
         float* yb = y + (size_t)b * rows;
         if (lng)
             hipLaunchKernelGGL(gemv_kernel<true>, dim3(row_tiles * split), dim3(kGemvThreads), lds, st, m->dev, m->S,
-                               static_cast<const uint4*>(blocks), meta, rows, gpr, split, xb, yb);
+                               static_cast<const uint4*>(blocks), meta, rows, gpr, split, xb, yb, ws_partial, ws_counter);
         else
             hipLaunchKernelGGL(gemv_kernel<false>, dim3(row_tiles * split), dim3(kGemvThreads), lds, st, m->dev, m->S,
-                               static_cast<const uint4*>(blocks), meta, rows, gpr, split, xb, yb);
+                               static_cast<const uint4*>(blocks), meta, rows, gpr, split, xb, yb, ws_partial, ws_counter);
         ECCO_HIP_CHECK(hipGetLastError());
     }
     return ECCO_OK;

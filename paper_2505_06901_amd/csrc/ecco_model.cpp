@@ -53,26 +53,12 @@ void derive_codes(ecco_model* m) {
     for (int i = 0; i < m->S * kK; ++i) m->max_len = std::max<int>(m->max_len, m->lens[i]);
 }
 
-// Index whose code is a prefix of the top bits of `peek` (a kPeekBits-bit value, first stream bit
-// most significant), or -1 when that code is longer than the peek.
-static int match_prefix(const ecco_model* m, int p, uint32_t peek, int* len) {
-    for (int k = 0; k < kK; ++k) {
-        int l = m->lens[p * kK + k];
-        if (l <= kPeekBits && (peek >> (kPeekBits - l)) == m->codes[p * kK + k]) {
-            *len = l;
-            return k;
-        }
-    }
-    return -1;
-}
-
-void build_device_image(const ecco_model* m, unsigned char* img) {
-    std::memset(img, 0, DevLayout::total);
-    std::memcpy(img + DevLayout::cent, m->cent, sizeof(uint16_t) * m->S * kK);
-    uint32_t* enc = reinterpret_cast<uint32_t*>(img + DevLayout::enc);
-    uint32_t* longtab = reinterpret_cast<uint32_t*>(img + DevLayout::longtab);
-    uint32_t* rawlut = reinterpret_cast<uint32_t*>(img + DevLayout::rawlut);
-    uint32_t* lut = reinterpret_cast<uint32_t*>(img + DevLayout::lut);
+void build_device_image(const ecco_model* m, uint32_t* img) {
+    const DevLayout D{m->S};
+    std::memset(img, 0, D.image_words() * 4);
+    uint32_t* enc = img + D.enc();
+    uint32_t* longtab = img + D.longtab();
+    std::memcpy(img + D.cent(), m->cent, sizeof(uint16_t) * m->S * kK);
     for (int p = 0; p < m->S; ++p) {
         int order[kK];
         canonical_order(&m->lens[p * kK], order);
@@ -80,14 +66,7 @@ void build_device_image(const ecco_model* m, unsigned char* img) {
             int k = order[j], l = m->lens[p * kK + k];
             longtab[p * kK + j] = ((uint32_t)m->codes[p * kK + k] << (kMaxLen - l)) | ((uint32_t)k << 12) | ((uint32_t)l << 16);
         }
-        for (int k = 0; k < kK; ++k) {
-            enc[p * kK + k] = (uint32_t)m->codes[p * kK + k] | ((uint32_t)m->lens[p * kK + k] << 16);
-            rawlut[p * kK + k] = ((uint32_t)m->cent[p * kK + k] << 16) | ((uint32_t)k << 8) | 4u;
-        }
-        for (uint32_t v = 0; v < (uint32_t)kPeekEntries; ++v) {
-            int l = 0, k = match_prefix(m, p, v, &l);
-            lut[p * kPeekEntries + v] = (k < 0) ? 0u : (((uint32_t)m->cent[p * kK + k] << 16) | ((uint32_t)k << 8) | (uint32_t)l);
-        }
+        for (int k = 0; k < kK; ++k) enc[p * kK + k] = (uint32_t)m->codes[p * kK + k] | ((uint32_t)m->lens[p * kK + k] << 16);
     }
 }
 
@@ -176,21 +155,22 @@ int ecco_model_to_device(ecco_model* m, int device) {
         m->device = -1;
     }
     if (hipSetDevice(device) != hipSuccess) return ECCO_EHIP;
-    std::vector<unsigned char> img(DevLayout::total);
+    const DevLayout D{m->S};
+    std::vector<uint32_t> img(D.image_words());
     build_device_image(m, img.data());
     void* d = nullptr;
-    hipError_t e = hipMalloc(&d, DevLayout::total);
+    hipError_t e = hipMalloc(&d, D.total_bytes());
     if (e != hipSuccess) {
         (void)hipSetDevice(prev);
         return e == hipErrorOutOfMemory ? ECCO_ENOMEM : ECCO_EHIP;
     }
-    e = hipMemcpy(d, img.data(), DevLayout::total, hipMemcpyHostToDevice);
+    e = hipMemcpy(d, img.data(), D.image_words() * 4, hipMemcpyHostToDevice);
     (void)hipSetDevice(prev);
     if (e != hipSuccess) {
         (void)hipFree(d);
         return ECCO_EHIP;
     }
-    m->dev = static_cast<unsigned char*>(d);
+    m->dev = static_cast<uint32_t*>(d);
     m->device = device;
     return ECCO_OK;
 }
