@@ -30,6 +30,9 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 BYTES_PER_GROUP = 68   # 64-byte payload + 4-byte meta word
+# HBM bytes per launch of the fused batch-1 kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs, scaled by
+# what the same counters read for an 8 MiB plain copy); see profiles/gemv_batch1_proj7b.md
+MEASURED_TRAFFIC_BYTES = {"proj7b": int((5251.0 * 1.994 + 90.0) * 1024)}
 
 
 def cpu_baseline(m, blocks_np, meta_np, rows, cols, x_np, budget_s=12.0):
@@ -67,8 +70,6 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only", default="", help="comma list of rows to run (kv_append,decode,gemv1,gemv8,gemv16,kv_attend)")
     ap.add_argument("--workload", default="proj7b", choices=["proj7b", "mlp_up", "mlp_down", "proj70b"])
-    ap.add_argument("--copy-probe", action="store_true",
-                    help="also run one plain 256 MiB device copy before the warm-up (reference for rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (every box has one); run with --gpus 1")
@@ -164,13 +165,6 @@ def main():
             else:
                 run_row(row)
 
-    if args.copy_probe:
-        probe_src = torch.ones(256 * 2**20, dtype=torch.uint8, device=dev)
-        probe_dst = torch.empty_like(probe_src)
-        torch.cuda.synchronize()
-        probe_dst.copy_(probe_src)  # one kernel that reads 256 MiB and writes 256 MiB
-        torch.cuda.synchronize()
-        del probe_src, probe_dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -235,7 +229,7 @@ def main():
                    "pct_hbm_peak": 100.0 * achieved / HBM_PEAK_GBS, "raw_block_fraction": raw_frac,
                    "rotating_copies": n_copies, "cache_warm_gemv1_GBps": (comp_bytes / (warm_ms * 1e-3) / 1e9) if warm_ms else None},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
                      "kernel": "fused decode-GEMV, batch 1", "bytes_per_launch": comp_bytes,
                      "avg_launch_ms": ms.get(metric_row)},
         "rows": rows_out,

@@ -131,6 +131,9 @@ int ecco_decode_indices(const ecco_model* m, const void* blocks, const uint32_t*
  *   W = rows x cols, stored as rows*(cols/128) blocks, row-major;   x  device, batch x cols FP16
  *   y  device, batch x rows FP32:  y[b][r] = sum_c W[r][c] * x[b][c]  (FP32 accumulation)
  *   batch 1..16;  cols % 128 == 0;  cols <= 65536.
+ * Partial sums of a launch that splits a row tile over workgroups pass through a workspace owned by
+ * the model: two calls with the SAME model must not overlap in time (different streams); calls on one
+ * stream, and calls with different models, are fine.
  * Errors: EINVAL, ESHAPE (cols, batch, rows <= 0), EALIGN, EHIP. */
 int ecco_decode_gemv(const ecco_model* m, const void* blocks, const uint32_t* meta,
                      int rows, int cols, const uint16_t* x, int batch, float* y, void* stream);
