@@ -399,6 +399,152 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_kernel(const uint32_t* __re
     }
 }
 
+// ---- ecco_decode_gemv, batch 2..16: MFMA tile ------------------------------------------------------------
+// Same 64 x 8 tile and staging as the batch-1 kernel, but a wavefront now owns 32 rows of one column
+// group with BOTH chains: lane l decodes chain l / 32 of row l % 32.  Eight values per lane and step
+// are exactly the A operand of v_mfma_f32_32x32x16_f16 (row l % 32, k slice l / 32), the matching
+// eight activations of batch row l % 32 are the B operand (read from an LDS copy of x; lanes past the
+// batch hold zeros), and the 32 x 32 FP32 accumulator (rows x batch) lives in registers across all
+// column tiles.  The weights enter the MFMA as fp16(centroid * scale) -- packed FP16 multiplies,
+// which round exactly like the FP32-multiply-then-round rule -- so no per-row scaling of the
+// accumulator is needed.  The 8 column-group wavefronts of a row half are added through LDS.
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef float float16_t __attribute__((ext_vector_type(16)));
+constexpr int kXRow = kTileGroups * kGroup + 8;  // halves per batch row of the x tile in LDS (16-byte skew between rows)
+constexpr int kMaxBatch = 16;
+inline size_t gemm_lds_bytes(int S) {
+    return (table_words(S) + (size_t)kTileBlocks * kStride) * 4 + (size_t)kMaxBatch * kXRow * 2 + 16;
+}
+
+template <bool kLong>
+__global__ __launch_bounds__(kGemvThreads) void gemm_kernel(const uint32_t* __restrict__ dev, int S,
+                                                            const uint4* __restrict__ blocks, const uint32_t* __restrict__ meta,
+                                                            int rows, int cols, int split, int batch,
+                                                            const uint16_t* __restrict__ x, float* __restrict__ y,
+                                                            float* __restrict__ ws_partial, int* __restrict__ ws_counter) {
+    extern __shared__ __align__(16) uint32_t smem[];
+    const int gpr = cols / kGroup;
+    const int row_tile = blockIdx.x / split, k0 = blockIdx.x % split;
+    const int col_tiles = (gpr + kTileGroups - 1) / kTileGroups;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const bool loader = wave < kLoaders / 64;
+    const int cgl = wave >> 1, row_half = wave & 1;
+    const int chain = lane >> 5, n = lane & 31;               // this lane's chain, and its batch column in B / C
+    const int trow = row_half * 32 + (lane & 31);             // row inside the tile
+    const int row = min(row_tile * kTileRows + trow, rows - 1);
+    uint32_t* payload = smem + table_words(S);
+    _Float16* xt = reinterpret_cast<_Float16*>(payload + kTileBlocks * kStride);
+    int* last_flag = reinterpret_cast<int*>(xt + kMaxBatch * kXRow);
+    TileLoad pre;
+    if (loader) {
+        pre = load_tile(blocks, rows, gpr, row_tile, k0);
+    } else {
+        for (int t = threadIdx.x - kLoaders; t < S * kK; t += kGemvThreads - kLoaders) build_table_item(smem, S, t, load_table_item(dev, S, t));
+        if (kLong) {
+            const DevLayout D{S};
+            for (int i = threadIdx.x - kLoaders; i < S * kK; i += kGemvThreads - kLoaders) smem[S * (kPeekEntries + kK) + i] = dev[D.longtab() + i];
+            for (int i = threadIdx.x - kLoaders; i < S * kK / 2; i += kGemvThreads - kLoaders) smem[S * (kPeekEntries + 2 * kK) + i] = dev[D.cent() + i];
+        }
+    }
+    uint32_t mw_next = (k0 * kTileGroups + cgl < gpr) ? meta[(size_t)row * gpr + k0 * kTileGroups + cgl] : 0u;
+    const Tables T = table_pointers(smem, S);
+    zero_pads(payload, kTileBlocks);
+    float16_t acc;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) acc[j] = 0.0f;
+    for (int ct = k0; ct < col_tiles; ct += split) {
+        __syncthreads();  // the previous tile (payload and x) has been consumed
+        if (loader) store_tile(payload, pre);
+        // x tile: batch rows x 1024 columns of this column tile, 16 bytes per thread and pass
+        {
+            const int col0 = ct * kTileGroups * kGroup;
+            const int width = min(kTileGroups * kGroup, cols - col0);  // multiple of 128
+            for (int q = threadIdx.x; q < batch * (kTileGroups * kGroup / 8); q += kGemvThreads) {
+                const int b = q / (kTileGroups * kGroup / 8), c8 = (q % (kTileGroups * kGroup / 8)) * 8;
+                uint4 v = make_uint4(0, 0, 0, 0);
+                if (c8 < width) v = *reinterpret_cast<const uint4*>(x + (size_t)b * cols + col0 + c8);
+                *reinterpret_cast<uint4*>(xt + b * kXRow + c8) = v;
+            }
+        }
+        const int cg = ct * kTileGroups + cgl;
+        const bool active = cg < gpr;  // uniform over the wavefront
+        const uint32_t mw = mw_next;
+        if (ct + split < col_tiles) {
+            const int ncg = (ct + split) * kTileGroups + cgl;
+            mw_next = ncg < gpr ? meta[(size_t)row * gpr + ncg] : 0u;
+            if (loader) pre = load_tile(blocks, rows, gpr, row_tile, ct + split);
+        }
+        __syncthreads();
+        if (active) {
+            const Lane L = lane_setup(T, mw, S);
+            const _Float16 sh = __builtin_bit_cast(_Float16, (unsigned short)(mw & 0xFFFFu));
+            const half2_t s2 = {sh, sh};
+            const _Float16* xrow = xt + n * kXRow + cgl * kGroup + chain * kHalf;  // this lane's 64 activations (if n < batch)
+            uint32_t pk[4];
+            decode_chain<kLong, kHalf>(payload + (cgl * kTileRows + trow) * kStride, chain ? L.second_start : 0u, L,
+                                       [&](int i, uint32_t e) {
+                                           if ((i & 1) == 0) pk[(i >> 1) & 3] = e >> 16;
+                                           else pk[(i >> 1) & 3] |= e & 0xFFFF0000u;
+                                           if ((i & 7) == 7) {
+                                               half8_t a, b;
+#pragma unroll
+                                               for (int j = 0; j < 4; ++j) {
+                                                   const half2_t w2 = __builtin_bit_cast(half2_t, pk[j]) * s2;
+                                                   a[2 * j] = w2[0];
+                                                   a[2 * j + 1] = w2[1];
+                                               }
+#pragma unroll
+                                               for (int j = 0; j < 8; ++j) b[j] = (_Float16)0.0f;
+                                               if (n < batch) b = *reinterpret_cast<const half8_t*>(xrow + (i - 7));
+                                               acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc, 0, 0, 0);
+                                           }
+                                       });
+        }
+    }
+    // accumulator layout of the 32x32 tile: register r of lane l is row 8 * (r / 4) + 4 * (l / 32) + r % 4, column l % 32
+    __syncthreads();
+    float* red = reinterpret_cast<float*>(payload);  // [cgl 8][row 64][batch 16] floats = 32 KB
+    if (n < kMaxBatch) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int i = 8 * (r >> 2) + 4 * chain + (r & 3);
+            red[(cgl * kTileRows + row_half * 32 + i) * kMaxBatch + n] = acc[r];
+        }
+    }
+    __syncthreads();
+    // thread (b, r) adds the 8 column-group wavefronts: 16 x 64 = 1024 outputs, one per thread
+    const int ob = threadIdx.x >> 6, orow = threadIdx.x & 63;
+    float sum = 0.0f;
+#pragma unroll
+    for (int c = 0; c < kTileGroups; ++c) sum += red[(c * kTileRows + orow) * kMaxBatch + ob];
+    const int out_row = row_tile * kTileRows + orow;
+    const bool valid = ob < batch && out_row < rows;
+    if (split == 1) {
+        if (valid) y[(size_t)ob * rows + out_row] = sum;
+        return;
+    }
+    // several workgroups share this row tile (see gemv_kernel): publish, count arrivals, the last one adds up
+    float* mine = ws_partial + ((size_t)row_tile * split + k0) * (kMaxBatch * kTileRows);
+    __hip_atomic_store(&mine[threadIdx.x], sum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // every wavefront waits for its own stores
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const int seen = __hip_atomic_fetch_add(&ws_counter[row_tile], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *last_flag = (seen == split - 1);
+    }
+    __syncthreads();
+    if (*last_flag) {
+        float total = 0.0f;
+        for (int k = 0; k < split; ++k)
+            total += __hip_atomic_load(&ws_partial[((size_t)row_tile * split + k) * (kMaxBatch * kTileRows) + threadIdx.x],
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (valid) y[(size_t)ob * rows + out_row] = total;
+        if (threadIdx.x == 0) __hip_atomic_store(&ws_counter[row_tile], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
 // ---- encoder ---------------------------------------------------------------------------------------
 // One wavefront per group; lane l holds values 2l and 2l+1.
 constexpr int kEncThreads = 256;
@@ -750,7 +896,7 @@ int ecco_decode_gemv(const ecco_model* m, const void* blocks, const uint32_t* me
     if (!blocks || !meta || !x || !y) return ECCO_EINVAL;
     if (model_ready(m) != ECCO_OK) return ECCO_EINVAL;
     if (rows <= 0 || cols <= 0 || cols % kGroup != 0 || cols > 65536 || batch < 1 || batch > 16) return ECCO_ESHAPE;
-    if (!aligned(blocks, 64) || !aligned(x, 4) || !aligned(y, 4) || !aligned(meta, 4)) return ECCO_EALIGN;
+    if (!aligned(blocks, 64) || !aligned(x, batch > 1 ? 16 : 4) || !aligned(y, 4) || !aligned(meta, 4)) return ECCO_EALIGN;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int gpr = cols / kGroup;
     const int row_tiles = (rows + kTileRows - 1) / kTileRows;
@@ -761,22 +907,31 @@ int ecco_decode_gemv(const ecco_model* m, const void* blocks, const uint32_t* me
     while (split > 1 && (row_tiles * split > kMaxWsTiles || row_tiles > kWsCounters)) --split;
     const size_t lds = gemv_lds_bytes(m->S);
     const bool lng = m->max_len > kPeekBits;
-    int rc = lng ? allow_lds(gemv_kernel<true>, lds) : allow_lds(gemv_kernel<false>, lds);
-    if (rc != ECCO_OK) return rc;
     const DevLayout D{m->S};
     float* ws_partial = reinterpret_cast<float*>(m->dev + D.ws_partial());
     int* ws_counter = reinterpret_cast<int*>(m->dev + D.ws_counter());
-    for (int b = 0; b < batch; ++b) {  // launches on one stream run in order, so they can share the workspace
-        const uint32_t* xb = reinterpret_cast<const uint32_t*>(x + (size_t)b * cols);
-        float* yb = y + (size_t)b * rows;
+    if (batch == 1) {
+        int rc = lng ? allow_lds(gemv_kernel<true>, lds) : allow_lds(gemv_kernel<false>, lds);
+        if (rc != ECCO_OK) return rc;
+        const uint32_t* xb = reinterpret_cast<const uint32_t*>(x);
         if (lng)
             hipLaunchKernelGGL(gemv_kernel<true>, dim3(row_tiles * split), dim3(kGemvThreads), lds, st, m->dev, m->S,
-                               static_cast<const uint4*>(blocks), meta, rows, gpr, split, xb, yb, ws_partial, ws_counter);
+                               static_cast<const uint4*>(blocks), meta, rows, gpr, split, xb, y, ws_partial, ws_counter);
         else
             hipLaunchKernelGGL(gemv_kernel<false>, dim3(row_tiles * split), dim3(kGemvThreads), lds, st, m->dev, m->S,
-                               static_cast<const uint4*>(blocks), meta, rows, gpr, split, xb, yb, ws_partial, ws_counter);
-        ECCO_HIP_CHECK(hipGetLastError());
+                               static_cast<const uint4*>(blocks), meta, rows, gpr, split, xb, y, ws_partial, ws_counter);
+    } else {
+        const size_t glds = gemm_lds_bytes(m->S);
+        int rc = lng ? allow_lds(gemm_kernel<true>, glds) : allow_lds(gemm_kernel<false>, glds);
+        if (rc != ECCO_OK) return rc;
+        if (lng)
+            hipLaunchKernelGGL(gemm_kernel<true>, dim3(row_tiles * split), dim3(kGemvThreads), glds, st, m->dev, m->S,
+                               static_cast<const uint4*>(blocks), meta, rows, cols, split, batch, x, y, ws_partial, ws_counter);
+        else
+            hipLaunchKernelGGL(gemm_kernel<false>, dim3(row_tiles * split), dim3(kGemvThreads), glds, st, m->dev, m->S,
+                               static_cast<const uint4*>(blocks), meta, rows, cols, split, batch, x, y, ws_partial, ws_counter);
     }
+    ECCO_HIP_CHECK(hipGetLastError());
     return ECCO_OK;
 }
 
