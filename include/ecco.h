@@ -128,7 +128,7 @@ int ecco_decode_indices(const ecco_model* m, const void* blocks, const uint32_t*
 
 /* Decode fused into the consuming GEMV (Section 2.1: decode-phase projections are memory-bound
  * matrix-vector products); the FP16 weights never reach HBM.
- *   W = rows x cols, stored as rows*(cols/128) blocks, row-major;   x  device, batch x cols FP16
+ *   W = rows x cols, stored as rows*(cols/128) blocks, row-major;   x  device, batch x cols FP16, 16-byte aligned
  *   y  device, batch x rows FP32:  y[b][r] = sum_c W[r][c] * x[b][c]  (FP32 accumulation)
  *   batch 1..16;  cols % 128 == 0;  cols <= 65536.
  * Partial sums of a launch that splits a row tile over workgroups pass through a workspace owned by

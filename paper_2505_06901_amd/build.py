@@ -2,6 +2,7 @@
 from __future__ import annotations
 
 import os
+import re
 import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
@@ -18,6 +19,27 @@ def _hipcc() -> str:
     return "hipcc"
 
 
+def _check_kernel_resources(remarks: str, verbose: bool) -> None:
+    """Every kernel must keep its working set in registers: a kernel that spills to scratch memory is
+    far off its design point (the decode loops are sized for 1024-thread workgroups, 128 VGPRs), so
+    a register spill is a build error rather than a silent slowdown."""
+    name, found = None, 0
+    for line in remarks.splitlines():
+        m = re.search(r"remark:\s+Function Name: (\S+)", line)
+        if m:
+            name = m.group(1)
+            continue
+        m = re.search(r"remark:\s+ScratchSize \[bytes/lane\]: (\d+)", line)
+        if m and name:
+            found += 1
+            if verbose:
+                print("  %s: scratch %s bytes/lane" % (name, m.group(1)))
+            if int(m.group(1)) != 0:
+                raise RuntimeError("kernel %s spills %s bytes/lane to scratch memory" % (name, m.group(1)))
+    if found == 0:
+        raise RuntimeError("no kernel resource remarks found: cannot verify register use")
+
+
 def build(verbose: bool = False) -> str:
     """Compiles every source for gfx950 and links libecco.so; always recompiles."""
     objs = []
@@ -28,12 +50,16 @@ def build(verbose: bool = False) -> str:
         obj = os.path.join(CSRC, os.path.splitext(src)[0] + ".o")
         if src.endswith(".hip"):
             cmd = [_hipcc(), "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-                   *common, "-c", path, "-o", obj]
+                   "-Rpass-analysis=kernel-resource-usage", *common, "-c", path, "-o", obj]
         else:
             cmd = [_hipcc(), "-x", "c++", "-D__HIP_PLATFORM_AMD__", "-I/opt/rocm/include", *common, "-c", path, "-o", obj]
         if verbose:
             print(" ".join(cmd))
-        subprocess.check_call(cmd)
+        proc = subprocess.run(cmd, stderr=subprocess.PIPE, text=True)
+        if proc.returncode != 0:
+            raise RuntimeError("compiling %s failed:\n%s" % (src, proc.stderr))
+        if src.endswith(".hip"):
+            _check_kernel_resources(proc.stderr, verbose)
         objs.append(obj)
     cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB, "-lpthread"]
     if verbose:

@@ -254,148 +254,144 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(const uint32_t* __r
     }
 }
 
-// ---- ecco_decode_gemv, batch row by batch row ------------------------------------------------------------
-// Tile = 64 rows x 8 column groups = 512 blocks; 16 wavefronts: wavefront (c, h) decodes half h of
-// column group c for the 64 rows, lane = row.  x[i] is then uniform over the wavefront and comes
-// from scalar registers.  A workgroup (row tile, split k) walks the column tiles k, k + split, ...
-// (the next tile's payload is already in flight while the current one is decoded); each lane keeps
-// the running dot product of its row; the 16 wavefronts are added in LDS in a fixed order.  With
-// split > 1 every workgroup leaves its 64 sums in the model's workspace and the last one to arrive
-// (an arrival counter per row tile) adds them in split order and writes y: one launch, no atomics
-// on y, and the same bits on every run.
+// ---- tiles of the fused kernels ---------------------------------------------------------------------------
+// A workgroup of 1024 threads works on tiles of 512 blocks (R rows x C column groups).  The payload
+// of a tile is fetched by the first kLoaders threads (wavefronts 0..7), four 16-byte pieces each;
+// the other wavefronts build the decode tables meanwhile.  Loads of one wavefront return in issue
+// order, so keeping the two jobs in different wavefronts lets the table build proceed while the
+// payload is still on its way from HBM.  In LDS block (r, c) of the tile sits in slot c * R + r.
 constexpr int kGemvThreads = 1024;
-constexpr int kTileRows = 64;
-constexpr int kTileGroups = 8;
-constexpr int kTileBlocks = kTileRows * kTileGroups;
-constexpr int kMaxWsTiles = (int)(kWsFloats / 16 / kTileRows);  // row tiles x split that fit the workspace
-inline size_t gemv_lds_bytes(int S) { return (table_words(S) + (size_t)kTileBlocks * kStride + 16 * 64 + 4) * 4; }
-
-// The payload of a tile is fetched by the first kLoaders threads (wavefronts 0..7), four 16-byte
-// pieces each; the other wavefronts build the decode tables meanwhile.  Loads of one wavefront
-// return in issue order, so keeping the two jobs in different wavefronts lets the table build
-// proceed while the payload is still on its way from HBM.
+constexpr int kTileBlocks = 512;
 constexpr int kLoaders = 512;
 constexpr int kPiecesPerLoader = kTileBlocks * 4 / kLoaders;
 struct TileLoad {
     uint4 v[kPiecesPerLoader];
 };
 // this thread's pieces of tile (row_tile, ct); pieces outside the matrix are zero
+template <int R, int C>
 __device__ __forceinline__ TileLoad load_tile(const uint4* __restrict__ blocks, int rows, int gpr, int row_tile, int ct) {
+    static_assert(R * C == kTileBlocks, "tile size");
     TileLoad t;
 #pragma unroll
     for (int j = 0; j < kPiecesPerLoader; ++j) {
         const int q = threadIdx.x + j * kLoaders;
-        const int r = q >> 5, c = (q >> 2) & 7, piece = q & 3;
-        const int gr = min(row_tile * kTileRows + r, rows - 1), gc = ct * kTileGroups + c;
+        const int r = q / (C * 4), c = (q >> 2) % C, piece = q & 3;
+        const int gr = min(row_tile * R + r, rows - 1), gc = ct * C + c;
         t.v[j] = gc < gpr ? blocks[((size_t)gr * gpr + gc) * 4 + piece] : make_uint4(0, 0, 0, 0);
     }
     return t;
 }
+template <int R, int C>
 __device__ __forceinline__ void store_tile(uint32_t* payload, const TileLoad& t) {
 #pragma unroll
     for (int j = 0; j < kPiecesPerLoader; ++j) {
         const int q = threadIdx.x + j * kLoaders;
-        const int r = q >> 5, c = (q >> 2) & 7, piece = q & 3;
-        uint32_t* d = payload + (c * kTileRows + r) * kStride + piece * 4;
+        const int r = q / (C * 4), c = (q >> 2) % C, piece = q & 3;
+        uint32_t* d = payload + (c * R + r) * kStride + piece * 4;
         d[0] = t.v[j].x; d[1] = t.v[j].y; d[2] = t.v[j].z; d[3] = t.v[j].w;
     }
 }
+// tables by the non-loader threads (the caller synchronises afterwards)
+template <bool kLong>
+__device__ __forceinline__ void build_tables_by_builders(uint32_t* smem, const uint32_t* __restrict__ dev, int S) {
+    for (int t = threadIdx.x - kLoaders; t < S * kK; t += kGemvThreads - kLoaders) build_table_item(smem, S, t, load_table_item(dev, S, t));
+    if (kLong) {
+        const DevLayout D{S};
+        for (int i = threadIdx.x - kLoaders; i < S * kK; i += kGemvThreads - kLoaders) smem[S * (kPeekEntries + kK) + i] = dev[D.longtab() + i];
+        for (int i = threadIdx.x - kLoaders; i < S * kK / 2; i += kGemvThreads - kLoaders) smem[S * (kPeekEntries + 2 * kK) + i] = dev[D.cent() + i];
+    }
+}
+
+// ---- ecco_decode_gemv, batch 1 ----------------------------------------------------------------------------
+// A workgroup owns 16 whole rows and walks them in tiles of 16 rows x 32 column groups (2 KB runs
+// per row).  Wavefront w takes chain w & 1 of column groups 4 * (w >> 1) .. + 3; lane l is row
+// l & 15 of column group l >> 4 of those four.  All lanes sit at the same value position; the
+// activations come from an LDS copy of x, eight per read shared by the 16 rows of a column group,
+// so each value costs one mixed-precision FMA.  Sixteen rows per workgroup
+// cover 256 compute units from 4096 rows on without splitting a row over workgroups: no partial
+// sums in memory, and the sum order is fixed (lanes of a row in LDS, in order).
+constexpr int kG1Rows = 16;
+constexpr int kG1Groups = 32;
+constexpr int kXGroupWords = kGroup / 2 + 4;  // words per column group of the x tile in LDS (skewed against bank conflicts)
+inline size_t gemv_lds_bytes(int S) { return (table_words(S) + (size_t)kTileBlocks * kStride + kG1Groups * kXGroupWords + kGemvThreads) * 4; }
 
 template <bool kLong>
 __global__ __launch_bounds__(kGemvThreads) void gemv_kernel(const uint32_t* __restrict__ dev, int S,
                                                             const uint4* __restrict__ blocks, const uint32_t* __restrict__ meta,
-                                                            int rows, int gpr, int split,
-                                                            const uint32_t* __restrict__ x, float* __restrict__ y,
-                                                            float* __restrict__ ws_partial, int* __restrict__ ws_counter) {
+                                                            int rows, int gpr,
+                                                            const uint32_t* __restrict__ x, float* __restrict__ y) {
     extern __shared__ __align__(16) uint32_t smem[];
-    const int row_tile = blockIdx.x / split, k0 = blockIdx.x % split;
-    const int col_tiles = (gpr + kTileGroups - 1) / kTileGroups;
+    const int row_tile = blockIdx.x;
+    const int col_tiles = (gpr + kG1Groups - 1) / kG1Groups;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const bool loader = wave < kLoaders / 64;
-    const int cgl = wave >> 1, half = wave & 1;
-    const int row = min(row_tile * kTileRows + lane, rows - 1);  // lanes past the last row repeat it; their sums are dropped
+    const int half = wave & 1;
+    const int cgl = (wave >> 1) * 4 + (lane >> 4);              // column group inside the tile
+    const int trow = lane & 15;
+    const int row = min(row_tile * kG1Rows + trow, rows - 1);   // lanes past the last row repeat it; their sums are dropped
     uint32_t* payload = smem + table_words(S);
-    float* part = reinterpret_cast<float*>(payload + kTileBlocks * kStride);
+    uint32_t* xt = payload + kTileBlocks * kStride;
+    float* part = reinterpret_cast<float*>(xt + kG1Groups * kXGroupWords);
     TileLoad pre;
-    if (loader) {
-        pre = load_tile(blocks, rows, gpr, row_tile, k0);
-    } else {
-        for (int t = threadIdx.x - kLoaders; t < S * kK; t += kGemvThreads - kLoaders) build_table_item(smem, S, t, load_table_item(dev, S, t));
-        if (kLong) {
-            const DevLayout D{S};
-            for (int i = threadIdx.x - kLoaders; i < S * kK; i += kGemvThreads - kLoaders) smem[S * (kPeekEntries + kK) + i] = dev[D.longtab() + i];
-            for (int i = threadIdx.x - kLoaders; i < S * kK / 2; i += kGemvThreads - kLoaders) smem[S * (kPeekEntries + 2 * kK) + i] = dev[D.cent() + i];
-        }
-    }
+    if (loader) pre = load_tile<kG1Rows, kG1Groups>(blocks, rows, gpr, row_tile, 0);
+    else build_tables_by_builders<kLong>(smem, dev, S);
     // the meta word is fetched after the table build: it comes from HBM and would hold up the (cached)
     // table loads issued behind it
-    uint32_t mw_next = (k0 * kTileGroups + cgl < gpr) ? meta[(size_t)row * gpr + k0 * kTileGroups + cgl] : 0u;
+    uint32_t mw_next = cgl < gpr ? meta[(size_t)row * gpr + cgl] : 0u;
     const Tables T = table_pointers(smem, S);
     zero_pads(payload, kTileBlocks);
     float total = 0.0f;
-    for (int ct = k0; ct < col_tiles; ct += split) {
+    for (int ct = 0; ct < col_tiles; ++ct) {
         __syncthreads();  // the previous tile has been consumed
-        if (loader) store_tile(payload, pre);
-        const int cg = ct * kTileGroups + cgl;
-        const bool active = cg < gpr;  // uniform over the wavefront
-        const uint32_t mw = mw_next;
-        uint32_t xs[kHalf / 2];
-        if (active) {
-            const uint32_t* xw = x + (size_t)cg * (kGroup / 2) + half * (kHalf / 2);
-#pragma unroll
-            for (int j = 0; j < kHalf / 2; ++j) xs[j] = xw[j];
+        if (loader) {
+            store_tile<kG1Rows, kG1Groups>(payload, pre);
+        } else {  // x of this column tile: 32 groups x 64 words, one 16-byte piece per builder thread
+            const int q = threadIdx.x - kLoaders, g = q >> 4, piece = q & 15;
+            const int gc = ct * kG1Groups + g;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (gc < gpr) v = reinterpret_cast<const uint4*>(x)[(size_t)gc * 16 + piece];
+            *reinterpret_cast<uint4*>(xt + g * kXGroupWords + piece * 4) = v;
         }
-        if (ct + split < col_tiles) {
-            const int ncg = (ct + split) * kTileGroups + cgl;
+        const int cg = ct * kG1Groups + cgl;
+        const bool active = cg < gpr;
+        const uint32_t mw = mw_next;
+        if (ct + 1 < col_tiles) {
+            const int ncg = (ct + 1) * kG1Groups + cgl;
             mw_next = ncg < gpr ? meta[(size_t)row * gpr + ncg] : 0u;
-            if (loader) pre = load_tile(blocks, rows, gpr, row_tile, ct + split);
+            if (loader) pre = load_tile<kG1Rows, kG1Groups>(blocks, rows, gpr, row_tile, ct + 1);
         }
         __syncthreads();
         if (active) {
             const Lane L = lane_setup(T, mw, S);
+            // the 64 activations of the chain come from the x tile eight at a time (one 16-byte read that
+            // all 16 rows of the column group share), so only a few registers hold activations
+            const uint4* xsrc = reinterpret_cast<const uint4*>(xt + cgl * kXGroupWords + half * (kHalf / 2));
+            uint4 xq = xsrc[0];
             float acc = 0.0f;
-            decode_chain<kLong, kHalf>(payload + (cgl * kTileRows + lane) * kStride, half ? L.second_start : 0u, L,
+            decode_chain<kLong, kHalf>(payload + (cgl * kG1Rows + trow) * kStride, half ? L.second_start : 0u, L,
                                        [&](int i, uint32_t e) {
-                                           const uint32_t xp = xs[i >> 1];
+                                           const int j = (i >> 1) & 3;
+                                           const uint32_t xp = j == 0 ? xq.x : j == 1 ? xq.y : j == 2 ? xq.z : xq.w;
                                            const float xv = half_bits_f((i & 1) ? (xp >> 16) : (xp & 0xFFFFu));
                                            acc = fmaf(half_bits_f(e >> 16), xv, acc);
+                                           if ((i & 7) == 7 && i + 1 < kHalf) xq = xsrc[(i + 1) >> 3];
+                                           // pins the running sum every four values: otherwise the multiply-adds are
+                                           // sunk below the whole chain and all 64 table entries stay in registers
+                                           if ((i & 3) == 3) asm volatile("" : "+v"(acc));
                                        });
             total = fmaf(acc, L.scale, total);
         }
     }
-    part[wave * 64 + lane] = total;
+    part[threadIdx.x] = total;
     __syncthreads();
-    float s = 0.0f;
-    if (threadIdx.x < 64) {
+    if (threadIdx.x < kG1Rows) {
+        float s = 0.0f;
+        for (int w = 0; w < kGemvThreads / 64; ++w)
 #pragma unroll
-        for (int w = 0; w < 16; ++w) s += part[w * 64 + threadIdx.x];
-    }
-    const int out_row = row_tile * kTileRows + (int)threadIdx.x;
-    if (split == 1) {
-        if (threadIdx.x < 64 && out_row < rows) y[out_row] = s;
-        return;
-    }
-    // Several workgroups share this row tile: publish, count arrivals, the last one adds up.  The eight
-    // L2 caches of the chip are not coherent with each other inside a kernel, so the partial sums and the
-    // counter travel as device-scope atomics (they bypass L2); ordering comes from completion: the
-    // stores of a wavefront are waited for before its lane 0 bumps the counter, and the reader's loads
-    // are issued only after its own counter update has returned.  No cache-wide flush is involved.
-    if (threadIdx.x < 64) {
-        __hip_atomic_store(&ws_partial[((size_t)row_tile * split + k0) * kTileRows + threadIdx.x], s, __ATOMIC_RELAXED,
-                           __HIP_MEMORY_SCOPE_AGENT);
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // waits until the stores above have completed
-        int seen = 0;
-        if (threadIdx.x == 0) seen = __hip_atomic_fetch_add(&ws_counter[row_tile], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        seen = __builtin_amdgcn_readfirstlane(seen);
-        if (seen == split - 1) {
-            float sum = 0.0f;
-            for (int k = 0; k < split; ++k)
-                sum += __hip_atomic_load(&ws_partial[((size_t)row_tile * split + k) * kTileRows + threadIdx.x], __ATOMIC_RELAXED,
-                                         __HIP_MEMORY_SCOPE_AGENT);
-            if (out_row < rows) y[out_row] = sum;
-            if (threadIdx.x == 0) __hip_atomic_store(&ws_counter[row_tile], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // ready for the next launch
-        }
+            for (int q = 0; q < 4; ++q) s += part[w * 64 + q * 16 + threadIdx.x];
+        const int out_row = row_tile * kG1Rows + (int)threadIdx.x;
+        if (out_row < rows) y[out_row] = s;
     }
 }
 
@@ -408,6 +404,9 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_kernel(const uint32_t* __re
 // column tiles.  The weights enter the MFMA as fp16(centroid * scale) -- packed FP16 multiplies,
 // which round exactly like the FP32-multiply-then-round rule -- so no per-row scaling of the
 // accumulator is needed.  The 8 column-group wavefronts of a row half are added through LDS.
+constexpr int kTileRows = 64;
+constexpr int kTileGroups = 8;
+constexpr int kMaxWsTiles = (int)(kWsFloats / 16 / kTileRows);  // row tiles x split that fit the workspace
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef float float16_t __attribute__((ext_vector_type(16)));
@@ -438,16 +437,8 @@ __global__ __launch_bounds__(kGemvThreads) void gemm_kernel(const uint32_t* __re
     _Float16* xt = reinterpret_cast<_Float16*>(payload + kTileBlocks * kStride);
     int* last_flag = reinterpret_cast<int*>(xt + kMaxBatch * kXRow);
     TileLoad pre;
-    if (loader) {
-        pre = load_tile(blocks, rows, gpr, row_tile, k0);
-    } else {
-        for (int t = threadIdx.x - kLoaders; t < S * kK; t += kGemvThreads - kLoaders) build_table_item(smem, S, t, load_table_item(dev, S, t));
-        if (kLong) {
-            const DevLayout D{S};
-            for (int i = threadIdx.x - kLoaders; i < S * kK; i += kGemvThreads - kLoaders) smem[S * (kPeekEntries + kK) + i] = dev[D.longtab() + i];
-            for (int i = threadIdx.x - kLoaders; i < S * kK / 2; i += kGemvThreads - kLoaders) smem[S * (kPeekEntries + 2 * kK) + i] = dev[D.cent() + i];
-        }
-    }
+    if (loader) pre = load_tile<kTileRows, kTileGroups>(blocks, rows, gpr, row_tile, k0);
+    else build_tables_by_builders<kLong>(smem, dev, S);
     uint32_t mw_next = (k0 * kTileGroups + cgl < gpr) ? meta[(size_t)row * gpr + k0 * kTileGroups + cgl] : 0u;
     const Tables T = table_pointers(smem, S);
     zero_pads(payload, kTileBlocks);
@@ -456,7 +447,7 @@ __global__ __launch_bounds__(kGemvThreads) void gemm_kernel(const uint32_t* __re
     for (int j = 0; j < 16; ++j) acc[j] = 0.0f;
     for (int ct = k0; ct < col_tiles; ct += split) {
         __syncthreads();  // the previous tile (payload and x) has been consumed
-        if (loader) store_tile(payload, pre);
+        if (loader) store_tile<kTileRows, kTileGroups>(payload, pre);
         // x tile: batch rows x 1024 columns of this column tile, 16 bytes per thread and pass
         {
             const int col0 = ct * kTileGroups * kGroup;
@@ -474,7 +465,7 @@ __global__ __launch_bounds__(kGemvThreads) void gemm_kernel(const uint32_t* __re
         if (ct + split < col_tiles) {
             const int ncg = (ct + split) * kTileGroups + cgl;
             mw_next = ncg < gpr ? meta[(size_t)row * gpr + ncg] : 0u;
-            if (loader) pre = load_tile(blocks, rows, gpr, row_tile, ct + split);
+            if (loader) pre = load_tile<kTileRows, kTileGroups>(blocks, rows, gpr, row_tile, ct + split);
         }
         __syncthreads();
         if (active) {
@@ -525,7 +516,11 @@ __global__ __launch_bounds__(kGemvThreads) void gemm_kernel(const uint32_t* __re
         if (valid) y[(size_t)ob * rows + out_row] = sum;
         return;
     }
-    // several workgroups share this row tile (see gemv_kernel): publish, count arrivals, the last one adds up
+    // Several workgroups share this row tile: publish, count arrivals, the last one adds up in split order.
+    // The eight L2 caches of the chip are not coherent with each other inside a kernel, so the partial sums
+    // and the counter travel as device-scope atomics (they bypass L2); ordering comes from completion: every
+    // wavefront waits for its own stores before the barrier that precedes the counter update, and the
+    // reader's loads are issued only after its counter update has returned.  No cache-wide flush.
     float* mine = ws_partial + ((size_t)row_tile * split + k0) * (kMaxBatch * kTileRows);
     __hip_atomic_store(&mine[threadIdx.x], sum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // every wavefront waits for its own stores
@@ -896,7 +891,7 @@ int ecco_decode_gemv(const ecco_model* m, const void* blocks, const uint32_t* me
     if (!blocks || !meta || !x || !y) return ECCO_EINVAL;
     if (model_ready(m) != ECCO_OK) return ECCO_EINVAL;
     if (rows <= 0 || cols <= 0 || cols % kGroup != 0 || cols > 65536 || batch < 1 || batch > 16) return ECCO_ESHAPE;
-    if (!aligned(blocks, 64) || !aligned(x, batch > 1 ? 16 : 4) || !aligned(y, 4) || !aligned(meta, 4)) return ECCO_EALIGN;
+    if (!aligned(blocks, 64) || !aligned(x, 16) || !aligned(y, 4) || !aligned(meta, 4)) return ECCO_EALIGN;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int gpr = cols / kGroup;
     const int row_tiles = (rows + kTileRows - 1) / kTileRows;
@@ -914,12 +909,13 @@ int ecco_decode_gemv(const ecco_model* m, const void* blocks, const uint32_t* me
         int rc = lng ? allow_lds(gemv_kernel<true>, lds) : allow_lds(gemv_kernel<false>, lds);
         if (rc != ECCO_OK) return rc;
         const uint32_t* xb = reinterpret_cast<const uint32_t*>(x);
+        const int grid = (rows + kG1Rows - 1) / kG1Rows;
         if (lng)
-            hipLaunchKernelGGL(gemv_kernel<true>, dim3(row_tiles * split), dim3(kGemvThreads), lds, st, m->dev, m->S,
-                               static_cast<const uint4*>(blocks), meta, rows, gpr, split, xb, y, ws_partial, ws_counter);
+            hipLaunchKernelGGL(gemv_kernel<true>, dim3(grid), dim3(kGemvThreads), lds, st, m->dev, m->S,
+                               static_cast<const uint4*>(blocks), meta, rows, gpr, xb, y);
         else
-            hipLaunchKernelGGL(gemv_kernel<false>, dim3(row_tiles * split), dim3(kGemvThreads), lds, st, m->dev, m->S,
-                               static_cast<const uint4*>(blocks), meta, rows, gpr, split, xb, y, ws_partial, ws_counter);
+            hipLaunchKernelGGL(gemv_kernel<false>, dim3(grid), dim3(kGemvThreads), lds, st, m->dev, m->S,
+                               static_cast<const uint4*>(blocks), meta, rows, gpr, xb, y);
     } else {
         const size_t glds = gemm_lds_bytes(m->S);
         int rc = lng ? allow_lds(gemm_kernel<true>, glds) : allow_lds(gemm_kernel<false>, glds);
