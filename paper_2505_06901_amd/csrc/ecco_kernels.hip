@@ -142,49 +142,44 @@ __device__ __forceinline__ Lane lane_setup(const Tables& T, uint32_t meta, int S
 }
 
 // ---- the chain decoder ----------------------------------------------------------------------------------
-// Decodes kCount values starting at stream bit `start` of the staged block `w` (16 words + zero pad),
-// calling sink(i, entry) with the table entry of each (length, index, centroid).  The window is
-// left-aligned; it is topped up to more than 32 valid bits every 4 values (every 2 when the model
-// has codes longer than 8 bits: kLong), which covers the longest possible run of codes in between.
-// Words past the block read as zero, so arbitrary bytes decode without touching other memory.
+// Decodes kCount values starting at stream bit `start` of the staged block `w` (16 words, then a zero
+// word, then one more readable word), calling sink(i, entry) with the table entry of each (length,
+// index, centroid).  Values are taken in runs of 4 (2 when the model has codes longer than 8 bits:
+// kLong).  A run starts by fetching the two words around its bit position into a left-aligned
+// 64-bit window: at least 33 valid bits, enough for the longest run of codes plus the last peek, so
+// there is no refill logic and no branch inside a run.  The position is clamped to 512, where the
+// window's upper half is the zero word: bits past the block read as zero and arbitrary bytes decode
+// without touching other memory (the lower half of that last window is never looked at).
 template <bool kLong, int kCount, class Sink>
 __device__ __forceinline__ void decode_chain(const uint32_t* w, uint32_t start, const Lane& L, Sink&& sink) {
-    const uint32_t* wend = w + kBlockWords;
-    const uint32_t* wp = w + (start >> 5);
-    const uint32_t r = start & 31u;
-    uint64_t win = (((uint64_t)wp[0] << 32) | (uint64_t)wp[1]) << r;
-    int valid = 64 - (int)r;
-    wp += 2;
-    uint32_t next = wp < wend ? *wp : 0u;
-    constexpr int kCheck = kLong ? 2 : 4;
-    uint32_t used = 0;  // sum of the entries since the last check; its low byte is the number of bits consumed
+    constexpr int kRun = kLong ? 2 : 4;
+    static_assert(kCount % kRun == 0, "chain length");
+    uint32_t pos = start;
 #pragma unroll
-    for (int i = 0; i < kCount; ++i) {
-        if (i > 0 && i % kCheck == 0) {
-            valid -= (int)(used & 0xFFu);
-            used = 0;
-            if (valid <= 32) {
-                win |= (uint64_t)next << (32 - valid);
-                valid += 32;
-                ++wp;
-                next = wp < wend ? *wp : 0u;
+    for (int i0 = 0; i0 < kCount; i0 += kRun) {
+        pos = min(pos, (uint32_t)(kBlockWords * 32));
+        const uint32_t* wp = w + (pos >> 5);
+        uint64_t win = (((uint64_t)wp[0] << 32) | (uint64_t)wp[1]) << (pos & 31u);
+        uint32_t used = 0;  // sum of the run's entries; its low byte is the number of bits consumed (at most 4 x 12)
+#pragma unroll
+        for (int j = 0; j < kRun; ++j) {
+            uint32_t e = L.lut[(uint32_t)(win >> 32) >> L.shift];
+            if (kLong) {
+                if ((e & 0xFFu) == 0u) {
+                    // code longer than the peek: rank of the next 12 bits among the left-aligned canonical codes
+                    const uint32_t v = (uint32_t)(win >> 32) >> (32 - kMaxLen);
+                    int rank = 0;
+                    for (int q = 1; q < kK; ++q) rank += ((L.longtab[q] & 0xFFFu) <= v) ? 1 : 0;
+                    const uint32_t t = L.longtab[rank];
+                    const uint32_t idx = (t >> 12) & 15u;
+                    e = ((uint32_t)__half_as_ushort(L.cent[idx]) << 16) | (idx << 8) | (t >> 16);
+                }
             }
+            sink(i0 + j, e);
+            used += e;
+            win <<= (e & 0xFFu);
         }
-        uint32_t e = L.lut[(uint32_t)(win >> 32) >> L.shift];
-        if (kLong) {
-            if ((e & 0xFFu) == 0u) {
-                // code longer than the peek: rank of the next 12 bits among the left-aligned canonical codes
-                const uint32_t v = (uint32_t)(win >> 32) >> (32 - kMaxLen);
-                int rank = 0;
-                for (int j = 1; j < kK; ++j) rank += ((L.longtab[j] & 0xFFFu) <= v) ? 1 : 0;
-                const uint32_t t = L.longtab[rank];
-                const uint32_t idx = (t >> 12) & 15u;
-                e = ((uint32_t)__half_as_ushort(L.cent[idx]) << 16) | (idx << 8) | (t >> 16);
-            }
-        }
-        sink(i, e);
-        used += e;  // lengths add up in the low byte (at most 4 x 12), the rest is ignored
-        win <<= (e & 0xFFu);
+        pos += used & 0xFFu;
     }
 }
 
@@ -205,7 +200,7 @@ __device__ inline void zero_pads(uint32_t* lds, int slots) {
 // ---- ecco_decode / ecco_decode_indices ---------------------------------------------------------------
 constexpr int kDecThreads = 1024;
 constexpr int kDecBlocks = kDecThreads / 2;  // blocks per tile: two lanes per block
-inline size_t decode_lds_bytes(int S) { return (table_words(S) + (size_t)kDecBlocks * kStride) * 4; }
+inline size_t decode_lds_bytes(int S) { return (table_words(S) + (size_t)kDecBlocks * kStride + 4) * 4; }  // + the word a chain may read past the last slot
 
 template <bool kLong, bool kIndices>
 __global__ __launch_bounds__(kDecThreads) void decode_kernel(const uint32_t* __restrict__ dev, int S,
