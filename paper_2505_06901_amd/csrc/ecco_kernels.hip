@@ -14,6 +14,7 @@
 #include <hip/hip_fp16.h>
 
 #include <algorithm>
+#include <type_traits>
 
 #include "ecco_internal.h"
 
@@ -298,95 +299,171 @@ __device__ __forceinline__ void build_tables_by_builders(uint32_t* smem, const u
 }
 
 // ---- ecco_decode_gemv, batch 1 ----------------------------------------------------------------------------
-// A workgroup owns 16 whole rows and walks them in tiles of 16 rows x 32 column groups (2 KB runs
-// per row).  Wavefront w takes chain w & 1 of column groups 4 * (w >> 1) .. + 3; lane l is row
-// l & 15 of column group l >> 4 of those four.  All lanes sit at the same value position; the
-// activations come from an LDS copy of x, eight per read shared by the 16 rows of a column group,
-// so each value costs one mixed-precision FMA.  Sixteen rows per workgroup
-// cover 256 compute units from 4096 rows on without splitting a row over workgroups: no partial
-// sums in memory, and the sum order is fixed (lanes of a row in LDS, in order).
-constexpr int kG1Rows = 16;
-constexpr int kG1Groups = 32;
-constexpr int kXGroupWords = kGroup / 2 + 4;  // words per column group of the x tile in LDS (skewed against bank conflicts)
-inline size_t gemv_lds_bytes(int S) { return (table_words(S) + (size_t)kTileBlocks * kStride + kG1Groups * kXGroupWords + kGemvThreads) * 4; }
+// A workgroup (one per compute unit) owns a band of R consecutive rows; its work is cut into units
+// of one row x 32 column groups: 32 blocks, a contiguous 2 KB of payload, 64 chains -- one
+// wavefront.  Lane l of the wavefront decodes chain l / 32 of block l % 32.  After the decode tables
+// and x are in LDS (one workgroup barrier), the 16 wavefronts run on their own: each fetches the
+// payload of its next unit into registers, decodes the current one out of a private 2 KB LDS
+// buffer, adds the 64 lane sums with a wavefront reduction and goes on, without any further
+// workgroup barrier, so a wavefront starts decoding as soon as its own bytes have arrived and the
+// loads of one unit overlap the decode of the one before.  Units of a wavefront stay in one column
+// tile as long as possible, and the lane keeps the 64 activations of its chain in registers across
+// those units, so a value costs one mixed-precision FMA.  Rows are never split over workgroups:
+// partial sums of a row's column tiles meet in LDS and are added in a fixed order.
+constexpr int kUnitBlocks = 32;
+constexpr int kWaves = kGemvThreads / 64;
+constexpr int kUnitWords = kUnitBlocks * kStride + 4;  // private payload buffer of a wavefront (+ the word a chain may read past the last slot)
+constexpr int kXGroupWords = kGroup / 2 + 4;           // words per column group of x in LDS (skewed against bank conflicts)
+constexpr int kXLdsGroups = 128;                       // x is staged in LDS up to this many column groups, read from L2 beyond
+constexpr int kMaxBandRows = 128;
+constexpr int kMaxColTiles = 65536 / kGroup / kUnitBlocks;
+inline size_t gemv_lds_bytes(int S, int gpr) {
+    const size_t xwords = gpr <= kXLdsGroups ? (size_t)gpr * kXGroupWords : 0;
+    return (table_words(S) + (size_t)kWaves * kUnitWords + (size_t)kMaxBandRows * kMaxColTiles + xwords) * 4;
+}
+
+// sum over the 64 lanes of a wavefront in a fixed order, on the VALU (cross-lane moves inside rows of
+// 16 lanes, then the four row sums through scalar registers); every lane returns the total
+__device__ __forceinline__ float wave_sum(float t) {
+    auto dpp = [](float v, auto ctrl) {
+        return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), decltype(ctrl)::value, 0xF, 0xF, true));
+    };
+    t += dpp(t, std::integral_constant<int, 0xB1>{});   // quad_perm [1,0,3,2]
+    t += dpp(t, std::integral_constant<int, 0x4E>{});   // quad_perm [2,3,0,1]
+    t += dpp(t, std::integral_constant<int, 0x141>{});  // row_half_mirror
+    t += dpp(t, std::integral_constant<int, 0x140>{});  // row_mirror
+    const int b = __builtin_bit_cast(int, t);
+    const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 0)), r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 16));
+    const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 32)), r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 48));
+    return (r0 + r1) + (r2 + r3);
+}
+
+struct UnitLoad {
+    uint4 v0, v1;
+    uint32_t meta;
+};
+// the payload pieces and the meta word of this lane for unit (row, ct); addresses are clamped into the
+// row so that every lane issues the same loads, pieces past the row end are zeroed afterwards
+__device__ __forceinline__ UnitLoad load_unit(const uint4* __restrict__ blocks, const uint32_t* __restrict__ meta,
+                                              int row, int gpr, int ct, int lane) {
+    UnitLoad u;
+    const size_t row_base = (size_t)row * gpr;
+    const int g0 = ct * kUnitBlocks + (lane >> 2), g1 = g0 + 16;
+    const uint4 a = blocks[(row_base + min(g0, gpr - 1)) * 4 + (lane & 3)];
+    const uint4 b = blocks[(row_base + min(g1, gpr - 1)) * 4 + (lane & 3)];
+    const int g = ct * kUnitBlocks + (lane & (kUnitBlocks - 1));
+    u.meta = meta[row_base + min(g, gpr - 1)];
+    const bool in0 = g0 < gpr, in1 = g1 < gpr;
+    u.v0 = make_uint4(in0 ? a.x : 0u, in0 ? a.y : 0u, in0 ? a.z : 0u, in0 ? a.w : 0u);
+    u.v1 = make_uint4(in1 ? b.x : 0u, in1 ? b.y : 0u, in1 ? b.z : 0u, in1 ? b.w : 0u);
+    return u;
+}
+__device__ __forceinline__ void store_unit(uint32_t* wbuf, const UnitLoad& u, int lane) {
+    uint32_t* d = wbuf + (lane >> 2) * kStride + (lane & 3) * 4;
+    d[0] = u.v0.x; d[1] = u.v0.y; d[2] = u.v0.z; d[3] = u.v0.w;
+    d += 16 * kStride;
+    d[0] = u.v1.x; d[1] = u.v1.y; d[2] = u.v1.z; d[3] = u.v1.w;
+}
 
 template <bool kLong>
 __global__ __launch_bounds__(kGemvThreads) void gemv_kernel(const uint32_t* __restrict__ dev, int S,
                                                             const uint4* __restrict__ blocks, const uint32_t* __restrict__ meta,
-                                                            int rows, int gpr,
+                                                            int rows, int gpr, int band,
                                                             const uint32_t* __restrict__ x, float* __restrict__ y) {
     extern __shared__ __align__(16) uint32_t smem[];
-    const int row_tile = blockIdx.x;
-    const int col_tiles = (gpr + kG1Groups - 1) / kG1Groups;
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const bool loader = wave < kLoaders / 64;
-    const int half = wave & 1;
-    const int cgl = (wave >> 1) * 4 + (lane >> 4);              // column group inside the tile
-    const int trow = lane & 15;
-    const int row = min(row_tile * kG1Rows + trow, rows - 1);   // lanes past the last row repeat it; their sums are dropped
-    uint32_t* payload = smem + table_words(S);
-    uint32_t* xt = payload + kTileBlocks * kStride;
-    float* part = reinterpret_cast<float*>(xt + kG1Groups * kXGroupWords);
-    TileLoad pre;
-    if (loader) pre = load_tile<kG1Rows, kG1Groups>(blocks, rows, gpr, row_tile, 0);
-    else build_tables_by_builders<kLong>(smem, dev, S);
-    // the meta word is fetched after the table build: it comes from HBM and would hold up the (cached)
-    // table loads issued behind it
-    uint32_t mw_next = cgl < gpr ? meta[(size_t)row * gpr + cgl] : 0u;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int row0 = blockIdx.x * band;
+    const int band_rows = min(band, rows - row0);
+    const int col_tiles = (gpr + kUnitBlocks - 1) / kUnitBlocks;
+    const int units = band_rows * col_tiles;  // unit u = (column tile u / band_rows, row u % band_rows)
+    const bool x_in_lds = gpr <= kXLdsGroups;
+    uint32_t* wbuf = smem + table_words(S) + wave * kUnitWords;
+    float* part = reinterpret_cast<float*>(smem + table_words(S) + kWaves * kUnitWords);
+    uint32_t* xt = reinterpret_cast<uint32_t*>(part + kMaxBandRows * kMaxColTiles);
+    const uint4* x4 = reinterpret_cast<const uint4*>(x);
+
+    // loads in the order they are needed: table item, x, then the first unit's payload (from HBM)
+    TableItem item{0u, 0u};
+    if (tid < S * kK) item = load_table_item(dev, S, tid);
+    static_assert(kXLdsGroups * 16 == 2 * kGemvThreads, "two x pieces per thread");
+    uint4 xp0 = make_uint4(0, 0, 0, 0), xp1 = xp0;
+    if (x_in_lds) {
+        xp0 = x4[min(tid, gpr * 16 - 1)];
+        xp1 = x4[min(tid + kGemvThreads, gpr * 16 - 1)];
+    }
+    int u = wave;
+    UnitLoad pre;
+    if (u < units) pre = load_unit(blocks, meta, row0 + u % band_rows, gpr, u / band_rows, lane);
+    if (tid < S * kK) build_table_item(smem, S, tid, item);
+    if (kLong) {
+        const DevLayout D{S};
+        for (int i = tid; i < S * kK; i += kGemvThreads) smem[S * (kPeekEntries + kK) + i] = dev[D.longtab() + i];
+        for (int i = tid; i < S * kK / 2; i += kGemvThreads) smem[S * (kPeekEntries + 2 * kK) + i] = dev[D.cent() + i];
+    }
+    if (x_in_lds) {
+        const int i0 = tid, i1 = tid + kGemvThreads;
+        if (i0 < gpr * 16) *reinterpret_cast<uint4*>(xt + (i0 >> 4) * kXGroupWords + (i0 & 15) * 4) = xp0;
+        if (i1 < gpr * 16) *reinterpret_cast<uint4*>(xt + (i1 >> 4) * kXGroupWords + (i1 & 15) * 4) = xp1;
+    }
+    if (lane < kUnitBlocks) wbuf[lane * kStride + kBlockWords] = 0u;  // zero pads of the private buffer
+    if (lane == 0) wbuf[kUnitBlocks * kStride] = 0u;
     const Tables T = table_pointers(smem, S);
-    zero_pads(payload, kTileBlocks);
-    float total = 0.0f;
-    for (int ct = 0; ct < col_tiles; ++ct) {
-        __syncthreads();  // the previous tile has been consumed
-        if (loader) {
-            store_tile<kG1Rows, kG1Groups>(payload, pre);
-        } else {  // x of this column tile: 32 groups x 64 words, one 16-byte piece per builder thread
-            const int q = threadIdx.x - kLoaders, g = q >> 4, piece = q & 15;
-            const int gc = ct * kG1Groups + g;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (gc < gpr) v = reinterpret_cast<const uint4*>(x)[(size_t)gc * 16 + piece];
-            *reinterpret_cast<uint4*>(xt + g * kXGroupWords + piece * 4) = v;
+    __syncthreads();
+
+    const int blk = lane & (kUnitBlocks - 1), half = lane >> 5;
+    uint32_t xs[kHalf / 2];
+    int cur_ct = -1;
+    for (; u < units; u += kWaves) {
+        const int ct = u / band_rows, r = u - ct * band_rows;
+        store_unit(wbuf, pre, lane);
+        const uint32_t mw = pre.meta;
+        const int un = u + kWaves;
+        if (un < units) pre = load_unit(blocks, meta, row0 + un % band_rows, gpr, un / band_rows, lane);
+        const int cg = ct * kUnitBlocks + blk;
+        if (ct != cur_ct) {  // the activations of this lane's chain: 64 FP16 = 8 x 16 bytes
+            cur_ct = ct;
+            const int cgx = min(cg, gpr - 1);
+            if (x_in_lds) {
+                const uint4* src = reinterpret_cast<const uint4*>(xt + cgx * kXGroupWords + half * (kHalf / 2));
+#pragma unroll
+                for (int j = 0; j < kHalf / 8; ++j) {
+                    const uint4 v = src[j];
+                    xs[4 * j] = v.x; xs[4 * j + 1] = v.y; xs[4 * j + 2] = v.z; xs[4 * j + 3] = v.w;
+                }
+            } else {
+                const uint4* src = x4 + (size_t)cgx * 16 + half * 8;
+#pragma unroll
+                for (int j = 0; j < kHalf / 8; ++j) {
+                    const uint4 v = src[j];
+                    xs[4 * j] = v.x; xs[4 * j + 1] = v.y; xs[4 * j + 2] = v.z; xs[4 * j + 3] = v.w;
+                }
+            }
         }
-        const int cg = ct * kG1Groups + cgl;
-        const bool active = cg < gpr;
-        const uint32_t mw = mw_next;
-        if (ct + 1 < col_tiles) {
-            const int ncg = (ct + 1) * kG1Groups + cgl;
-            mw_next = ncg < gpr ? meta[(size_t)row * gpr + ncg] : 0u;
-            if (loader) pre = load_tile<kG1Rows, kG1Groups>(blocks, rows, gpr, row_tile, ct + 1);
-        }
-        __syncthreads();
-        if (active) {
-            const Lane L = lane_setup(T, mw, S);
-            // the 64 activations of the chain come from the x tile eight at a time (one 16-byte read that
-            // all 16 rows of the column group share), so only a few registers hold activations
-            const uint4* xsrc = reinterpret_cast<const uint4*>(xt + cgl * kXGroupWords + half * (kHalf / 2));
-            uint4 xq = xsrc[0];
-            float acc = 0.0f;
-            decode_chain<kLong, kHalf>(payload + (cgl * kG1Rows + trow) * kStride, half ? L.second_start : 0u, L,
-                                       [&](int i, uint32_t e) {
-                                           const int j = (i >> 1) & 3;
-                                           const uint32_t xp = j == 0 ? xq.x : j == 1 ? xq.y : j == 2 ? xq.z : xq.w;
-                                           const float xv = half_bits_f((i & 1) ? (xp >> 16) : (xp & 0xFFFFu));
-                                           acc = fmaf(half_bits_f(e >> 16), xv, acc);
-                                           if ((i & 7) == 7 && i + 1 < kHalf) xq = xsrc[(i + 1) >> 3];
-                                           // pins the running sum every four values: otherwise the multiply-adds are
-                                           // sunk below the whole chain and all 64 table entries stay in registers
-                                           if ((i & 3) == 3) asm volatile("" : "+v"(acc));
-                                       });
-            total = fmaf(acc, L.scale, total);
+        const Lane L = lane_setup(T, mw, S);
+        float acc = 0.0f;
+        decode_chain<kLong, kHalf>(wbuf + blk * kStride, half ? L.second_start : 0u, L, [&](int i, uint32_t e) {
+            const uint32_t xp = xs[i >> 1];
+            const float xv = half_bits_f((i & 1) ? (xp >> 16) : (xp & 0xFFFFu));
+            acc = fmaf(half_bits_f(e >> 16), xv, acc);
+            // pins the running sum every four values: otherwise the multiply-adds are sunk below the whole
+            // chain and all 64 table entries stay in registers
+            if ((i & 3) == 3) asm volatile("" : "+v"(acc));
+        });
+        const float t = wave_sum(cg < gpr ? acc * L.scale : 0.0f);
+        if (lane == 0) {
+            if (col_tiles == 1) y[row0 + r] = t;
+            else part[r * col_tiles + ct] = t;
         }
     }
-    part[threadIdx.x] = total;
-    __syncthreads();
-    if (threadIdx.x < kG1Rows) {
-        float s = 0.0f;
-        for (int w = 0; w < kGemvThreads / 64; ++w)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) s += part[w * 64 + q * 16 + threadIdx.x];
-        const int out_row = row_tile * kG1Rows + (int)threadIdx.x;
-        if (out_row < rows) y[out_row] = s;
+    if (col_tiles > 1) {
+        __syncthreads();
+        if (tid < band_rows) {
+            float sum = 0.0f;
+            for (int ct = 0; ct < col_tiles; ++ct) sum += part[tid * col_tiles + ct];
+            y[row0 + tid] = sum;
+        }
     }
 }
 
@@ -895,22 +972,24 @@ int ecco_decode_gemv(const ecco_model* m, const void* blocks, const uint32_t* me
     const int cus = cu_count(m->device);
     int split = std::max(1, std::min(col_tiles, (cus + row_tiles - 1) / row_tiles));
     while (split > 1 && (row_tiles * split > kMaxWsTiles || row_tiles > kWsCounters)) --split;
-    const size_t lds = gemv_lds_bytes(m->S);
     const bool lng = m->max_len > kPeekBits;
     const DevLayout D{m->S};
     float* ws_partial = reinterpret_cast<float*>(m->dev + D.ws_partial());
     int* ws_counter = reinterpret_cast<int*>(m->dev + D.ws_counter());
     if (batch == 1) {
+        // one band of rows per workgroup, one workgroup per compute unit where the matrix allows it
+        const int band = std::min(kMaxBandRows, std::max(1, (rows + cus - 1) / cus));
+        const size_t lds = gemv_lds_bytes(m->S, gpr);
         int rc = lng ? allow_lds(gemv_kernel<true>, lds) : allow_lds(gemv_kernel<false>, lds);
         if (rc != ECCO_OK) return rc;
         const uint32_t* xb = reinterpret_cast<const uint32_t*>(x);
-        const int grid = (rows + kG1Rows - 1) / kG1Rows;
+        const int grid = (rows + band - 1) / band;
         if (lng)
             hipLaunchKernelGGL(gemv_kernel<true>, dim3(grid), dim3(kGemvThreads), lds, st, m->dev, m->S,
-                               static_cast<const uint4*>(blocks), meta, rows, gpr, xb, y);
+                               static_cast<const uint4*>(blocks), meta, rows, gpr, band, xb, y);
         else
             hipLaunchKernelGGL(gemv_kernel<false>, dim3(grid), dim3(kGemvThreads), lds, st, m->dev, m->S,
-                               static_cast<const uint4*>(blocks), meta, rows, gpr, xb, y);
+                               static_cast<const uint4*>(blocks), meta, rows, gpr, band, xb, y);
     } else {
         const size_t glds = gemm_lds_bytes(m->S);
         int rc = lng ? allow_lds(gemm_kernel<true>, glds) : allow_lds(gemm_kernel<false>, glds);
