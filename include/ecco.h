@@ -152,7 +152,7 @@ int ecco_kv_append(const ecco_model* mk, const ecco_model* mv,
 
 /* Single-query attention over the compressed caches (Section 2.1): per (b,h), scores
  * q.K_t / sqrt(128) for t < seq_len[b], softmax, out = sum_t p_t V_t.  No mask beyond seq_len.
- *   q  device [B][H][128] FP16;  out  device [B][H][128] FP32 (zeros where seq_len[b] <= 0).
+ *   q  device [B][H][128] FP16, 16-byte aligned;  out  device [B][H][128] FP32 (zeros where seq_len[b] <= 0).
  * seq_len values above T_max are clamped to T_max.  Errors as ecco_kv_append. */
 int ecco_kv_attend(const ecco_model* mk, const ecco_model* mv, const uint16_t* q,
                    const void* k_blocks, const uint32_t* k_meta, const void* v_blocks, const uint32_t* v_meta,

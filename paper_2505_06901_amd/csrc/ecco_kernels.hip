@@ -14,7 +14,6 @@
 #include <hip/hip_fp16.h>
 
 #include <algorithm>
-#include <type_traits>
 
 #include "ecco_internal.h"
 
@@ -169,9 +168,11 @@ __device__ __forceinline__ void decode_chain(const uint32_t* w, uint32_t start, 
                 if ((e & 0xFFu) == 0u) {
                     // code longer than the peek: rank of the next 12 bits among the left-aligned canonical codes
                     const uint32_t v = (uint32_t)(win >> 32) >> (32 - kMaxLen);
+                    const uint32_t* lt = L.longtab;
+                    asm volatile("" : "+v"(lt));  // the list is read here, on the rare path, not held in 16 registers throughout
                     int rank = 0;
-                    for (int q = 1; q < kK; ++q) rank += ((L.longtab[q] & 0xFFFu) <= v) ? 1 : 0;
-                    const uint32_t t = L.longtab[rank];
+                    for (int q = 1; q < kK; ++q) rank += ((lt[q] & 0xFFFu) <= v) ? 1 : 0;
+                    const uint32_t t = lt[rank];
                     const uint32_t idx = (t >> 12) & 15u;
                     e = ((uint32_t)__half_as_ushort(L.cent[idx]) << 16) | (idx << 8) | (t >> 16);
                 }
@@ -322,20 +323,21 @@ inline size_t gemv_lds_bytes(int S, int gpr) {
     return (table_words(S) + (size_t)kWaves * kUnitWords + (size_t)kMaxBandRows * kMaxColTiles + xwords) * 4;
 }
 
+template <int kCtrl>
+__device__ __forceinline__ float dpp_mov(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), kCtrl, 0xF, 0xF, true));
+}
+__device__ __forceinline__ float read_lane(float v, int l) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), l));
+}
 // sum over the 64 lanes of a wavefront in a fixed order, on the VALU (cross-lane moves inside rows of
 // 16 lanes, then the four row sums through scalar registers); every lane returns the total
 __device__ __forceinline__ float wave_sum(float t) {
-    auto dpp = [](float v, auto ctrl) {
-        return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), decltype(ctrl)::value, 0xF, 0xF, true));
-    };
-    t += dpp(t, std::integral_constant<int, 0xB1>{});   // quad_perm [1,0,3,2]
-    t += dpp(t, std::integral_constant<int, 0x4E>{});   // quad_perm [2,3,0,1]
-    t += dpp(t, std::integral_constant<int, 0x141>{});  // row_half_mirror
-    t += dpp(t, std::integral_constant<int, 0x140>{});  // row_mirror
-    const int b = __builtin_bit_cast(int, t);
-    const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 0)), r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 16));
-    const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 32)), r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 48));
-    return (r0 + r1) + (r2 + r3);
+    t += dpp_mov<0xB1>(t);   // quad_perm [1,0,3,2]
+    t += dpp_mov<0x4E>(t);   // quad_perm [2,3,0,1]
+    t += dpp_mov<0x141>(t);  // row_half_mirror
+    t += dpp_mov<0x140>(t);  // row_mirror
+    return (read_lane(t, 0) + read_lane(t, 16)) + (read_lane(t, 32) + read_lane(t, 48));
 }
 
 struct UnitLoad {
@@ -755,23 +757,29 @@ __global__ __launch_bounds__(kEncThreads) void kv_append_kernel(const uint32_t* 
 }
 
 // ---- single-query attention over compressed K / V ----------------------------------------------------
-// One workgroup per (sequence, head), one token per lane (both chains of its block one after the
-// other).  The sequence is walked in spans of kSpan tokens.  Per span: the K tables are staged and
-// the scores q.K_t / sqrt(128) are formed (q sits in LDS; all lanes read the same element at the
-// same time) and kept in LDS; the span's maximum updates the running softmax (maximum, denominator,
-// rescale of what has been accumulated); then the V tables replace the K tables and every lane adds
-// p_t * V_t into its own 128 FP32 accumulators (static register per value position, nothing shared).
-// At the end the accumulators of the 256 lanes are added through LDS.  Only one model's tables are
-// resident at a time, which keeps S = 64 for both K and V within 160 KB of LDS.
-constexpr int kAttnThreads = 256;
+// One workgroup of 12 wavefronts per (sequence, head): three per SIMD, which leaves each lane the
+// registers for 64 private accumulators next to the decoder state (8 wavefronts when the V model has
+// codes longer than the table peek: that decoder needs more registers still).  The cache of a head is a band of T blocks,
+// so the kernel reuses the streaming scheme of the batch-1 GEMV: a unit is 32 consecutive tokens
+// (2 KB of payload), lane l of a wavefront decodes chain l / 32 of token l % 32, units are
+// prefetched into registers and decoded out of the wavefront's private LDS buffer.  The sequence is
+// walked in spans of kSpan tokens.  Per span: with the K tables in LDS the scores q.K_t / sqrt(128)
+// are formed (the lane keeps the 64 query elements of its chain in registers) and kept in LDS; the
+// span's maximum updates the running softmax (maximum, denominator, rescale of what has been
+// accumulated); then the V tables replace the K tables and every lane adds p_t * V_t of its chain
+// into 64 private FP32 accumulators (a static register per value position, nothing shared).  At the
+// end the accumulators are added over the lanes of a wavefront on the VALU and over the wavefronts
+// through LDS.  K and V enter as fp16(centroid * scale), formed two at a time by a packed FP16
+// multiply, which rounds exactly like the FP32-multiply-then-round rule.  Only one model's tables
+// are resident at a time, which keeps S = 64 for both K and V within 160 KB of LDS.
+constexpr int kAttnThreads = 768;      // workgroup size; 512 for a V model with long codes
+constexpr int kAttnWaves = kAttnThreads / 64;
 constexpr int kSpan = 8192;
-constexpr int kRedStride = 33;
-static_assert(kAttnThreads * kRedStride <= kAttnThreads * kStride + kSpan - 256, "reduction scratch must fit");
 inline size_t attn_lds_bytes(int Sk, int Sv) {
-    return (table_words(std::max(Sk, Sv)) + (size_t)kAttnThreads * kStride + kSpan + kGroup + 16) * 4;
+    return (table_words(std::max(Sk, Sv)) + (size_t)kAttnWaves * kUnitWords + kSpan + kAttnWaves * kGroup + 64) * 4;
 }
 
-__device__ inline float wg_reduce(float v, float* scratch, bool is_max) {
+__device__ inline float wg_reduce(float v, float* scratch, bool is_max, int waves) {
     for (int m = 1; m < 64; m <<= 1) {
         float o = __shfl_xor(v, m);
         v = is_max ? fmaxf(v, o) : v + o;
@@ -780,12 +788,12 @@ __device__ inline float wg_reduce(float v, float* scratch, bool is_max) {
     if ((threadIdx.x & 63) == 0) scratch[threadIdx.x >> 6] = v;
     __syncthreads();
     float r = scratch[0];
-    for (int w = 1; w < kAttnThreads / 64; ++w) r = is_max ? fmaxf(r, scratch[w]) : r + scratch[w];
+    for (int w = 1; w < waves; ++w) r = is_max ? fmaxf(r, scratch[w]) : r + scratch[w];
     return r;
 }
 
 template <bool kLongK, bool kLongV>
-__global__ __launch_bounds__(kAttnThreads) void kv_attend_kernel(const uint32_t* __restrict__ dev_k, int Sk,
+__global__ __launch_bounds__(kLongV ? 512 : kAttnThreads) void kv_attend_kernel(const uint32_t* __restrict__ dev_k, int Sk,
                                                                  const uint32_t* __restrict__ dev_v, int Sv,
                                                                  const uint16_t* __restrict__ q,
                                                                  const uint4* __restrict__ k_blocks, const uint32_t* __restrict__ k_meta,
@@ -794,98 +802,138 @@ __global__ __launch_bounds__(kAttnThreads) void kv_attend_kernel(const uint32_t*
                                                                  float* __restrict__ out) {
     extern __shared__ __align__(16) uint32_t smem[];
     const int Smax = max(Sk, Sv);
-    uint32_t* payload = smem + table_words(Smax);
-    float* scores = reinterpret_cast<float*>(payload + kAttnThreads * kStride);
-    float* qs = scores + kSpan;
-    float* scratch = qs + kGroup;
-    zero_pads(payload, kAttnThreads);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int waves = kLongV ? 8 : kAttnWaves, threads = waves * 64;
+    uint32_t* wbuf = smem + table_words(Smax) + wave * kUnitWords;
+    float* scores = reinterpret_cast<float*>(smem + table_words(Smax) + kAttnWaves * kUnitWords);
+    float* wred = scores + kSpan;               // [wavefront][128] at the end
+    float* scratch = wred + kAttnWaves * kGroup;
+    if (lane < kUnitBlocks) wbuf[lane * kStride + kBlockWords] = 0u;
+    if (lane == 0) wbuf[kUnitBlocks * kStride] = 0u;
 
     const int bh = blockIdx.x;
     const int T = min(seq_len[bh / H], T_max);
-    if (threadIdx.x < kGroup) qs[threadIdx.x] = half_bits_f(q[(size_t)bh * kGroup + threadIdx.x]);
-    float o[kGroup];
-#pragma unroll
-    for (int i = 0; i < kGroup; ++i) o[i] = 0.0f;
+    const int blk = lane & (kUnitBlocks - 1), half = lane >> 5;
+    float my_out = 0.0f;  // threads 0..127: output element `tid`, not yet divided by the denominator
     float run_max = -INFINITY, run_den = 0.0f;
     const float inv_sqrt_d = 0.08838834764831845f;  // 1 / sqrt(128)
     for (int s0 = 0; s0 < T; s0 += kSpan) {
         const int span = min(kSpan, T - s0);
+        const int units = (span + kUnitBlocks - 1) / kUnitBlocks, unit0 = s0 / kUnitBlocks;
         // ---- scores of the span
         __syncthreads();
         const Tables TK = stage_tables(smem, dev_k, Sk);
+        __syncthreads();
         float my_max = -INFINITY;
-        for (int t0 = 0; t0 < span; t0 += kAttnThreads) {
-            const int count = min(kAttnThreads, span - t0);
-            const size_t first = (size_t)bh * T_max + s0 + t0;
-            __syncthreads();
-            stage_linear(payload, k_blocks, first, count);
-            __syncthreads();
-            if ((int)threadIdx.x < count) {
-                const Lane L = lane_setup(TK, k_meta[first + threadIdx.x], Sk);
-                const uint32_t* w = payload + threadIdx.x * kStride;
-                // the softmax is sensitive to the scores (keys with large per-channel scales), so K takes the
-                // exact dequantisation rule, FP16 rounding included
+        {
+            uint32_t qx[kHalf / 2];  // the query elements of this lane's chain, FP16 pairs
+            const uint4* qsrc = reinterpret_cast<const uint4*>(q + (size_t)bh * kGroup + half * kHalf);
+            asm volatile("" : "+v"(qsrc));  // reloaded per span (from cache) rather than kept alive across the V phase
+#pragma unroll
+            for (int j = 0; j < kHalf / 8; ++j) {
+                const uint4 v = qsrc[j];
+                qx[4 * j] = v.x; qx[4 * j + 1] = v.y; qx[4 * j + 2] = v.z; qx[4 * j + 3] = v.w;
+            }
+            int u = wave;
+            UnitLoad pre;
+            if (u < units) pre = load_unit(k_blocks, k_meta, bh, T_max, unit0 + u, lane);
+            for (; u < units; u += waves) {
+                store_unit(wbuf, pre, lane);
+                const uint32_t mw = pre.meta;
+                if (u + waves < units) pre = load_unit(k_blocks, k_meta, bh, T_max, unit0 + u + waves, lane);
+                // the query stays packed: without this the conversions to FP32 are hoisted out of the loop and
+                // occupy 64 registers instead of 32
+#pragma unroll
+                for (int j = 0; j < kHalf / 2; ++j) asm volatile("" : "+v"(qx[j]));
+                const Lane L = lane_setup(TK, mw, Sk);
+                const _Float16 sh = __builtin_bit_cast(_Float16, (unsigned short)(mw & 0xFFFFu));
+                const half2_t s2 = {sh, sh};
+                uint32_t pk = 0;
                 float acc = 0.0f;
-                decode_chain<kLongK, kHalf>(w, 0u, L, [&](int i, uint32_t e) { acc = fmaf(half_bits_f(dequant_bits(e >> 16, L.scale)), qs[i], acc); });
-                decode_chain<kLongK, kHalf>(w, L.second_start, L,
-                                            [&](int i, uint32_t e) { acc = fmaf(half_bits_f(dequant_bits(e >> 16, L.scale)), qs[kHalf + i], acc); });
-                const float sc = acc * inv_sqrt_d;
-                scores[t0 + threadIdx.x] = sc;
+                decode_chain<kLongK, kHalf>(wbuf + blk * kStride, half ? L.second_start : 0u, L, [&](int i, uint32_t e) {
+                    if ((i & 1) == 0) {
+                        pk = e >> 16;
+                    } else {
+                        const half2_t w2 = __builtin_bit_cast(half2_t, pk | (e & 0xFFFF0000u)) * s2;
+                        const half2_t q2 = __builtin_bit_cast(half2_t, qx[i >> 1]);
+                        acc = fmaf((float)w2[0], (float)q2[0], acc);
+                        acc = fmaf((float)w2[1], (float)q2[1], acc);
+                        if ((i & 3) == 3) asm volatile("" : "+v"(acc));  // keeps the multiply-adds next to their table reads
+                    }
+                });
+                acc += __shfl_xor(acc, 32);
+                const int t = u * kUnitBlocks + blk;
+                const float sc = t < span ? acc * inv_sqrt_d : -INFINITY;
+                if (half == 0) scores[t] = sc;
                 my_max = fmaxf(my_max, sc);
             }
         }
         // ---- running softmax
-        const float new_max = fmaxf(run_max, wg_reduce(my_max, scratch, true));
+        const float new_max = fmaxf(run_max, wg_reduce(my_max, scratch, true, waves));
         float my_den = 0.0f;
-        for (int t = threadIdx.x; t < span; t += kAttnThreads) {  // each lane touches only its own tokens
-            const float p = __expf(scores[t] - new_max);
+        for (int t = tid; t < units * kUnitBlocks; t += threads) {
+            const float p = __expf(scores[t] - new_max);  // 0 for the tokens past the span
             scores[t] = p;
             my_den += p;
         }
         const float rescale = (run_max == -INFINITY) ? 0.0f : __expf(run_max - new_max);
-        run_den = run_den * rescale + wg_reduce(my_den, scratch, false);
+        run_den = run_den * rescale + wg_reduce(my_den, scratch, false, waves);
         run_max = new_max;
-#pragma unroll
-        for (int i = 0; i < kGroup; ++i) o[i] *= rescale;
-        // ---- weighted sum of V
+        // ---- weighted sum of V over the span
         __syncthreads();
         const Tables TV = stage_tables(smem, dev_v, Sv);
-        for (int t0 = 0; t0 < span; t0 += kAttnThreads) {
-            const int count = min(kAttnThreads, span - t0);
-            const size_t first = (size_t)bh * T_max + s0 + t0;
-            __syncthreads();
-            stage_linear(payload, v_blocks, first, count);
-            __syncthreads();
-            if ((int)threadIdx.x < count) {
-                const Lane L = lane_setup(TV, v_meta[first + threadIdx.x], Sv);
-                const uint32_t* w = payload + threadIdx.x * kStride;
-                const float p = scores[t0 + threadIdx.x];
-                decode_chain<kLongV, kHalf>(w, 0u, L, [&](int i, uint32_t e) { o[i] = fmaf(p, half_bits_f(dequant_bits(e >> 16, L.scale)), o[i]); });
-                decode_chain<kLongV, kHalf>(w, L.second_start, L,
-                                            [&](int i, uint32_t e) { o[kHalf + i] = fmaf(p, half_bits_f(dequant_bits(e >> 16, L.scale)), o[kHalf + i]); });
+        __syncthreads();
+        {
+            float o[kHalf];
+#pragma unroll
+            for (int i = 0; i < kHalf; ++i) o[i] = 0.0f;
+            int u = wave;
+            UnitLoad pre;
+            if (u < units) pre = load_unit(v_blocks, v_meta, bh, T_max, unit0 + u, lane);
+            for (; u < units; u += waves) {
+                store_unit(wbuf, pre, lane);
+                const uint32_t mw = pre.meta;
+                if (u + waves < units) pre = load_unit(v_blocks, v_meta, bh, T_max, unit0 + u + waves, lane);
+                const Lane L = lane_setup(TV, mw, Sv);
+                const _Float16 sh = __builtin_bit_cast(_Float16, (unsigned short)(mw & 0xFFFFu));
+                const half2_t s2 = {sh, sh};
+                const float p = scores[u * kUnitBlocks + blk];
+                uint32_t pk = 0;
+                decode_chain<kLongV, kHalf>(wbuf + blk * kStride, half ? L.second_start : 0u, L, [&](int i, uint32_t e) {
+                    if ((i & 1) == 0) {
+                        pk = e >> 16;
+                    } else {
+                        const half2_t w2 = __builtin_bit_cast(half2_t, pk | (e & 0xFFFF0000u)) * s2;
+                        o[i - 1] = fmaf(p, (float)w2[0], o[i - 1]);
+                        o[i] = fmaf(p, (float)w2[1], o[i]);
+                    }
+                });
+            }
+            // the span's sums: over the lanes of a wavefront on the VALU (lanes 0..31 hold values 0..63, lanes
+            // 32..63 values 64..127), then over the wavefronts through LDS into the running output
+#pragma unroll
+            for (int i = 0; i < kHalf; ++i) {
+                float t = o[i];
+                t += dpp_mov<0xB1>(t);   // quad_perm [1,0,3,2]
+                t += dpp_mov<0x4E>(t);   // quad_perm [2,3,0,1]
+                t += dpp_mov<0x141>(t);  // row_half_mirror
+                t += dpp_mov<0x140>(t);  // row_mirror
+                const float lo = read_lane(t, 0) + read_lane(t, 16), hi = read_lane(t, 32) + read_lane(t, 48);
+                if (lane == 0) {
+                    wred[wave * kGroup + i] = lo;
+                    wred[wave * kGroup + kHalf + i] = hi;
+                }
             }
         }
-    }
-    // ---- add the 256 lanes' accumulators: four passes of 32 values through LDS
-    float* red = reinterpret_cast<float*>(payload);      // 256 x 33 floats: the payload area and the start of `scores`
-    float* partial = scores + kSpan - 256;               // 8 x 32 partial sums, clear of `red`
-    const int col = threadIdx.x & 31, part = threadIdx.x >> 5;
-#pragma unroll
-    for (int pass = 0; pass < 4; ++pass) {
         __syncthreads();
-#pragma unroll
-        for (int j = 0; j < 32; ++j) red[threadIdx.x * kRedStride + j] = o[pass * 32 + j];
-        __syncthreads();
-        float s = 0.0f;
-        for (int l = 0; l < 32; ++l) s += red[(part * 32 + l) * kRedStride + col];
-        partial[part * 32 + col] = s;
-        __syncthreads();
-        if (threadIdx.x < 32) {
+        if (tid < kGroup) {
             float v = 0.0f;
-            for (int k = 0; k < 8; ++k) v += partial[k * 32 + threadIdx.x];
-            out[(size_t)bh * kGroup + pass * 32 + threadIdx.x] = T > 0 ? v / run_den : 0.0f;
+            for (int w = 0; w < waves; ++w) v += wred[w * kGroup + tid];
+            my_out = my_out * rescale + v;
         }
     }
+    if (tid < kGroup) out[(size_t)bh * kGroup + tid] = T > 0 ? my_out / run_den : 0.0f;
 }
 
 // ---- host side -----------------------------------------------------------------------------------------
@@ -1027,13 +1075,13 @@ int ecco_kv_attend(const ecco_model* mk, const ecco_model* mv, const uint16_t* q
     if (!q || !k_blocks || !k_meta || !v_blocks || !v_meta || !seq_len || !out) return ECCO_EINVAL;
     if (model_ready(mk) != ECCO_OK || model_ready(mv) != ECCO_OK || mk->device != mv->device) return ECCO_EINVAL;
     if (B <= 0 || H <= 0 || T_max <= 0) return ECCO_ESHAPE;
-    if (!aligned(k_blocks, 64) || !aligned(v_blocks, 64) || !aligned(q, 2) || !aligned(out, 4)) return ECCO_EALIGN;
+    if (!aligned(k_blocks, 64) || !aligned(v_blocks, 64) || !aligned(q, 16) || !aligned(out, 4)) return ECCO_EALIGN;
     const size_t lds = attn_lds_bytes(mk->S, mv->S);
     const bool lk = mk->max_len > kPeekBits, lv = mv->max_len > kPeekBits;
     auto launch = [&](auto kernel) -> int {
         int rc = allow_lds(kernel, lds);
         if (rc != ECCO_OK) return rc;
-        hipLaunchKernelGGL(kernel, dim3(B * H), dim3(kAttnThreads), lds, static_cast<hipStream_t>(stream), mk->dev, mk->S, mv->dev,
+        hipLaunchKernelGGL(kernel, dim3(B * H), dim3(lv ? 512 : kAttnThreads), lds, static_cast<hipStream_t>(stream), mk->dev, mk->S, mv->dev,
                            mv->S, q, static_cast<const uint4*>(k_blocks), k_meta, static_cast<const uint4*>(v_blocks), v_meta,
                            seq_len, H, T_max, out);
         ECCO_HIP_CHECK(hipGetLastError());
