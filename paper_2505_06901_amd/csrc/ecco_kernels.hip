@@ -344,20 +344,19 @@ struct UnitLoad {
     uint4 v0, v1;
     uint32_t meta;
 };
-// the payload pieces and the meta word of this lane for unit (row, ct); addresses are clamped into the
-// row so that every lane issues the same loads, pieces past the row end are zeroed afterwards
+// the payload pieces and the meta word of this lane for unit (row, ct).  Block indices are clamped into
+// the row, so every lane issues the same loads and a slot past the row end holds a copy of the row's
+// last block: it decodes to finite values, which the caller drops.  Nothing here uses the loaded
+// data, so the loads stay in flight while the previous unit is decoded.
 __device__ __forceinline__ UnitLoad load_unit(const uint4* __restrict__ blocks, const uint32_t* __restrict__ meta,
                                               int row, int gpr, int ct, int lane) {
     UnitLoad u;
     const size_t row_base = (size_t)row * gpr;
     const int g0 = ct * kUnitBlocks + (lane >> 2), g1 = g0 + 16;
-    const uint4 a = blocks[(row_base + min(g0, gpr - 1)) * 4 + (lane & 3)];
-    const uint4 b = blocks[(row_base + min(g1, gpr - 1)) * 4 + (lane & 3)];
+    u.v0 = blocks[(row_base + min(g0, gpr - 1)) * 4 + (lane & 3)];
+    u.v1 = blocks[(row_base + min(g1, gpr - 1)) * 4 + (lane & 3)];
     const int g = ct * kUnitBlocks + (lane & (kUnitBlocks - 1));
     u.meta = meta[row_base + min(g, gpr - 1)];
-    const bool in0 = g0 < gpr, in1 = g1 < gpr;
-    u.v0 = make_uint4(in0 ? a.x : 0u, in0 ? a.y : 0u, in0 ? a.z : 0u, in0 ? a.w : 0u);
-    u.v1 = make_uint4(in1 ? b.x : 0u, in1 ? b.y : 0u, in1 ? b.z : 0u, in1 ? b.w : 0u);
     return u;
 }
 __device__ __forceinline__ void store_unit(uint32_t* wbuf, const UnitLoad& u, int lane) {
