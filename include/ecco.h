@@ -117,7 +117,7 @@ int ecco_encode(const ecco_model* m, const uint16_t* src, size_t n_groups,
                 void* blocks, uint32_t* meta, void* stream);
 
 /* Section 4.2: pattern retrieval, Huffman decode, centroid x scale.  dst: device, n_groups*128 FP16,
- * 16-byte aligned.  Same errors as ecco_encode. */
+ * 16-byte aligned.  Same errors as ecco_encode, plus ESHAPE for n_groups >= 2^31 - 32. */
 int ecco_decode(const ecco_model* m, const void* blocks, const uint32_t* meta, size_t n_groups,
                 uint16_t* dst, void* stream);
 

@@ -24,6 +24,9 @@ namespace {
 constexpr int kStride = kBlockWords + 1;  // LDS words per staged block (last one is a zero pad)
 constexpr int kHalf = kGroup / 2;         // values per chain
 
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+
 #define ECCO_HIP_CHECK(expr) do { if ((expr) != hipSuccess) return ECCO_EHIP; } while (0)
 
 __device__ __forceinline__ float half_bits_f(uint32_t bits) { return __half2float(__ushort_as_half((unsigned short)bits)); }
@@ -186,69 +189,8 @@ __device__ __forceinline__ void decode_chain(const uint32_t* w, uint32_t start, 
 }
 
 // ---- payload staging ------------------------------------------------------------------------------------
-// `count` consecutive blocks starting at block `first` -> LDS slots 0..count-1
-__device__ inline void stage_linear(uint32_t* lds, const uint4* blocks, size_t first, int count) {
-    const uint4* src = blocks + first * 4;
-    for (int i = threadIdx.x; i < count * 4; i += blockDim.x) {
-        uint4 v = src[i];
-        uint32_t* d = lds + (i >> 2) * kStride + (i & 3) * 4;
-        d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
-    }
-}
 __device__ inline void zero_pads(uint32_t* lds, int slots) {
     for (int i = threadIdx.x; i < slots; i += blockDim.x) lds[i * kStride + kBlockWords] = 0u;
-}
-
-// ---- ecco_decode / ecco_decode_indices ---------------------------------------------------------------
-constexpr int kDecThreads = 1024;
-constexpr int kDecBlocks = kDecThreads / 2;  // blocks per tile: two lanes per block
-inline size_t decode_lds_bytes(int S) { return (table_words(S) + (size_t)kDecBlocks * kStride + 4) * 4; }  // + the word a chain may read past the last slot
-
-template <bool kLong, bool kIndices>
-__global__ __launch_bounds__(kDecThreads) void decode_kernel(const uint32_t* __restrict__ dev, int S,
-                                                             const uint4* __restrict__ blocks, const uint32_t* __restrict__ meta,
-                                                             size_t n_groups, void* __restrict__ dst) {
-    extern __shared__ __align__(16) uint32_t smem[];
-    const Tables T = stage_tables(smem, dev, S);
-    uint32_t* payload = smem + table_words(S);
-    zero_pads(payload, kDecBlocks);
-    // lane layout: waves 0..7 take the first half of blocks 0..511, waves 8..15 the second half
-    const int slot = threadIdx.x & (kDecBlocks - 1);
-    const int half = threadIdx.x / kDecBlocks;
-    for (size_t first = (size_t)blockIdx.x * kDecBlocks; first < n_groups; first += (size_t)gridDim.x * kDecBlocks) {
-        const size_t left = n_groups - first;
-        const int count = left < (size_t)kDecBlocks ? (int)left : kDecBlocks;
-        __syncthreads();
-        stage_linear(payload, blocks, first, count);
-        __syncthreads();
-        if (slot < count) {
-            const size_t g = first + slot;
-            const Lane L = lane_setup(T, meta[g], S);
-            const uint32_t* w = payload + slot * kStride;
-            const uint32_t start = half ? L.second_start : 0u;
-            if (kIndices) {
-                uint4* out = reinterpret_cast<uint4*>(static_cast<uint8_t*>(dst) + g * kGroup + half * kHalf);
-                uint32_t acc[4] = {0, 0, 0, 0};
-                decode_chain<kLong, kHalf>(w, start, L, [&](int i, uint32_t e) {
-                    acc[(i >> 2) & 3] |= ((e >> 8) & 15u) << (8 * (i & 3));
-                    if ((i & 15) == 15) {
-                        out[i >> 4] = make_uint4(acc[0], acc[1], acc[2], acc[3]);
-                        acc[0] = acc[1] = acc[2] = acc[3] = 0;
-                    }
-                });
-            } else {
-                uint4* out = reinterpret_cast<uint4*>(static_cast<uint16_t*>(dst) + g * kGroup + half * kHalf);
-                uint32_t acc[4] = {0, 0, 0, 0};
-                decode_chain<kLong, kHalf>(w, start, L, [&](int i, uint32_t e) {
-                    acc[(i >> 1) & 3] |= dequant_bits(e >> 16, L.scale) << (16 * (i & 1));
-                    if ((i & 7) == 7) {
-                        out[i >> 3] = make_uint4(acc[0], acc[1], acc[2], acc[3]);
-                        acc[0] = acc[1] = acc[2] = acc[3] = 0;
-                    }
-                });
-            }
-        }
-    }
 }
 
 // ---- tiles of the fused kernels ---------------------------------------------------------------------------
@@ -468,6 +410,96 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_kernel(const uint32_t* __re
     }
 }
 
+// ---- ecco_decode / ecco_decode_indices ---------------------------------------------------------------
+// The streaming scheme of the batch-1 GEMV on a linear array of blocks: a unit is 32 consecutive
+// groups, lane l decodes chain l / 32 of block l % 32, a workgroup takes a contiguous range of units
+// and its wavefronts stride through it.  A lane ends up with 128 contiguous output bytes, 16 at a
+// time; written directly, one store instruction would touch 64 different lines with 16 bytes each,
+// and the L2 request rate, not bandwidth, would bound the kernel (measured: 13 of 21 us on the
+// 4096 x 4096 matrix).  So the FP16 values pass through a per-wavefront LDS image, 32 values per
+// chain at a time, and are read back so that adjacent lanes hold adjacent 16-byte pieces: four lanes
+// write the 64 contiguous bytes a segment gets per pass.  The image is swizzled (piece c of segment
+// s sits at 4 s + (c ^ (s / 4) % 4)) so that the transposed reads are conflict-free.  Twelve
+// wavefronts with a 4 KB image each fit 160 KB of LDS next to the S = 64 tables (sixteen with 2 KB
+// images and 32-byte pieces measured slower, also on small inputs).
+constexpr int kDecWaves = 12;
+struct DecCfg {
+    static constexpr int kPass = 32;                               // values per chain and pass
+    static constexpr int kPieces = kPass / 8;                      // 16-byte pieces per segment and pass
+    static constexpr int kImageWords = 64 * kPieces * 4;           // 64 segments
+    static constexpr int kWaveWords = kUnitWords + kImageWords;    // private LDS of a wavefront
+};
+inline size_t decode_lds_bytes(int S) { return (table_words(S) + (size_t)kDecWaves * DecCfg::kWaveWords) * 4; }
+
+template <bool kLong, bool kIndices>
+__global__ __launch_bounds__(kDecWaves * 64) void decode_kernel(const uint32_t* __restrict__ dev, int S,
+                                                              const uint4* __restrict__ blocks, const uint32_t* __restrict__ meta,
+                                                              int n_groups, int units_per_wg, void* __restrict__ dst) {
+    using Cfg = DecCfg;
+    extern __shared__ __align__(16) uint32_t smem[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const Tables T = stage_tables(smem, dev, S);
+    uint32_t* wbuf = smem + table_words(S) + wave * Cfg::kWaveWords;
+    uint4* image = reinterpret_cast<uint4*>(wbuf + kUnitWords);
+    if (lane < kUnitBlocks) wbuf[lane * kStride + kBlockWords] = 0u;
+    if (lane == 0) wbuf[kUnitBlocks * kStride] = 0u;
+    __syncthreads();
+
+    const int total_units = (n_groups + kUnitBlocks - 1) / kUnitBlocks;
+    const int u_end = min(total_units, (int)(blockIdx.x + 1) * units_per_wg);
+    int u = blockIdx.x * units_per_wg + wave;
+    UnitLoad pre;
+    if (u < u_end) pre = load_unit(blocks, meta, 0, n_groups, u, lane);
+    const int blk = lane & (kUnitBlocks - 1), half = lane >> 5, seg = blk * 2 + half;  // segment = 128 output bytes
+    for (; u < u_end; u += kDecWaves) {
+        store_unit(wbuf, pre, lane);
+        const uint32_t mw = pre.meta;
+        if (u + kDecWaves < u_end) pre = load_unit(blocks, meta, 0, n_groups, u + kDecWaves, lane);
+        const Lane L = lane_setup(T, mw, S);
+        const int g = u * kUnitBlocks + blk;
+        const uint32_t* w = wbuf + blk * kStride;
+        const uint32_t start = half ? L.second_start : 0u;
+        if (kIndices) {
+            uint4* out = reinterpret_cast<uint4*>(static_cast<uint8_t*>(dst) + (size_t)g * kGroup + half * kHalf);
+            uint32_t acc[4] = {0, 0, 0, 0};
+            decode_chain<kLong, kHalf>(w, start, L, [&](int i, uint32_t e) {
+                acc[(i >> 2) & 3] |= ((e >> 8) & 15u) << (8 * (i & 3));
+                if ((i & 15) == 15) {
+                    if (g < n_groups) out[i >> 4] = make_uint4(acc[0], acc[1], acc[2], acc[3]);
+                    acc[0] = acc[1] = acc[2] = acc[3] = 0;
+                }
+            });
+        } else {
+            uint8_t* obase = static_cast<uint8_t*>(dst) + (size_t)u * kUnitBlocks * kGroup * 2;  // the unit's 8 KB of output
+            const _Float16 sh = __builtin_bit_cast(_Float16, (unsigned short)(mw & 0xFFFFu));
+            const half2_t s2 = {sh, sh};
+            uint32_t acc[4] = {0, 0, 0, 0};
+            uint32_t pk = 0;
+            decode_chain<kLong, kHalf>(w, start, L, [&](int i, uint32_t e) {
+                if ((i & 1) == 0) {
+                    pk = e >> 16;
+                    return;
+                }
+                // fp16(centroid * scale) for two values: the packed FP16 product rounds once, like the FP32 rule
+                acc[(i >> 1) & 3] = __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2_t, pk | (e & 0xFFFF0000u)) * s2);
+                if ((i & 7) != 7) return;
+                const int c = (i >> 3) & (Cfg::kPieces - 1);
+                image[seg * Cfg::kPieces + (c ^ ((seg >> 2) & (Cfg::kPieces - 1)))] = make_uint4(acc[0], acc[1], acc[2], acc[3]);
+                if ((i & (Cfg::kPass - 1)) != Cfg::kPass - 1) return;
+                const int pass = i / Cfg::kPass;
+#pragma unroll
+                for (int k = 0; k < Cfg::kPieces; ++k) {
+                    const int n = k * 64 + lane, s = n / Cfg::kPieces, cc = n & (Cfg::kPieces - 1);
+                    const uint4 v = image[s * Cfg::kPieces + (cc ^ ((s >> 2) & (Cfg::kPieces - 1)))];
+                    if (u * kUnitBlocks + (s >> 1) < n_groups)
+                        *reinterpret_cast<uint4*>(obase + s * (kHalf * 2) + pass * (Cfg::kPass * 2) + cc * 16) = v;
+                }
+            });
+        }
+    }
+}
+
 // ---- ecco_decode_gemv, batch 2..16: MFMA tile ------------------------------------------------------------
 // Same 64 x 8 tile and staging as the batch-1 kernel, but a wavefront now owns 32 rows of one column
 // group with BOTH chains: lane l decodes chain l / 32 of row l % 32.  Eight values per lane and step
@@ -480,8 +512,6 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_kernel(const uint32_t* __re
 constexpr int kTileRows = 64;
 constexpr int kTileGroups = 8;
 constexpr int kMaxWsTiles = (int)(kWsFloats / 16 / kTileRows);  // row tiles x split that fit the workspace
-typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
-typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef float float16_t __attribute__((ext_vector_type(16)));
 constexpr int kXRow = kTileGroups * kGroup + 8;  // halves per batch row of the x tile in LDS (16-byte skew between rows)
 constexpr int kMaxBatch = 16;
@@ -980,16 +1010,19 @@ static int decode_common(const ecco_model* m, const void* blocks, const uint32_t
     if (model_ready(m) != ECCO_OK) return ECCO_EINVAL;
     if (n_groups == 0) return ECCO_OK;  // nothing to do; pointers may be null
     if (!blocks || !meta || !dst) return ECCO_EINVAL;
+    if (n_groups > (size_t)0x7FFFFFFF - kUnitBlocks) return ECCO_ESHAPE;
     if (!aligned(blocks, 64) || !aligned(dst, 16) || !aligned(meta, 4)) return ECCO_EALIGN;
-    const size_t tiles = (n_groups + kDecBlocks - 1) / kDecBlocks;
-    const int grid = (int)std::min<size_t>(tiles, (size_t)cu_count(m->device) * 4);
+    const int units = (int)((n_groups + kUnitBlocks - 1) / kUnitBlocks);
+    const int cus = cu_count(m->device);
+    const int units_per_wg = std::max(kDecWaves, (units + cus - 1) / cus);
+    const int grid = (units + units_per_wg - 1) / units_per_wg;
     const size_t lds = decode_lds_bytes(m->S);
     const bool lng = m->max_len > kPeekBits;
     auto launch = [&](auto kernel) -> int {
         int rc = allow_lds(kernel, lds);
         if (rc != ECCO_OK) return rc;
-        hipLaunchKernelGGL(kernel, dim3(grid), dim3(kDecThreads), lds, static_cast<hipStream_t>(stream), m->dev, m->S,
-                           static_cast<const uint4*>(blocks), meta, n_groups, dst);
+        hipLaunchKernelGGL(kernel, dim3(grid), dim3(kDecWaves * 64), lds, static_cast<hipStream_t>(stream), m->dev, m->S,
+                           static_cast<const uint4*>(blocks), meta, (int)n_groups, units_per_wg, dst);
         ECCO_HIP_CHECK(hipGetLastError());
         return ECCO_OK;
     };
