@@ -648,7 +648,6 @@ __global__ __launch_bounds__(kGemvThreads) void gemm_kernel(const uint32_t* __re
 constexpr int kEncThreads = 256;
 constexpr int kEncWaves = kEncThreads / 64;
 
-__device__ inline float wave_xor_add(float v, int mask) { return __fadd_rn(v, __shfl_xor(v, mask)); }
 __device__ inline void wave_lds_fence() {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -662,40 +661,58 @@ struct EncLds {
     uint32_t* bits;         // per wave 16 words
 };
 
-// Encodes the group whose two values of this lane are (hx0, hx1) as FP16 bits; lanes 0..15 return
-// one payload word each in *word, every lane the meta word in *meta.
-__device__ inline void encode_group(const EncLds& E, int S, uint32_t hx0, uint32_t hx1, uint32_t* word, uint32_t* meta) {
-    const int lane = threadIdx.x & 63;
-    // scale: the largest magnitude, as an FP16 bit pattern
+// The group's scale: the largest magnitude among the 128 values (two per lane), as an FP16 bit pattern.
+__device__ inline uint32_t group_scale_bits(uint32_t hx0, uint32_t hx1) {
     uint32_t smax = max(hx0 & 0x7FFFu, hx1 & 0x7FFFu);
     for (int m = 1; m < 64; m <<= 1) smax = max(smax, (uint32_t)__shfl_xor((int)smax, m));
-    const float s = half_bits_f(smax);
-    // reconstructed values of every pattern: fp16(centroid * s), kept as FP32
-    for (int i = lane; i < S * kK; i += 64) E.recon[i] = half_bits_f(dequant_bits(__half_as_ushort(E.cent[i]), s));
-    if (lane < kBlockWords) E.bits[lane] = 0;
+    return smax;
+}
+
+struct EncChoice {
+    float sse;         // squared error of the best pattern so far (uniform over the wavefront)
+    int pattern;
+    uint32_t idx;      // this lane's two indices: value 2l in bits 3:0, value 2l+1 in bits 7:4
+};
+
+// Pattern search over patterns [p0, p1) for the group whose two values of this lane are (x0, x1):
+// reconstructed values fp16(centroid * s) of those patterns into E.recon, nearest value per element
+// (strict <: the lowest index wins a tie), squared errors summed by the balanced tree, least sum
+// wins (strict <: the lowest pattern wins a tie).  p0 < p1.
+__device__ inline EncChoice search_patterns(const EncLds& E, int p0, int p1, float s, float x0, float x1) {
+    const int lane = threadIdx.x & 63;
+    for (int i = p0 * kK + lane; i < p1 * kK; i += 64) E.recon[i] = half_bits_f(dequant_bits(__half_as_ushort(E.cent[i]), s));
     wave_lds_fence();
-    const float x0 = half_bits_f(hx0), x1 = half_bits_f(hx1);
-    float best = 0.0f;
-    int best_p = 0;
-    uint32_t best_idx = 0;
-    for (int p = 0; p < S; ++p) {
+    EncChoice best{0.0f, p0, 0u};
+    for (int p = p0; p < p1; ++p) {
         const float* r = E.recon + p * kK;
-        const float r0 = r[0];
-        float d0 = fabsf(__fsub_rn(x0, r0)), d1 = fabsf(__fsub_rn(x1, r0));
+        float d0 = fabsf(__fsub_rn(x0, r[0])), d1 = fabsf(__fsub_rn(x1, r[0]));
         uint32_t k0 = 0, k1 = 0;
-        float q0 = r0, q1 = r0;
 #pragma unroll
         for (int k = 1; k < kK; ++k) {
             const float rk = r[k];
             const float a = fabsf(__fsub_rn(x0, rk)), b = fabsf(__fsub_rn(x1, rk));
-            if (a < d0) { d0 = a; k0 = k; q0 = rk; }   // strict: the lowest index wins a tie
-            if (b < d1) { d1 = b; k1 = k; q1 = rk; }
+            const bool c0 = a < d0, c1 = b < d1;  // strict: the lowest index wins a tie
+            k0 = c0 ? (uint32_t)k : k0;
+            k1 = c1 ? (uint32_t)k : k1;
+            d0 = c0 ? a : d0;
+            d1 = c1 ? b : d1;
         }
-        const float e0 = __fsub_rn(x0, q0), e1 = __fsub_rn(x1, q1);
-        float v = __fadd_rn(__fmul_rn(e0, e0), __fmul_rn(e1, e1));  // tree level 0: values 2l and 2l+1
-        for (int m = 1; m < 64; m <<= 1) v = wave_xor_add(v, m);    // levels 1..6
-        if (p == 0 || v < best) { best = v; best_p = p; best_idx = k0 | (k1 << 4); }
+        const float e0 = __fsub_rn(x0, r[k0]), e1 = __fsub_rn(x1, r[k1]);
+        // tree level 0: values 2l and 2l+1; levels 1..6 over the lanes: aligned blocks of 2, 4, 8, 16 lanes by
+        // cross-lane moves (every lane of a block holds the block's sum, so a mirror pairs the same two
+        // blocks as the xor butterfly), then (row 0 + row 1) + (row 2 + row 3)
+        const float v = wave_sum(__fadd_rn(__fmul_rn(e0, e0), __fmul_rn(e1, e1)));
+        if (p == p0 || v < best.sse) best = EncChoice{v, p, k0 | (k1 << 4)};
     }
+    return best;
+}
+
+// Packs the group with the chosen pattern and indices: lanes 0..15 return one payload word each in
+// *word, every lane the meta word in *meta.
+__device__ inline void pack_group(const EncLds& E, uint32_t smax, int best_p, uint32_t best_idx, uint32_t* word, uint32_t* meta) {
+    const int lane = threadIdx.x & 63;
+    if (lane < kBlockWords) E.bits[lane] = 0;
+    wave_lds_fence();
     // codes of the chosen pattern, bit positions by an inclusive scan over lanes
     const uint32_t c0 = E.enc[best_p * kK + (best_idx & 15u)], c1 = E.enc[best_p * kK + (best_idx >> 4)];
     const uint32_t l0 = c0 >> 16, l1 = c1 >> 16;
@@ -721,6 +738,13 @@ __device__ inline void encode_group(const EncLds& E, int S, uint32_t hx0, uint32
     *word = lane < kBlockWords ? E.bits[lane] : 0u;
     *meta = smax | ((uint32_t)best_p << 16) | (raw ? (1u << 22) : 0u) | ((raw ? 4u * kHalf : mid) << 23);
     wave_lds_fence();
+}
+
+// One wavefront encodes one group (hx0, hx1: this lane's two values as FP16 bits).
+__device__ inline void encode_group(const EncLds& E, int S, uint32_t hx0, uint32_t hx1, uint32_t* word, uint32_t* meta) {
+    const uint32_t smax = group_scale_bits(hx0, hx1);
+    const EncChoice c = search_patterns(E, 0, S, half_bits_f(smax), half_bits_f(hx0), half_bits_f(hx1));
+    pack_group(E, smax, c.pattern, c.idx, word, meta);
 }
 
 constexpr size_t enc_lds_bytes(int S) { return (size_t)S * kK * 2 + (size_t)S * kK * 4 + (size_t)kEncWaves * ((size_t)S * kK * 4 + kBlockWords * 4); }
@@ -758,7 +782,10 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const uint32_t* __r
     }
 }
 
-// grid: (ceil(B*H / 4), 2); y = 0 encodes K, y = 1 encodes V
+// grid: (B*H, 2); y = 0 encodes K, y = 1 encodes V.  One workgroup per new group: the append is a
+// latency problem (B*H*2 groups, far fewer than the chip has wavefront slots), so the four wavefronts
+// of the workgroup split the pattern search, a quarter of the patterns each, and wavefront 0 packs
+// the winner (ascending pattern ranges, strict <: the lowest pattern still wins a tie).
 __global__ __launch_bounds__(kEncThreads) void kv_append_kernel(const uint32_t* __restrict__ dev_k, int Sk,
                                                                 const uint32_t* __restrict__ dev_v, int Sv,
                                                                 const uint32_t* __restrict__ k_new, const uint32_t* __restrict__ v_new,
@@ -766,18 +793,36 @@ __global__ __launch_bounds__(kEncThreads) void kv_append_kernel(const uint32_t* 
                                                                 uint32_t* __restrict__ v_blocks, uint32_t* __restrict__ v_meta,
                                                                 const int32_t* __restrict__ seq_len, int B, int H, int T_max) {
     extern __shared__ __align__(16) unsigned char smem_enc[];
+    __shared__ float cand_sse[kEncWaves];
+    __shared__ int cand_pattern[kEncWaves];
+    __shared__ uint32_t cand_idx[kEncWaves][64];
     const bool is_v = blockIdx.y != 0;  // uniform per workgroup, so each workgroup stages one model
     const int S = is_v ? Sv : Sk;
     EncLds E = setup_enc_lds(smem_enc, is_v ? dev_v : dev_k, S);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int bh = blockIdx.x * kEncWaves + wave;
-    if (bh >= B * H) return;
+    const int bh = blockIdx.x;
     const int t = seq_len[bh / H];
-    if (t < 0 || t >= T_max) return;
+    if (t < 0 || t >= T_max) return;  // uniform over the workgroup
     const uint32_t* src = (is_v ? v_new : k_new) + (size_t)bh * (kGroup / 2);
     const uint32_t pair = src[lane];
+    const uint32_t smax = group_scale_bits(pair & 0xFFFFu, pair >> 16);
+    const int per = (S + kEncWaves - 1) / kEncWaves;
+    const int p0 = wave * per, p1 = min(S, p0 + per);
+    if (p0 < p1) {
+        const EncChoice c = search_patterns(E, p0, p1, half_bits_f(smax), half_bits_f(pair & 0xFFFFu), half_bits_f(pair >> 16));
+        cand_idx[wave][lane] = c.idx;
+        if (lane == 0) {
+            cand_sse[wave] = c.sse;
+            cand_pattern[wave] = c.pattern;
+        }
+    }
+    __syncthreads();
+    if (wave != 0) return;
+    int win = 0;
+    for (int w = 1; w < kEncWaves; ++w)
+        if (w * per < S && cand_sse[w] < cand_sse[win]) win = w;
     uint32_t word, mw;
-    encode_group(E, S, pair & 0xFFFFu, pair >> 16, &word, &mw);
+    pack_group(E, smax, cand_pattern[win], cand_idx[win][lane], &word, &mw);
     const size_t g = (size_t)bh * T_max + t;
     uint32_t* blocks = is_v ? v_blocks : k_blocks;
     uint32_t* meta = is_v ? v_meta : k_meta;
@@ -1092,7 +1137,7 @@ int ecco_kv_append(const ecco_model* mk, const ecco_model* mv, const uint16_t* k
     if (model_ready(mk) != ECCO_OK || model_ready(mv) != ECCO_OK || mk->device != mv->device) return ECCO_EINVAL;
     if (B <= 0 || H <= 0 || T_max <= 0) return ECCO_ESHAPE;
     if (!aligned(k_blocks, 64) || !aligned(v_blocks, 64) || !aligned(k_new, 4) || !aligned(v_new, 4)) return ECCO_EALIGN;
-    dim3 grid((B * H + kEncWaves - 1) / kEncWaves, 2);
+    dim3 grid(B * H, 2);
     hipLaunchKernelGGL(kv_append_kernel, grid, dim3(kEncThreads), enc_lds_bytes(std::max(mk->S, mv->S)),
                        static_cast<hipStream_t>(stream), mk->dev, mk->S, mv->dev, mv->S,
                        reinterpret_cast<const uint32_t*>(k_new), reinterpret_cast<const uint32_t*>(v_new),
