@@ -324,3 +324,40 @@ def test_full_mlp_down(dev, oracle):
 def test_proj70b_row_slab(dev, oracle):
     # the 70B-class projection at its real row length (224 column groups), first 1024 rows
     _full_weight_case(dev, oracle, "proj70b", 0, rows_limit=1024, batches=(1,))
+
+
+def test_full_kv_cache(dev, oracle):
+    # the KV configuration at full size (8 x 32 heads x 4096 tokens, patterns fitted on a 512-token prefix), in the
+    # launch shapes the benchmark times; sampled heads are checked one by one against the oracle
+    c = W.CONFIGS["kv"]
+    B, H, T, S = c["batch"], c["heads"], c["tokens"], c["S"]
+    k, v = W.kv_cache(B, H, T, 128, c["seeds"][0])
+    cal = c["calib_tokens"]
+    mk = E.ecco_model_to_device(E.ecco_fit_patterns(k[:, :, :cal], S, 12, c["seeds"][0]), 0)
+    mv = E.ecco_model_to_device(E.ecco_fit_patterns(v[:, :, :cal], S, 12, c["seeds"][0] + 1), 0)
+    assert oracle.verify_model(mk.centroids, mk.code_lens) == 0 and oracle.verify_model(mv.centroids, mv.code_lens) == 0
+    kb, km = E.ecco_encode(mk, t16(k, dev)); vb, vm = E.ecco_encode(mv, t16(v, dev))
+    kb = kb.view(B, H, T, 64); vb = vb.view(B, H, T, 64); km = km.view(B, H, T); vm = vm.view(B, H, T)
+    q = W.activation(B * H, 128, c["q_seed"]).reshape(B, H, 128)
+    seq = np.array([T, T, T - 1, 2500, 33, 1, T, 777], np.int32)
+    out = E.ecco_kv_attend(mk, mv, t16(q, dev), kb, km, vb, vm, ti32(seq, dev), B, H, T).cpu().numpy()
+    assert np.isfinite(out).all()
+    one = np.ones(1, np.int32)
+    for b, h in [(0, 0), (1, 17), (2, 31), (3, 5), (4, 9), (5, 2), (7, 30)]:
+        okb, okm = oracle.encode(mk.centroids, mk.code_lens, np.ascontiguousarray(k[b, h]).view(np.uint16))
+        ovb, ovm = oracle.encode(mv.centroids, mv.code_lens, np.ascontiguousarray(v[b, h]).view(np.uint16))
+        assert np.array_equal(kb[b, h].cpu().numpy(), okb.reshape(T, 64)) and np.array_equal(np_meta(km[b, h]), okm)
+        assert np.array_equal(vb[b, h].cpu().numpy(), ovb.reshape(T, 64)) and np.array_equal(np_meta(vm[b, h]), ovm)
+        want = oracle.kv_attend(mk.centroids, mk.code_lens, mv.centroids, mv.code_lens, np.ascontiguousarray(q[b, h]).view(np.uint16),
+                                okb, okm, ovb, ovm, one * seq[b], 1, 1, T)
+        assert rel_l2(out[b, h], want.reshape(128)) <= REL_L2, (b, h)
+    # append of one token per sequence at the last slot, on every head; sampled heads against the oracle
+    kb2, km2, vb2, vm2 = kb.clone(), km.clone(), vb.clone(), vm.clone()
+    kn = np.ascontiguousarray(k[:, :, 7]); vn = np.ascontiguousarray(v[:, :, 7])
+    pos = np.full(B, T - 1, np.int32)
+    E.ecco_kv_append(mk, mv, t16(kn, dev), t16(vn, dev), kb2, km2, vb2, vm2, ti32(pos, dev), B, H, T)
+    torch.cuda.synchronize()
+    assert torch.equal(kb2[:, :, : T - 1], kb[:, :, : T - 1]) and torch.equal(vm2[:, :, : T - 1], vm[:, :, : T - 1])
+    # token 7 encoded into slot T-1 must equal its encoding in slot 7 (same values, same model), on all heads
+    assert torch.equal(kb2[:, :, T - 1], kb[:, :, 7]) and torch.equal(km2[:, :, T - 1], km[:, :, 7])
+    assert torch.equal(vb2[:, :, T - 1], vb[:, :, 7]) and torch.equal(vm2[:, :, T - 1], vm[:, :, 7])
