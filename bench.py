@@ -74,6 +74,7 @@ def main():
     ap.add_argument("--eager", action="store_true", help="launch every call from Python with its own event pair instead of replaying a HIP graph")
     ap.add_argument("--only", default="", help="comma list of rows to run (kv_append,decode,gemv1,gemv8,gemv16,kv_attend)")
     ap.add_argument("--workload", default="proj7b", choices=["proj7b", "mlp_up", "mlp_down", "proj70b"])
+    ap.add_argument("--sweep", action="store_true", help="add an ecco_decode sweep over block counts 2^14..2^22 (as far as the workload has blocks)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (every box has one); run with --gpus 1")
@@ -245,6 +246,36 @@ def main():
             warm_ms = timed_replays(g, 2) / 100
             del g
 
+    # ---- standalone decode over growing block counts (the first n groups of every rotating copy) -----
+    sweep = None
+    if args.sweep:
+        sweep = []
+        for lg in range(14, 23):
+            n = 1 << lg
+            if n > n_groups:
+                break
+            def one_round(n=n):
+                for c in range(n_copies):
+                    E.ecco_decode(m, wb[c][:n], wm[c][:n], dec_out[:n])
+            if args.eager:
+                one_round()
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                one_round()
+                e1.record()
+                torch.cuda.synchronize()
+                t_ms = e0.elapsed_time(e1) / n_copies
+            else:
+                g = capture(one_round)
+                g.replay()
+                torch.cuda.synchronize()
+                replays = max(1, int(np.ceil(60 / n_copies)))
+                t_ms = timed_replays(g, replays) / (replays * n_copies)
+                del g
+            sweep.append({"n_groups": n, "us": t_ms * 1e3, "GBps_compressed_read": n * BYTES_PER_GROUP / (t_ms * 1e-3) / 1e9,
+                          "GBps_total_traffic": n * (BYTES_PER_GROUP + 256) / (t_ms * 1e-3) / 1e9})
+
     comp_bytes = n_groups * BYTES_PER_GROUP
     rows_out = {}
     for r in row_names:
@@ -288,7 +319,10 @@ def main():
                      "kernel": "fused decode-GEMV, batch 1", "bytes_per_launch": comp_bytes,
                      "avg_launch_ms": ms.get(metric_row)},
         "rows": rows_out,
+        "footprint": {"fp16_bytes": n_groups * 256, "compressed_bytes": comp_bytes, "ratio": 256.0 / BYTES_PER_GROUP},
     }
+    if sweep is not None:
+        out["decode_sweep"] = sweep
     if not args.no_cpu_baseline and want("gemv1"):
         out["cpu_baseline"] = cpu_baseline(m, blocks0.cpu().numpy(), meta0.cpu().numpy().view(np.uint32), rows, cols,
                                            xs[1].cpu().numpy())
