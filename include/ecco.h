@@ -131,9 +131,8 @@ int ecco_decode_indices(const ecco_model* m, const void* blocks, const uint32_t*
  *   W = rows x cols, stored as rows*(cols/128) blocks, row-major;   x  device, batch x cols FP16, 16-byte aligned
  *   y  device, batch x rows FP32:  y[b][r] = sum_c W[r][c] * x[b][c]  (FP32 accumulation)
  *   batch 1..16;  cols % 128 == 0;  cols <= 65536.
- * Partial sums of a launch that splits a row tile over workgroups pass through a workspace owned by
- * the model: two calls with the SAME model must not overlap in time (different streams); calls on one
- * stream, and calls with different models, are fine.
+ * A row is never split over workgroups and no device memory beyond the arguments and the model's
+ * tables is touched, so calls may overlap freely and the sum order is fixed (results are reproducible).
  * Errors: EINVAL, ESHAPE (cols, batch, rows <= 0), EALIGN, EHIP. */
 int ecco_decode_gemv(const ecco_model* m, const void* blocks, const uint32_t* meta,
                      int rows, int cols, const uint16_t* x, int batch, float* y, void* stream);

@@ -26,21 +26,16 @@ constexpr int kPeekEntries = 1 << kPeekBits;
 
 // Device memory of a model, one allocation, in 32-bit words:
 //   compact tables  [enc S x 16][centroids S x 8][longtab S x 16]   (a few KB; kernels expand them in LDS)
-//   workspace       partial sums of split fused-GEMV launches and their arrival counters
 // The decode table itself (S x 256 entries) is never stored in global memory: every workgroup
 // builds it in LDS from `enc` and the centroids, which costs less than fetching 64 KB per workgroup.
-constexpr int kWsCounters = 1024;
-constexpr size_t kWsFloats = 16 * 64 * 512;  // batch 16 x 64 rows x (row tiles x split <= 512)
 struct DevLayout {
     int S;
     constexpr size_t enc() const { return 0; }
     constexpr size_t cent() const { return (size_t)S * kK; }
     constexpr size_t longtab() const { return cent() + (size_t)S * kK / 2; }
     constexpr size_t table_words() const { return longtab() + (size_t)S * kK; }
-    constexpr size_t ws_counter() const { return (table_words() + 63) / 64 * 64; }
-    constexpr size_t ws_partial() const { return ws_counter() + kWsCounters; }
-    constexpr size_t image_words() const { return ws_partial(); }  // what the host image holds (workspace excluded)
-    constexpr size_t total_bytes() const { return (ws_partial() + kWsFloats) * 4; }
+    constexpr size_t image_words() const { return table_words(); }
+    constexpr size_t total_bytes() const { return image_words() * 4; }
 };
 
 // longtab entry j (canonical position j): bits 11:0 the code left-aligned in 12 bits,

@@ -189,57 +189,8 @@ __device__ __forceinline__ void decode_chain(const uint32_t* w, uint32_t start, 
 }
 
 // ---- payload staging ------------------------------------------------------------------------------------
-__device__ inline void zero_pads(uint32_t* lds, int slots) {
-    for (int i = threadIdx.x; i < slots; i += blockDim.x) lds[i * kStride + kBlockWords] = 0u;
-}
 
-// ---- tiles of the fused kernels ---------------------------------------------------------------------------
-// A workgroup of 1024 threads works on tiles of 512 blocks (R rows x C column groups).  The payload
-// of a tile is fetched by the first kLoaders threads (wavefronts 0..7), four 16-byte pieces each;
-// the other wavefronts build the decode tables meanwhile.  Loads of one wavefront return in issue
-// order, so keeping the two jobs in different wavefronts lets the table build proceed while the
-// payload is still on its way from HBM.  In LDS block (r, c) of the tile sits in slot c * R + r.
 constexpr int kGemvThreads = 1024;
-constexpr int kTileBlocks = 512;
-constexpr int kLoaders = 512;
-constexpr int kPiecesPerLoader = kTileBlocks * 4 / kLoaders;
-struct TileLoad {
-    uint4 v[kPiecesPerLoader];
-};
-// this thread's pieces of tile (row_tile, ct); pieces outside the matrix are zero
-template <int R, int C>
-__device__ __forceinline__ TileLoad load_tile(const uint4* __restrict__ blocks, int rows, int gpr, int row_tile, int ct) {
-    static_assert(R * C == kTileBlocks, "tile size");
-    TileLoad t;
-#pragma unroll
-    for (int j = 0; j < kPiecesPerLoader; ++j) {
-        const int q = threadIdx.x + j * kLoaders;
-        const int r = q / (C * 4), c = (q >> 2) % C, piece = q & 3;
-        const int gr = min(row_tile * R + r, rows - 1), gc = ct * C + c;
-        t.v[j] = gc < gpr ? blocks[((size_t)gr * gpr + gc) * 4 + piece] : make_uint4(0, 0, 0, 0);
-    }
-    return t;
-}
-template <int R, int C>
-__device__ __forceinline__ void store_tile(uint32_t* payload, const TileLoad& t) {
-#pragma unroll
-    for (int j = 0; j < kPiecesPerLoader; ++j) {
-        const int q = threadIdx.x + j * kLoaders;
-        const int r = q / (C * 4), c = (q >> 2) % C, piece = q & 3;
-        uint32_t* d = payload + (c * R + r) * kStride + piece * 4;
-        d[0] = t.v[j].x; d[1] = t.v[j].y; d[2] = t.v[j].z; d[3] = t.v[j].w;
-    }
-}
-// tables by the non-loader threads (the caller synchronises afterwards)
-template <bool kLong>
-__device__ __forceinline__ void build_tables_by_builders(uint32_t* smem, const uint32_t* __restrict__ dev, int S) {
-    for (int t = threadIdx.x - kLoaders; t < S * kK; t += kGemvThreads - kLoaders) build_table_item(smem, S, t, load_table_item(dev, S, t));
-    if (kLong) {
-        const DevLayout D{S};
-        for (int i = threadIdx.x - kLoaders; i < S * kK; i += kGemvThreads - kLoaders) smem[S * (kPeekEntries + kK) + i] = dev[D.longtab() + i];
-        for (int i = threadIdx.x - kLoaders; i < S * kK / 2; i += kGemvThreads - kLoaders) smem[S * (kPeekEntries + 2 * kK) + i] = dev[D.cent() + i];
-    }
-}
 
 // ---- ecco_decode_gemv, batch 1 ----------------------------------------------------------------------------
 // A workgroup (one per compute unit) owns a band of R consecutive rows; its work is cut into units
@@ -500,146 +451,116 @@ __global__ __launch_bounds__(kDecWaves * 64) void decode_kernel(const uint32_t* 
     }
 }
 
-// ---- ecco_decode_gemv, batch 2..16: MFMA tile ------------------------------------------------------------
-// Same 64 x 8 tile and staging as the batch-1 kernel, but a wavefront now owns 32 rows of one column
-// group with BOTH chains: lane l decodes chain l / 32 of row l % 32.  Eight values per lane and step
-// are exactly the A operand of v_mfma_f32_32x32x16_f16 (row l % 32, k slice l / 32), the matching
-// eight activations of batch row l % 32 are the B operand (read from an LDS copy of x; lanes past the
-// batch hold zeros), and the 32 x 32 FP32 accumulator (rows x batch) lives in registers across all
-// column tiles.  The weights enter the MFMA as fp16(centroid * scale) -- packed FP16 multiplies,
-// which round exactly like the FP32-multiply-then-round rule -- so no per-row scaling of the
-// accumulator is needed.  The 8 column-group wavefronts of a row half are added through LDS.
-constexpr int kTileRows = 64;
-constexpr int kTileGroups = 8;
-constexpr int kMaxWsTiles = (int)(kWsFloats / 16 / kTileRows);  // row tiles x split that fit the workspace
-typedef float float16_t __attribute__((ext_vector_type(16)));
-constexpr int kXRow = kTileGroups * kGroup + 8;  // halves per batch row of the x tile in LDS (16-byte skew between rows)
+// ---- ecco_decode_gemv, batch 2..16: MFMA ------------------------------------------------------------------
+// The streaming scheme of the batch-1 kernel with the multiply-adds on the matrix cores.  A unit is
+// 16 rows x 2 column groups (32 blocks, 16 runs of 128 contiguous bytes): lane l decodes, for row
+// l % 16, chain (l / 16) % 2 of column group l / 32.  Eight decoded values of the lane are exactly
+// its A operand of v_mfma_f32_16x16x32_f16 (row l % 16, k slice l / 16); the B operand of the lane
+// is eight activations of batch row l % 16 at the columns of the chain of slice l / 16, which it
+// holds in registers for the unit (zeros past the batch); the 16 x 16 FP32 accumulator (rows x
+// batch) stays in registers over all units of a 16-row block.  The weights enter as
+// fp16(centroid * scale) -- packed FP16 multiplies, which round exactly like the
+// FP32-multiply-then-round rule -- so no per-row scaling of the accumulator is needed.  A workgroup
+// owns whole 16-row blocks (all their column groups), so nothing is split over workgroups: per row
+// block the 16 wavefronts add their accumulators through LDS in a fixed order.
+constexpr int kMmaRows = 16;
 constexpr int kMaxBatch = 16;
-inline size_t gemm_lds_bytes(int S) {
-    return (table_words(S) + (size_t)kTileBlocks * kStride) * 4 + (size_t)kMaxBatch * kXRow * 2 + 16;
+typedef float float4_t __attribute__((ext_vector_type(4)));
+inline size_t gemm_lds_bytes(int S) { return (table_words(S) + (size_t)kWaves * kUnitWords + (size_t)kWaves * kMmaRows * kMaxBatch) * 4; }
+
+// this lane's payload pieces and meta word of unit (rb, u): block (r, c) of the unit -- row 16 rb + r,
+// column group 2 u + c -- goes to slot 2 r + c.  Indices are clamped into the matrix (see load_unit).
+__device__ __forceinline__ UnitLoad load_unit16(const uint4* __restrict__ blocks, const uint32_t* __restrict__ meta,
+                                                int rows, int gpr, int rb, int u, int lane) {
+    UnitLoad t;
+    const int slot = lane >> 2, c = slot & 1;
+    const int cg = min(2 * u + c, gpr - 1);
+    const int r0 = min(rb * kMmaRows + (slot >> 1), rows - 1), r1 = min(rb * kMmaRows + 8 + (slot >> 1), rows - 1);
+    t.v0 = blocks[((size_t)r0 * gpr + cg) * 4 + (lane & 3)];
+    t.v1 = blocks[((size_t)r1 * gpr + cg) * 4 + (lane & 3)];
+    const int mr = min(rb * kMmaRows + (lane & 15), rows - 1), mc = min(2 * u + (lane >> 5), gpr - 1);
+    t.meta = meta[(size_t)mr * gpr + mc];
+    return t;
 }
 
 template <bool kLong>
 __global__ __launch_bounds__(kGemvThreads) void gemm_kernel(const uint32_t* __restrict__ dev, int S,
                                                             const uint4* __restrict__ blocks, const uint32_t* __restrict__ meta,
-                                                            int rows, int cols, int split, int batch,
-                                                            const uint16_t* __restrict__ x, float* __restrict__ y,
-                                                            float* __restrict__ ws_partial, int* __restrict__ ws_counter) {
+                                                            int rows, int gpr, int rb_per_wg, int batch,
+                                                            const uint16_t* __restrict__ x, float* __restrict__ y) {
     extern __shared__ __align__(16) uint32_t smem[];
-    const int gpr = cols / kGroup;
-    const int row_tile = blockIdx.x / split, k0 = blockIdx.x % split;
-    const int col_tiles = (gpr + kTileGroups - 1) / kTileGroups;
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const bool loader = wave < kLoaders / 64;
-    const int cgl = wave >> 1, row_half = wave & 1;
-    const int chain = lane >> 5, n = lane & 31;               // this lane's chain, and its batch column in B / C
-    const int trow = row_half * 32 + (lane & 31);             // row inside the tile
-    const int row = min(row_tile * kTileRows + trow, rows - 1);
-    uint32_t* payload = smem + table_words(S);
-    _Float16* xt = reinterpret_cast<_Float16*>(payload + kTileBlocks * kStride);
-    int* last_flag = reinterpret_cast<int*>(xt + kMaxBatch * kXRow);
-    TileLoad pre;
-    if (loader) pre = load_tile<kTileRows, kTileGroups>(blocks, rows, gpr, row_tile, k0);
-    else build_tables_by_builders<kLong>(smem, dev, S);
-    uint32_t mw_next = (k0 * kTileGroups + cgl < gpr) ? meta[(size_t)row * gpr + k0 * kTileGroups + cgl] : 0u;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    uint32_t* wbuf = smem + table_words(S) + wave * kUnitWords;
+    float* part = reinterpret_cast<float*>(smem + table_words(S) + kWaves * kUnitWords);  // [wavefront][row 16][batch 16]
+    const int total_rb = (rows + kMmaRows - 1) / kMmaRows;
+    const int rb0 = blockIdx.x * rb_per_wg, rb1 = min(total_rb, rb0 + rb_per_wg);
+    const int upr = (gpr + 1) / 2;  // units per row block
+    const size_t cols = (size_t)gpr * kGroup;
+
+    TableItem item{0u, 0u};
+    if (tid < S * kK) item = load_table_item(dev, S, tid);
+    UnitLoad pre;
+    if (wave < upr) pre = load_unit16(blocks, meta, rows, gpr, rb0, wave, lane);
+    if (tid < S * kK) build_table_item(smem, S, tid, item);
+    if (kLong) {
+        const DevLayout D{S};
+        for (int i = tid; i < S * kK; i += kGemvThreads) smem[S * (kPeekEntries + kK) + i] = dev[D.longtab() + i];
+        for (int i = tid; i < S * kK / 2; i += kGemvThreads) smem[S * (kPeekEntries + 2 * kK) + i] = dev[D.cent() + i];
+    }
+    if (lane < kUnitBlocks) wbuf[lane * kStride + kBlockWords] = 0u;
+    if (lane == 0) wbuf[kUnitBlocks * kStride] = 0u;
     const Tables T = table_pointers(smem, S);
-    zero_pads(payload, kTileBlocks);
-    float16_t acc;
-#pragma unroll
-    for (int j = 0; j < 16; ++j) acc[j] = 0.0f;
-    for (int ct = k0; ct < col_tiles; ct += split) {
-        __syncthreads();  // the previous tile (payload and x) has been consumed
-        if (loader) store_tile<kTileRows, kTileGroups>(payload, pre);
-        // x tile: batch rows x 1024 columns of this column tile, 16 bytes per thread and pass
-        {
-            const int col0 = ct * kTileGroups * kGroup;
-            const int width = min(kTileGroups * kGroup, cols - col0);  // multiple of 128
-            for (int q = threadIdx.x; q < batch * (kTileGroups * kGroup / 8); q += kGemvThreads) {
-                const int b = q / (kTileGroups * kGroup / 8), c8 = (q % (kTileGroups * kGroup / 8)) * 8;
-                uint4 v = make_uint4(0, 0, 0, 0);
-                if (c8 < width) v = *reinterpret_cast<const uint4*>(x + (size_t)b * cols + col0 + c8);
-                *reinterpret_cast<uint4*>(xt + b * kXRow + c8) = v;
+    __syncthreads();
+
+    const int r = lane & 15, c = lane >> 5, half = (lane >> 4) & 1;  // this lane's chain: row r, column group 2 u + c, chain `half`
+    const int n = lane & 15;                                          // its batch row in B and its column in the accumulator
+    for (int rb = rb0; rb < rb1; ++rb) {
+        float4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
+        for (int u = wave; u < upr; u += kWaves) {
+            store_unit(wbuf, pre, lane);
+            const uint32_t mw = pre.meta;
+            int un = u + kWaves, rbn = rb;
+            if (un >= upr) {
+                un = wave;
+                ++rbn;
             }
-        }
-        const int cg = ct * kTileGroups + cgl;
-        const bool active = cg < gpr;  // uniform over the wavefront
-        const uint32_t mw = mw_next;
-        if (ct + split < col_tiles) {
-            const int ncg = (ct + split) * kTileGroups + cgl;
-            mw_next = ncg < gpr ? meta[(size_t)row * gpr + ncg] : 0u;
-            if (loader) pre = load_tile<kTileRows, kTileGroups>(blocks, rows, gpr, row_tile, ct + split);
-        }
-        __syncthreads();
-        if (active) {
+            if (rbn < rb1) pre = load_unit16(blocks, meta, rows, gpr, rbn, un, lane);
+            const int cg = 2 * u + c;
+            uint4 bx[kHalf / 8];  // B: 64 activations of batch row n at this chain's columns
+#pragma unroll
+            for (int j = 0; j < kHalf / 8; ++j) bx[j] = make_uint4(0, 0, 0, 0);
+            if (n < batch && cg < gpr) {
+                const uint4* src = reinterpret_cast<const uint4*>(x + (size_t)n * cols + (size_t)cg * kGroup + half * kHalf);
+#pragma unroll
+                for (int j = 0; j < kHalf / 8; ++j) bx[j] = src[j];
+            }
             const Lane L = lane_setup(T, mw, S);
             const _Float16 sh = __builtin_bit_cast(_Float16, (unsigned short)(mw & 0xFFFFu));
             const half2_t s2 = {sh, sh};
-            const _Float16* xrow = xt + n * kXRow + cgl * kGroup + chain * kHalf;  // this lane's 64 activations (if n < batch)
-            uint32_t pk[4];
-            decode_chain<kLong, kHalf>(payload + (cgl * kTileRows + trow) * kStride, chain ? L.second_start : 0u, L,
-                                       [&](int i, uint32_t e) {
-                                           if ((i & 1) == 0) pk[(i >> 1) & 3] = e >> 16;
-                                           else pk[(i >> 1) & 3] |= e & 0xFFFF0000u;
-                                           if ((i & 7) == 7) {
-                                               half8_t a, b;
-#pragma unroll
-                                               for (int j = 0; j < 4; ++j) {
-                                                   const half2_t w2 = __builtin_bit_cast(half2_t, pk[j]) * s2;
-                                                   a[2 * j] = w2[0];
-                                                   a[2 * j + 1] = w2[1];
-                                               }
-#pragma unroll
-                                               for (int j = 0; j < 8; ++j) b[j] = (_Float16)0.0f;
-                                               if (n < batch) b = *reinterpret_cast<const half8_t*>(xrow + (i - 7));
-                                               acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc, 0, 0, 0);
-                                           }
-                                       });
+            uint32_t pk[4] = {0, 0, 0, 0};
+            decode_chain<kLong, kHalf>(wbuf + (2 * r + c) * kStride, half ? L.second_start : 0u, L, [&](int i, uint32_t e) {
+                if ((i & 1) == 0) {
+                    pk[(i >> 1) & 3] = e >> 16;
+                    return;
+                }
+                pk[(i >> 1) & 3] = __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2_t, pk[(i >> 1) & 3] | (e & 0xFFFF0000u)) * s2);
+                if ((i & 7) != 7) return;
+                const uint4 av = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, av), __builtin_bit_cast(half8_t, bx[i >> 3]), acc, 0, 0, 0);
+            });
         }
-    }
-    // accumulator layout of the 32x32 tile: register r of lane l is row 8 * (r / 4) + 4 * (l / 32) + r % 4, column l % 32
-    __syncthreads();
-    float* red = reinterpret_cast<float*>(payload);  // [cgl 8][row 64][batch 16] floats = 32 KB
-    if (n < kMaxBatch) {
+        // accumulator layout of the 16 x 16 tile: register j of lane l is row 4 * (l / 16) + j, column l % 16
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int i = 8 * (r >> 2) + 4 * chain + (r & 3);
-            red[(cgl * kTileRows + row_half * 32 + i) * kMaxBatch + n] = acc[r];
+        for (int j = 0; j < 4; ++j) part[wave * (kMmaRows * kMaxBatch) + n * kMmaRows + 4 * (lane >> 4) + j] = acc[j];
+        __syncthreads();
+        if (tid < kMmaRows * kMaxBatch) {
+            float sum = 0.0f;
+            for (int w = 0; w < kWaves; ++w) sum += part[w * (kMmaRows * kMaxBatch) + tid];
+            const int b = tid >> 4, row = rb * kMmaRows + (tid & 15);
+            if (b < batch && row < rows) y[(size_t)b * rows + row] = sum;
         }
-    }
-    __syncthreads();
-    // thread (b, r) adds the 8 column-group wavefronts: 16 x 64 = 1024 outputs, one per thread
-    const int ob = threadIdx.x >> 6, orow = threadIdx.x & 63;
-    float sum = 0.0f;
-#pragma unroll
-    for (int c = 0; c < kTileGroups; ++c) sum += red[(c * kTileRows + orow) * kMaxBatch + ob];
-    const int out_row = row_tile * kTileRows + orow;
-    const bool valid = ob < batch && out_row < rows;
-    if (split == 1) {
-        if (valid) y[(size_t)ob * rows + out_row] = sum;
-        return;
-    }
-    // Several workgroups share this row tile: publish, count arrivals, the last one adds up in split order.
-    // The eight L2 caches of the chip are not coherent with each other inside a kernel, so the partial sums
-    // and the counter travel as device-scope atomics (they bypass L2); ordering comes from completion: every
-    // wavefront waits for its own stores before the barrier that precedes the counter update, and the
-    // reader's loads are issued only after its counter update has returned.  No cache-wide flush.
-    float* mine = ws_partial + ((size_t)row_tile * split + k0) * (kMaxBatch * kTileRows);
-    __hip_atomic_store(&mine[threadIdx.x], sum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // every wavefront waits for its own stores
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const int seen = __hip_atomic_fetch_add(&ws_counter[row_tile], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        *last_flag = (seen == split - 1);
-    }
-    __syncthreads();
-    if (*last_flag) {
-        float total = 0.0f;
-        for (int k = 0; k < split; ++k)
-            total += __hip_atomic_load(&ws_partial[((size_t)row_tile * split + k) * (kMaxBatch * kTileRows) + threadIdx.x],
-                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (valid) y[(size_t)ob * rows + out_row] = total;
-        if (threadIdx.x == 0) __hip_atomic_store(&ws_counter[row_tile], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
     }
 }
 
@@ -1091,16 +1012,8 @@ int ecco_decode_gemv(const ecco_model* m, const void* blocks, const uint32_t* me
     if (!aligned(blocks, 64) || !aligned(x, 16) || !aligned(y, 4) || !aligned(meta, 4)) return ECCO_EALIGN;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int gpr = cols / kGroup;
-    const int row_tiles = (rows + kTileRows - 1) / kTileRows;
-    const int col_tiles = (gpr + kTileGroups - 1) / kTileGroups;
-    // split the column tiles of a row tile over several workgroups until the chip is covered
     const int cus = cu_count(m->device);
-    int split = std::max(1, std::min(col_tiles, (cus + row_tiles - 1) / row_tiles));
-    while (split > 1 && (row_tiles * split > kMaxWsTiles || row_tiles > kWsCounters)) --split;
     const bool lng = m->max_len > kPeekBits;
-    const DevLayout D{m->S};
-    float* ws_partial = reinterpret_cast<float*>(m->dev + D.ws_partial());
-    int* ws_counter = reinterpret_cast<int*>(m->dev + D.ws_counter());
     if (batch == 1) {
         // one band of rows per workgroup, one workgroup per compute unit where the matrix allows it
         const int band = std::min(kMaxBandRows, std::max(1, (rows + cus - 1) / cus));
@@ -1116,15 +1029,19 @@ int ecco_decode_gemv(const ecco_model* m, const void* blocks, const uint32_t* me
             hipLaunchKernelGGL(gemv_kernel<false>, dim3(grid), dim3(kGemvThreads), lds, st, m->dev, m->S,
                                static_cast<const uint4*>(blocks), meta, rows, gpr, band, xb, y);
     } else {
+        // whole 16-row blocks per workgroup, one workgroup per compute unit where the matrix allows it
+        const int total_rb = (rows + kMmaRows - 1) / kMmaRows;
+        const int rb_per_wg = std::max(1, (total_rb + cus - 1) / cus);
+        const int grid = (total_rb + rb_per_wg - 1) / rb_per_wg;
         const size_t glds = gemm_lds_bytes(m->S);
         int rc = lng ? allow_lds(gemm_kernel<true>, glds) : allow_lds(gemm_kernel<false>, glds);
         if (rc != ECCO_OK) return rc;
         if (lng)
-            hipLaunchKernelGGL(gemm_kernel<true>, dim3(row_tiles * split), dim3(kGemvThreads), glds, st, m->dev, m->S,
-                               static_cast<const uint4*>(blocks), meta, rows, cols, split, batch, x, y, ws_partial, ws_counter);
+            hipLaunchKernelGGL(gemm_kernel<true>, dim3(grid), dim3(kGemvThreads), glds, st, m->dev, m->S,
+                               static_cast<const uint4*>(blocks), meta, rows, gpr, rb_per_wg, batch, x, y);
         else
-            hipLaunchKernelGGL(gemm_kernel<false>, dim3(row_tiles * split), dim3(kGemvThreads), glds, st, m->dev, m->S,
-                               static_cast<const uint4*>(blocks), meta, rows, cols, split, batch, x, y, ws_partial, ws_counter);
+            hipLaunchKernelGGL(gemm_kernel<false>, dim3(grid), dim3(kGemvThreads), glds, st, m->dev, m->S,
+                               static_cast<const uint4*>(blocks), meta, rows, gpr, rb_per_wg, batch, x, y);
     }
     ECCO_HIP_CHECK(hipGetLastError());
     return ECCO_OK;
