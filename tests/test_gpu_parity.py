@@ -361,3 +361,22 @@ def test_full_kv_cache(dev, oracle):
     # token 7 encoded into slot T-1 must equal its encoding in slot 7 (same values, same model), on all heads
     assert torch.equal(kb2[:, :, T - 1], kb[:, :, 7]) and torch.equal(km2[:, :, T - 1], km[:, :, 7])
     assert torch.equal(vb2[:, :, T - 1], vb[:, :, 7]) and torch.equal(vm2[:, :, T - 1], vm[:, :, 7])
+
+
+def test_repeated_launches_are_identical(dev, oracle):
+    # the fused kernels fix their summation order, so every launch must give the same bits; a timing-dependent
+    # slip (a race between wavefronts, a missed wait) shows up here as a launch that differs
+    c = W.CONFIGS["mlp"]
+    rows, cols = c["shapes"][0]
+    w = W.config_weight("mlp", 0)
+    m = E.ecco_model_to_device(E.ecco_fit_patterns(w, c["S"], 12, c["seeds"][0]), 0)
+    blocks, meta = E.ecco_encode(m, t16(w, dev))
+    dec = E.ecco_decode(m, blocks, meta).float().reshape(rows, cols)
+    for batch in (1, 2, 16):
+        x = t16(W.activation(batch, cols, 11), dev)
+        first = E.ecco_decode_gemv(m, blocks, meta, rows, cols, x)
+        ref = x.float() @ dec.T
+        assert float((first - ref).norm() / ref.norm()) <= REL_L2
+        for _ in range(40):
+            again = E.ecco_decode_gemv(m, blocks, meta, rows, cols, x)
+            assert torch.equal(first, again), batch
