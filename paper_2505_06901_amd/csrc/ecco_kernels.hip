@@ -4,12 +4,15 @@
 // meta word says where the code of value 64 begins, hence every block offers two independent
 // chains of 64 values.  One lane owns one chain.  All lanes of a wavefront sit at the same value
 // position (whatever their bit positions), which makes the position-dependent operand of the
-// consumer -- the activation x[i] in the fused GEMV, the query q[i] in attention -- uniform over
-// the wavefront.  Per value a lane does: peek 8 bits of its 64-bit window, one LDS table read that
+// consumer -- the activation x[i] in the fused GEMV, the query q[i] in attention -- a register with
+// a static index.  Per value a lane does: peek 8 bits of its 64-bit window, one LDS table read that
 // returns code length, index and the centroid as FP16, the consumer's multiply-add, one 64-bit
-// shift.  Raw-mode blocks run the same instructions against a 16-entry table with a 4-bit peek.
-// Block payloads are brought into LDS with coalesced 16-byte loads and kept there with a 17-word
-// stride (word 16 is a zero pad), so per-lane refills of the window hit distinct banks.
+// shift; every four values the window is rebuilt from LDS at the chain's bit position.  Raw-mode
+// blocks run the same instructions against a 16-entry table with a 4-bit peek.  All kernels work
+// in units of 32 blocks per wavefront: 2 KB of payload fetched with coalesced 16-byte loads one
+// unit ahead, kept in a per-wavefront LDS buffer with a 17-word stride per block (word 16 is a
+// zero pad), so the per-lane window reads hit distinct banks and wavefronts never wait for each
+// other inside the decode.
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 
