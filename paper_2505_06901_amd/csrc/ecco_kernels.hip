@@ -316,8 +316,6 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_kernel(const uint32_t* __re
         const int ct = u / band_rows, r = u - ct * band_rows;
         store_unit(wbuf, pre, lane);
         const uint32_t mw = pre.meta;
-        const int un = u + kWaves;
-        if (un < units) pre = load_unit(blocks, meta, row0 + un % band_rows, gpr, un / band_rows, lane);
         const int cg = ct * kUnitBlocks + blk;
         if (ct != cur_ct) {  // the activations of this lane's chain: 64 FP16 = 8 x 16 bytes
             cur_ct = ct;
@@ -338,6 +336,10 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_kernel(const uint32_t* __re
                 }
             }
         }
+        // the next unit's payload is requested after the activations: loads return in issue order, and the
+        // activations (from cache) must not queue behind a fetch from HBM
+        const int un = u + kWaves;
+        if (un < units) pre = load_unit(blocks, meta, row0 + un % band_rows, gpr, un / band_rows, lane);
         const Lane L = lane_setup(T, mw, S);
         float acc = 0.0f;
         decode_chain<kLong, kHalf>(wbuf + blk * kStride, half ? L.second_start : 0u, L, [&](int i, uint32_t e) {
@@ -523,12 +525,6 @@ __global__ __launch_bounds__(kGemvThreads) void gemm_kernel(const uint32_t* __re
         for (int u = wave; u < upr; u += kWaves) {
             store_unit(wbuf, pre, lane);
             const uint32_t mw = pre.meta;
-            int un = u + kWaves, rbn = rb;
-            if (un >= upr) {
-                un = wave;
-                ++rbn;
-            }
-            if (rbn < rb1) pre = load_unit16(blocks, meta, rows, gpr, rbn, un, lane);
             const int cg = 2 * u + c;
             uint4 bx[kHalf / 8];  // B: 64 activations of batch row n at this chain's columns
 #pragma unroll
@@ -538,6 +534,13 @@ __global__ __launch_bounds__(kGemvThreads) void gemm_kernel(const uint32_t* __re
 #pragma unroll
                 for (int j = 0; j < kHalf / 8; ++j) bx[j] = src[j];
             }
+            // the next unit's payload is requested after the activations (loads return in issue order)
+            int un = u + kWaves, rbn = rb;
+            if (un >= upr) {
+                un = wave;
+                ++rbn;
+            }
+            if (rbn < rb1) pre = load_unit16(blocks, meta, rows, gpr, rbn, un, lane);
             const Lane L = lane_setup(T, mw, S);
             const _Float16 sh = __builtin_bit_cast(_Float16, (unsigned short)(mw & 0xFFFFu));
             const half2_t s2 = {sh, sh};
