@@ -217,6 +217,27 @@ def test_edge_cases(dev, oracle, tiny):
     assert e.value.status == -3
 
 
+def test_ragged_matrix_shapes(dev, oracle, tiny):
+    # rows that do not fill a 16-row block or a workgroup's band, odd numbers of column groups (a unit of the batch
+    # kernel then has one column group only), a single group, every batch size class; decode on ragged group counts
+    m = tiny["m"]
+    for rows, gpr, seed in [(1, 1, 21), (5, 1, 22), (17, 3, 23), (33, 5, 24), (300, 33, 25), (16, 64, 26)]:
+        cols = gpr * 128
+        w = W.weight_matrix(rows, cols, 0.02, 0.001, 10.0, seed)
+        ob, om = oracle.encode(m.centroids, m.code_lens, w.reshape(-1, 128).view(np.uint16))
+        blocks, meta = E.ecco_encode(m, t16(w, dev))
+        assert np.array_equal(np_blocks(blocks), ob) and np.array_equal(np_meta(meta), om)
+        assert np.array_equal(E.ecco_decode(m, blocks, meta).cpu().numpy().view(np.uint16),
+                              oracle.decode(m.centroids, m.code_lens, ob, om))
+        oidx, _ = oracle.decode_indices(m.code_lens, m.S, ob, om)
+        assert np.array_equal(E.ecco_decode_indices(m, blocks, meta).cpu().numpy(), oidx)
+        for batch in (1, 3, 16):
+            x = W.activation(batch, cols, seed + 100)
+            y = E.ecco_decode_gemv(m, blocks, meta, rows, cols, t16(x, dev)).cpu().numpy()
+            want = oracle.gemv(m.centroids, m.code_lens, ob, om, rows, cols, x.view(np.uint16))
+            assert y.shape == (batch, rows) and rel_l2(y, want) <= REL_L2, (rows, gpr, batch)
+
+
 # ---------------------------------------------------------------------------------------------------
 def _kv_setup(dev, oracle, B, H, T, S):
     k, v = W.kv_cache(B, H, T, 128, seed=3)
