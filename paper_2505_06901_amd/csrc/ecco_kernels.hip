@@ -148,25 +148,29 @@ __device__ __forceinline__ Lane lane_setup(const Tables& T, uint32_t meta, int S
 }
 
 // ---- the chain decoder ----------------------------------------------------------------------------------
-// Decodes kCount values starting at stream bit `start` of the staged block `w` (16 words, then a zero
-// word, then one more readable word), calling sink(i, entry) with the table entry of each (length,
+// Decodes kCount values starting at stream bit `start` of the staged block `w` (16 words, a zero
+// word, then two more readable words), calling sink(i, entry) with the table entry of each (length,
 // index, centroid).  Values are taken in runs of 4 (2 when the model has codes longer than 8 bits:
-// kLong).  A run starts by fetching the two words around its bit position into a left-aligned
-// 64-bit window: at least 33 valid bits, enough for the longest run of codes plus the last peek, so
-// there is no refill logic and no branch inside a run.  The position is clamped to 512, where the
+// kLong).  A run works on a left-aligned 64-bit window made of the two words around its bit
+// position: at least 33 valid bits, enough for the longest run of codes plus the last peek, so
+// there is no refill test and no branch inside a run.  A run consumes at most 32 bits, so the next
+// run needs the same two words or the next two: the third word is requested one run ahead and the
+// window is rebuilt with two selects, which keeps the LDS latency of the stream itself off the
+// dependent chain (only the table reads remain on it).  The position is clamped to 512, where the
 // window's upper half is the zero word: bits past the block read as zero and arbitrary bytes decode
 // without touching other memory (the lower half of that last window is never looked at).
 template <bool kLong, int kCount, class Sink>
 __device__ __forceinline__ void decode_chain(const uint32_t* w, uint32_t start, const Lane& L, Sink&& sink) {
     constexpr int kRun = kLong ? 2 : 4;
     static_assert(kCount % kRun == 0, "chain length");
-    uint32_t pos = start;
+    static_assert(kRun * (kLong ? kMaxLen : kPeekBits) <= 32, "a run stays inside two words");
+    uint32_t pos = start;  // <= 511
+    uint32_t wi = pos >> 5;
+    uint32_t w0 = w[wi], w1 = w[wi + 1], w2 = w[wi + 2];
 #pragma unroll
     for (int i0 = 0; i0 < kCount; i0 += kRun) {
-        pos = min(pos, (uint32_t)(kBlockWords * 32));
-        const uint32_t* wp = w + (pos >> 5);
-        uint64_t win = (((uint64_t)wp[0] << 32) | (uint64_t)wp[1]) << (pos & 31u);
-        uint32_t used = 0;  // sum of the run's entries; its low byte is the number of bits consumed (at most 4 x 12)
+        uint64_t win = (((uint64_t)w0 << 32) | (uint64_t)w1) << (pos & 31u);
+        uint32_t used = 0;  // sum of the run's entries; its low byte is the number of bits consumed (at most 4 x 8 or 2 x 12)
 #pragma unroll
         for (int j = 0; j < kRun; ++j) {
             uint32_t e = L.lut[(uint32_t)(win >> 32) >> L.shift];
@@ -187,7 +191,15 @@ __device__ __forceinline__ void decode_chain(const uint32_t* w, uint32_t start, 
             used += e;
             win <<= (e & 0xFFu);
         }
-        pos += used & 0xFFu;
+        if (i0 + kRun < kCount) {
+            pos = min(pos + (used & 0xFFu), (uint32_t)(kBlockWords * 32));
+            const uint32_t nwi = pos >> 5;  // wi or wi + 1
+            const bool adv = nwi != wi;
+            w0 = adv ? w1 : w0;
+            w1 = adv ? w2 : w1;
+            w2 = w[nwi + 2];  // used one run later at the earliest
+            wi = nwi;
+        }
     }
 }
 
@@ -209,7 +221,7 @@ constexpr int kGemvThreads = 1024;
 // partial sums of a row's column tiles meet in LDS and are added in a fixed order.
 constexpr int kUnitBlocks = 32;
 constexpr int kWaves = kGemvThreads / 64;
-constexpr int kUnitWords = kUnitBlocks * kStride + 4;  // private payload buffer of a wavefront (+ the word a chain may read past the last slot)
+constexpr int kUnitWords = kUnitBlocks * kStride + 4;  // private payload buffer of a wavefront (+ the two words a chain may read past the last slot)
 constexpr int kXGroupWords = kGroup / 2 + 4;           // words per column group of x in LDS (skewed against bank conflicts)
 constexpr int kXLdsGroups = 128;                       // x is staged in LDS up to this many column groups, read from L2 beyond
 constexpr int kMaxBandRows = 128;
