@@ -5,7 +5,8 @@
 //            shared-pattern k-means) and steps 6-7 (index statistics -> Huffman codebooks, H = 1)
 //   encode   Section 3.2 step 5 (round to nearest centroid of every shared pattern, keep the
 //            pattern of minimum squared error) and Section 4.3 (value mappers, Huffman encode,
-//            concatenate, length check) with a raw 4-bit fallback instead of clipping
+//            concatenate, length check) with a raw 4-bit fallback instead of clipping; also with the
+//            online compressor's min/max pattern selector (Section 3.2 "KV Cache Compression")
 //   decode   Section 4.2 (pattern retrieval, Huffman decode, centroid x scale)
 //   gemv / attention: the consumers of the decompressed values (Section 2.1), in double.
 //
@@ -13,6 +14,8 @@
 //   fp16 helpers, dequant rule ........ pinned (exhaustive, against integer arithmetic and numpy)
 //   Huffman lengths / canonical codes .. pinned (Kraft, prefix-freeness, dyadic closed form, brute force)
 //   encode / decode ................... pinned (brute force on tiny inputs, round trip, uniform 4-bit special case)
+//   min/max pattern selector .......... pinned (hand-worked example, exact rational brute force, mirror symmetry,
+//                                       single-pattern case equals the least-squared-error encoder)
 //   k-means ........................... pinned (monotone objective, Lloyd-Max quantiser of a Gaussian)
 //   gemv / attention .................. pinned (unit vectors, ones, seq_len 1, q = 0)
 //   fitted pattern VALUES and code LENGTHS for a given tensor: parity unpinned -- the paper prints
@@ -358,12 +361,72 @@ void oracle_quantize_group(const uint16_t* centroids, int S, const uint16_t* x,
     std::memcpy(idx, best_idx, G);
 }
 
+// ------------------------------------------------------------------------------------------
+// Pattern selector of the online (KV cache) compressor: Section 3.2 "KV Cache Compression" and the
+// pattern selector of Section 4.3.  Instead of quantising the group with every pattern, only the
+// group's smallest and largest value are compared with each pattern's smallest and largest centroid:
+//     fitness_p = (group min - pattern min)^2 + (group max - pattern max)^2,   least fitness wins.
+// This build's reading: the pattern's ends are taken in the group's own scale, i.e. as the
+// reconstructed values fp16(c[p][0] * s) and fp16(c[p][15] * s), so no division is needed; the
+// group's extremes run over all 128 values (the paper leaves the absmax element out because its
+// format stores that element apart from the pattern; here it is quantised by the pattern like any
+// other value, so the pattern's ends cover it); differences, squares and the sum are fp32, each
+// rounded on its own; the lowest pattern wins a tie.
+void oracle_select_minmax(const uint16_t* centroids, int S, const uint16_t* x,
+                          uint16_t* scale, int* pattern, float* fitness_out) {
+    uint16_t s_bits = 0;
+    float lo = oracle_h2f(x[0]), hi = lo;
+    for (int i = 0; i < G; ++i) {
+        uint16_t a = (uint16_t)(x[i] & 0x7FFFu);
+        if (a > s_bits) s_bits = a;
+        float v = oracle_h2f(x[i]);
+        if (v < lo) lo = v;
+        if (v > hi) hi = v;
+    }
+    int best_p = 0;
+    float best_f = 0.0f;
+    for (int p = 0; p < S; ++p) {
+        float pmin = oracle_h2f(oracle_dequant(centroids[p * K], s_bits));
+        float pmax = oracle_h2f(oracle_dequant(centroids[p * K + K - 1], s_bits));
+        float dlo = lo - pmin, dhi = hi - pmax;
+        float qlo = dlo * dlo, qhi = dhi * dhi;
+        float f = qlo + qhi;
+        if (fitness_out) fitness_out[p] = f;
+        if (p == 0 || f < best_f) { best_f = f; best_p = p; }
+    }
+    *scale = s_bits;
+    *pattern = best_p;
+}
+
+// Value mapping with one given pattern (Section 4.3, the parallel value mappers): every value goes
+// to the nearest reconstructed value of that pattern, lowest index on ties.
+void oracle_map_values(const uint16_t* centroids, int p, uint16_t s_bits, const uint16_t* x, uint8_t* idx) {
+    float r[K];
+    for (int k = 0; k < K; ++k) r[k] = oracle_h2f(oracle_dequant(centroids[p * K + k], s_bits));
+    for (int i = 0; i < G; ++i) {
+        float xi = oracle_h2f(x[i]);
+        int bk = 0;
+        float bd = std::fabs(xi - r[0]);
+        for (int k = 1; k < K; ++k) {
+            float d = std::fabs(xi - r[k]);
+            if (d < bd) { bd = d; bk = k; }
+        }
+        idx[i] = (uint8_t)bk;
+    }
+}
+
+// selector: 0 = least squared error over all patterns, 1 = min/max fitness
 static void encode_one(const uint16_t* centroids, const uint8_t* lens, const uint16_t* codes, int S,
-                       const uint16_t* x, uint8_t* blk, uint32_t* meta) {
+                       const uint16_t* x, uint8_t* blk, uint32_t* meta, int selector = 0) {
     uint16_t s;
     int p;
     uint8_t idx[G];
-    oracle_quantize_group(centroids, S, x, &s, &p, idx, nullptr);
+    if (selector == 0) {
+        oracle_quantize_group(centroids, S, x, &s, &p, idx, nullptr);
+    } else {
+        oracle_select_minmax(centroids, S, x, &s, &p, nullptr);
+        oracle_map_values(centroids, p, s, x, idx);
+    }
     int total = 0;
     for (int i = 0; i < G; ++i) total += lens[p * K + idx[i]];
     std::memset(blk, 0, ORACLE_BLOCK_BYTES);
@@ -391,6 +454,16 @@ void oracle_encode(const uint16_t* centroids, const uint8_t* lens, int S,
     for (long g = 0; g < (long)n_groups; ++g)
         encode_one(centroids, lens, codes.data(), S, src + (size_t)g * G,
                    blocks + (size_t)g * ORACLE_BLOCK_BYTES, meta + g);
+}
+
+void oracle_encode_minmax(const uint16_t* centroids, const uint8_t* lens, int S,
+                          const uint16_t* src, size_t n_groups, uint8_t* blocks, uint32_t* meta) {
+    std::vector<uint16_t> codes((size_t)S * K);
+    for (int p = 0; p < S; ++p) oracle_canonical_codes(lens + p * K, K, codes.data() + p * K);
+#pragma omp parallel for num_threads(g_threads) schedule(static)
+    for (long g = 0; g < (long)n_groups; ++g)
+        encode_one(centroids, lens, codes.data(), S, src + (size_t)g * G,
+                   blocks + (size_t)g * ORACLE_BLOCK_BYTES, meta + g, 1);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -480,10 +553,10 @@ void oracle_gemv(const uint16_t* centroids, const uint8_t* lens, int S, const ui
 }
 
 // ------------------------------------------------------------------------------------------
-void oracle_kv_append(const uint16_t* ck, const uint8_t* lk, int Sk, const uint16_t* cv, const uint8_t* lv, int Sv,
-                      const uint16_t* k_new, const uint16_t* v_new,
-                      uint8_t* k_blocks, uint32_t* k_meta, uint8_t* v_blocks, uint32_t* v_meta,
-                      const int32_t* seq_len, int B, int H, int T_max) {
+static void kv_append_with(int selector, const uint16_t* ck, const uint8_t* lk, int Sk, const uint16_t* cv, const uint8_t* lv, int Sv,
+                           const uint16_t* k_new, const uint16_t* v_new,
+                           uint8_t* k_blocks, uint32_t* k_meta, uint8_t* v_blocks, uint32_t* v_meta,
+                           const int32_t* seq_len, int B, int H, int T_max) {
     std::vector<uint16_t> codes_k((size_t)Sk * K), codes_v((size_t)Sv * K);
     for (int p = 0; p < Sk; ++p) oracle_canonical_codes(lk + p * K, K, codes_k.data() + p * K);
     for (int p = 0; p < Sv; ++p) oracle_canonical_codes(lv + p * K, K, codes_v.data() + p * K);
@@ -493,10 +566,24 @@ void oracle_kv_append(const uint16_t* ck, const uint8_t* lk, int Sk, const uint1
         for (int h = 0; h < H; ++h) {
             size_t src = ((size_t)b * H + h) * G;
             size_t dst = ((size_t)b * H + h) * T_max + t;
-            encode_one(ck, lk, codes_k.data(), Sk, k_new + src, k_blocks + dst * ORACLE_BLOCK_BYTES, k_meta + dst);
-            encode_one(cv, lv, codes_v.data(), Sv, v_new + src, v_blocks + dst * ORACLE_BLOCK_BYTES, v_meta + dst);
+            encode_one(ck, lk, codes_k.data(), Sk, k_new + src, k_blocks + dst * ORACLE_BLOCK_BYTES, k_meta + dst, selector);
+            encode_one(cv, lv, codes_v.data(), Sv, v_new + src, v_blocks + dst * ORACLE_BLOCK_BYTES, v_meta + dst, selector);
         }
     }
+}
+
+void oracle_kv_append(const uint16_t* ck, const uint8_t* lk, int Sk, const uint16_t* cv, const uint8_t* lv, int Sv,
+                      const uint16_t* k_new, const uint16_t* v_new,
+                      uint8_t* k_blocks, uint32_t* k_meta, uint8_t* v_blocks, uint32_t* v_meta,
+                      const int32_t* seq_len, int B, int H, int T_max) {
+    kv_append_with(0, ck, lk, Sk, cv, lv, Sv, k_new, v_new, k_blocks, k_meta, v_blocks, v_meta, seq_len, B, H, T_max);
+}
+
+void oracle_kv_append_minmax(const uint16_t* ck, const uint8_t* lk, int Sk, const uint16_t* cv, const uint8_t* lv, int Sv,
+                             const uint16_t* k_new, const uint16_t* v_new,
+                             uint8_t* k_blocks, uint32_t* k_meta, uint8_t* v_blocks, uint32_t* v_meta,
+                             const int32_t* seq_len, int B, int H, int T_max) {
+    kv_append_with(1, ck, lk, Sk, cv, lv, Sv, k_new, v_new, k_blocks, k_meta, v_blocks, v_meta, seq_len, B, H, T_max);
 }
 
 // Scaled dot-product attention for one query token per sequence (Section 2.1): scores

@@ -63,6 +63,17 @@ void oracle_quantize_group(const uint16_t* centroids, int S, const uint16_t* x,
 void oracle_encode(const uint16_t* centroids, const uint8_t* lens, int S,
                    const uint16_t* src, size_t n_groups, uint8_t* blocks, uint32_t* meta);
 
+/* min/max pattern selector of the online compressor (Section 3.2 "KV Cache Compression", Section 4.3):
+ * fitness[p] = (group min - fp16(c[p][0]*s))^2 + (group max - fp16(c[p][15]*s))^2 in fp32; least wins,
+ * lowest pattern on ties.  fitness may be NULL. */
+void oracle_select_minmax(const uint16_t* centroids, int S, const uint16_t* x,
+                          uint16_t* scale, int* pattern, float* fitness);
+/* nearest reconstructed value of pattern p for each of the 128 values (lowest index on ties) */
+void oracle_map_values(const uint16_t* centroids, int p, uint16_t scale, const uint16_t* x, uint8_t* idx);
+/* as oracle_encode / oracle_kv_append, with the min/max selector in place of the least-squared-error search */
+void oracle_encode_minmax(const uint16_t* centroids, const uint8_t* lens, int S,
+                          const uint16_t* src, size_t n_groups, uint8_t* blocks, uint32_t* meta);
+
 /* ---- decoder (Section 4.2) -------------------------------------------------------------- */
 void oracle_decode_indices(const uint8_t* lens, int S, const uint8_t* blocks, const uint32_t* meta,
                            size_t n_groups, uint8_t* idx /* n_groups*128 */, uint16_t* used_bits /* may be NULL */);
@@ -79,6 +90,11 @@ void oracle_kv_append(const uint16_t* ck, const uint8_t* lk, int Sk, const uint1
                       const uint16_t* k_new, const uint16_t* v_new,
                       uint8_t* k_blocks, uint32_t* k_meta, uint8_t* v_blocks, uint32_t* v_meta,
                       const int32_t* seq_len, int B, int H, int T_max);
+
+void oracle_kv_append_minmax(const uint16_t* ck, const uint8_t* lk, int Sk, const uint16_t* cv, const uint8_t* lv, int Sv,
+                             const uint16_t* k_new, const uint16_t* v_new,
+                             uint8_t* k_blocks, uint32_t* k_meta, uint8_t* v_blocks, uint32_t* v_meta,
+                             const int32_t* seq_len, int B, int H, int T_max);
 
 /* single-query attention over the compressed caches, double precision; out [B][H][128] */
 void oracle_kv_attend(const uint16_t* ck, const uint8_t* lk, int Sk, const uint16_t* cv, const uint8_t* lv, int Sv,

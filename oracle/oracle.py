@@ -26,6 +26,7 @@ def lib():
         _lib.oracle_f2h.argtypes = [C.c_float]
         _lib.oracle_dequant.restype = C.c_uint16
         _lib.oracle_dequant.argtypes = [C.c_uint16, C.c_uint16]
+        _lib.oracle_map_values.argtypes = [C.c_void_p, C.c_int, C.c_uint16, C.c_void_p, C.c_void_p]
     return _lib
 
 
@@ -132,6 +133,40 @@ def encode(centroids, lens, src_u16):
     return blocks, meta
 
 
+def select_minmax(centroids, x_u16):
+    centroids = _c(centroids, np.uint16)
+    S = centroids.size // K
+    x = _c(x_u16, np.uint16).reshape(-1)
+    assert x.size == GROUP
+    scale = C.c_uint16(0)
+    pat = C.c_int(0)
+    fit_ = np.zeros(S, np.float32)
+    lib().oracle_select_minmax(_p(centroids), C.c_int(S), _p(x), C.byref(scale), C.byref(pat), _p(fit_))
+    return int(scale.value), int(pat.value), fit_
+
+
+def map_values(centroids, p: int, scale: int, x_u16):
+    centroids = _c(centroids, np.uint16)
+    x = _c(x_u16, np.uint16).reshape(-1)
+    assert x.size == GROUP and 0 <= p < centroids.size // K
+    idx = np.zeros(GROUP, np.uint8)
+    lib().oracle_map_values(_p(centroids), C.c_int(p), C.c_uint16(scale), _p(x), _p(idx))
+    return idx
+
+
+def encode_minmax(centroids, lens, src_u16):
+    centroids = _c(centroids, np.uint16)
+    lens = _c(lens, np.uint8)
+    S = centroids.size // K
+    src = _c(src_u16, np.uint16).reshape(-1)
+    assert src.size % GROUP == 0
+    n = src.size // GROUP
+    blocks = np.zeros((n, BLOCK_BYTES), np.uint8)
+    meta = np.zeros(n, np.uint32)
+    lib().oracle_encode_minmax(_p(centroids), _p(lens), C.c_int(S), _p(src), C.c_size_t(n), _p(blocks), _p(meta))
+    return blocks, meta
+
+
 def decode_indices(lens, S: int, blocks, meta):
     lens = _c(lens, np.uint8)
     blocks = _c(blocks, np.uint8).reshape(-1, BLOCK_BYTES)
@@ -172,7 +207,7 @@ def gemv(centroids, lens, blocks, meta, rows: int, cols: int, x_u16):
     return y
 
 
-def kv_append(ck, lk, cv, lv, k_new, v_new, k_blocks, k_meta, v_blocks, v_meta, seq_len, B, H, T_max):
+def kv_append(ck, lk, cv, lv, k_new, v_new, k_blocks, k_meta, v_blocks, v_meta, seq_len, B, H, T_max, minmax=False):
     """In place on the numpy caches (k_blocks [B,H,T_max,64] u8, k_meta [B,H,T_max] u32, ...)."""
     ck, cv = _c(ck, np.uint16), _c(cv, np.uint16)
     lk, lv = _c(lk, np.uint8), _c(lv, np.uint8)
@@ -180,7 +215,8 @@ def kv_append(ck, lk, cv, lv, k_new, v_new, k_blocks, k_meta, v_blocks, v_meta, 
     seq_len = _c(seq_len, np.int32)
     for a in (k_blocks, k_meta, v_blocks, v_meta):
         assert a.flags["C_CONTIGUOUS"]
-    lib().oracle_kv_append(_p(ck), _p(lk), C.c_int(ck.size // K), _p(cv), _p(lv), C.c_int(cv.size // K),
+    fn = lib().oracle_kv_append_minmax if minmax else lib().oracle_kv_append
+    fn(_p(ck), _p(lk), C.c_int(ck.size // K), _p(cv), _p(lv), C.c_int(cv.size // K),
                            _p(k_new), _p(v_new), _p(k_blocks), _p(k_meta), _p(v_blocks), _p(v_meta),
                            _p(seq_len), C.c_int(B), C.c_int(H), C.c_int(T_max))
 

@@ -331,6 +331,106 @@ def test_sse_tree_order(oracle):
     assert abs(float(sse[0]) - float(exact)) < 1e-5 * float(exact)
 
 
+# --------------------------------------------------------------------------------------------
+# min/max pattern selector of the online compressor (Section 3.2 "KV Cache Compression", Section 4.3)
+def _asym_model():
+    """Four patterns with clearly different ends (every value exact in fp16)."""
+    ends = [(-1.0, 0.5), (-0.5, 1.0), (-1.0, 1.0), (-0.25, 1.0)]
+    return np.stack([np.linspace(lo, hi, 16) for lo, hi in ends]).astype(np.float16)
+
+
+def test_minmax_selector_worked_example(oracle):
+    """Numbers worked by hand: scale 1, so the patterns' ends are the centroids themselves."""
+    cent = _asym_model().view(np.uint16)
+    x = np.zeros(128, np.float16)
+    x[17] = 1.0      # absmax and maximum
+    x[90] = -0.75    # minimum
+    x[3:9] = [0.5, -0.5, 0.25, -0.125, 0.0625, 0.75]
+    s, p, f = oracle.select_minmax(cent, x.view(np.uint16))
+    assert s == 0x3C00
+    # (min - lo)^2 + (max - hi)^2:  (0.25)^2 + (0.5)^2, (0.25)^2 + 0, (0.25)^2 + 0, (0.5)^2 + 0
+    assert list(f) == [0.3125, 0.0625, 0.0625, 0.25]
+    assert p == 1  # patterns 1 and 2 tie: the lower one wins
+    # only the extremes matter: new interior values, same choice and same fitness
+    y = x.copy()
+    y[20:80] = np.linspace(-0.7, 0.9, 60).astype(np.float16)
+    s2, p2, f2 = oracle.select_minmax(cent, y.view(np.uint16))
+    assert (s2, p2, list(f2)) == (s, p, list(f))
+    # the least-squared-error search looks at every value and may choose differently: here it must not
+    # pick a pattern whose range stops at 0.5 either, but it is a different function
+    _, pq, _, sse = oracle.quantize_group(cent, y.view(np.uint16))
+    assert sse[pq] <= sse[p]
+    # a group whose ends coincide with a pattern's ends: fitness exactly 0, that pattern is chosen
+    z = np.zeros(128, np.float16); z[0] = 1.0; z[1] = -0.25
+    _, pz, fz = oracle.select_minmax(cent, z.view(np.uint16))
+    assert pz == 3 and fz[3] == 0.0
+    # scaling the group by a power of two changes nothing but the scale (products by 2^k are exact)
+    s4, p4, f4 = oracle.select_minmax(cent, (y * np.float16(4)).view(np.uint16))
+    assert s4 == 0x4400 and p4 == p and list(f4) == [16 * v for v in f]
+
+
+def test_minmax_selector_bruteforce_and_symmetry(oracle):
+    cent = _hand_model()
+    cent[1] = np.sort(np.abs(cent[1]) * 0.8 - 0.3)   # give the patterns different ends
+    cent[3, 0] = -0.6
+    cent = np.sort(cent, axis=1)
+    cu = cent.view(np.uint16)
+    mirrored = np.ascontiguousarray(-cent[:, ::-1]).view(np.uint16)
+    rng = np.random.default_rng(5)
+    for trial in range(16):
+        x = (rng.normal(0, 1, 128) * 10.0 ** rng.uniform(-2, 1)).astype(np.float16)
+        if trial % 3 == 0:
+            x = np.abs(x)
+        x16 = x.view(np.uint16)
+        s, p, f = oracle.select_minmax(cu, x16)
+        sf = half_to_fraction(max(int(v) & 0x7FFF for v in x16))
+        lo = min(half_to_fraction(int(v)) for v in x16)
+        hi = max(half_to_fraction(int(v)) for v in x16)
+        exact = []
+        for q in range(cu.shape[0]):
+            r0 = half_to_fraction(round_fraction_to_half(half_to_fraction(int(cu[q, 0])) * sf))
+            r15 = half_to_fraction(round_fraction_to_half(half_to_fraction(int(cu[q, 15])) * sf))
+            exact.append((lo - r0) ** 2 + (hi - r15) ** 2)
+        assert s == max(int(v) & 0x7FFF for v in x16)
+        assert p == min(range(len(exact)), key=lambda q: (exact[q], q))
+        for q in range(len(exact)):
+            assert abs(float(f[q]) - float(exact[q])) <= 1e-6 * float(exact[q]) + 1e-30
+        # mirror image: negated group against negated, reversed patterns -> same choice, same fitness
+        s_m, p_m, f_m = oracle.select_minmax(mirrored, (-x).view(np.uint16))
+        assert (s_m, p_m) == (s, p) and np.array_equal(f_m, f)
+
+
+def test_minmax_encode_consistency(oracle, tiny):
+    """The block written with the min/max selector holds the selector's pattern and the value mapper's
+    indices; with a single pattern both selectors are the same function; the least-squared-error
+    choice is never worse."""
+    cent, lens = tiny["cent"], tiny["lens"]
+    S = cent.shape[0]
+    data = tiny["w"].view(np.uint16).reshape(-1, 128)[:96]
+    blocks, meta = oracle.encode_minmax(cent, lens, data)
+    idx, _ = oracle.decode_indices(lens, S, blocks, meta)
+    dec = oracle.decode(cent, lens, blocks, meta)
+    differs = 0
+    for g in range(data.shape[0]):
+        s, p, f = oracle.select_minmax(cent, data[g])
+        assert (int(meta[g]) & 0xFFFF) == s and ((int(meta[g]) >> 16) & 0x3F) == p
+        want = oracle.map_values(cent, p, s, data[g])
+        assert np.array_equal(idx[g], want)
+        assert all(int(dec[g, i]) == oracle.dequant(int(cent[p, want[i]]), s) for i in range(0, 128, 7))
+        sq, pq, iq, sse = oracle.quantize_group(cent, data[g])
+        assert sq == s and sse[pq] <= sse[p]
+        if pq == p:
+            assert np.array_equal(iq, want)
+        else:
+            differs += 1
+        # one pattern only: nothing to select, both encoders write the same block
+        one_c, one_l = cent[p:p + 1], lens[p:p + 1]
+        b1, m1 = oracle.encode(one_c, one_l, data[g])
+        b2, m2 = oracle.encode_minmax(one_c, one_l, data[g])
+        assert np.array_equal(b1, b2) and np.array_equal(m1, m2)
+    assert differs > 0  # otherwise this input does not tell the two selectors apart
+
+
 def test_uniform_special_case_is_absmax_int4(oracle):
     """S = 1, equidistant centroids, all code lengths 4: Ecco degenerates to symmetric absmax 4-bit
     round-to-nearest, and the Huffman payload is the raw payload bit for bit."""
