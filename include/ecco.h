@@ -149,6 +149,21 @@ int ecco_kv_append(const ecco_model* mk, const ecco_model* mv,
                    void* k_blocks, uint32_t* k_meta, void* v_blocks, uint32_t* v_meta,
                    const int32_t* seq_len, int B, int H, int T_max, void* stream);
 
+/* The online compressor's cheap pattern selector (Section 3.2 "KV Cache Compression"; pattern selector of
+ * Section 4.3): instead of quantising the group with every pattern, the group's least and greatest value are
+ * compared with each pattern's first and last centroid, both in the group's scale:
+ *     fitness[p] = (min_i x_i - fp16(c[p][0]*s))^2 + (max_i x_i - fp16(c[p][15]*s))^2     (FP32, each operation rounded)
+ * the least fitness wins (lowest p on a tie) and only that pattern's value mapping and packing are done.
+ * The extremes run over all 128 values: this format quantises the absmax element with the pattern like any
+ * other value.  Blocks and meta words have the format of ecco_encode, so every decoder reads them.
+ * Arguments, layout, ownership and errors as ecco_encode / ecco_kv_append. */
+int ecco_encode_minmax(const ecco_model* m, const uint16_t* src_fp16, size_t n_groups,
+                       void* blocks, uint32_t* meta, void* stream);
+int ecco_kv_append_minmax(const ecco_model* mk, const ecco_model* mv,
+                          const uint16_t* k_new, const uint16_t* v_new,
+                          void* k_blocks, uint32_t* k_meta, void* v_blocks, uint32_t* v_meta,
+                          const int32_t* seq_len, int B, int H, int T_max, void* stream);
+
 /* Single-query attention over the compressed caches (Section 2.1): per (b,h), scores
  * q.K_t / sqrt(128) for t < seq_len[b], softmax, out = sum_t p_t V_t.  No mask beyond seq_len.
  *   q  device [B][H][128] FP16, 16-byte aligned;  out  device [B][H][128] FP32 (zeros where seq_len[b] <= 0).

@@ -19,6 +19,7 @@ EXPORTS = [
     "ecco_strerror", "ecco_fit_patterns", "ecco_model_create", "ecco_model_save", "ecco_model_load",
     "ecco_model_S", "ecco_model_centroids", "ecco_model_code_lens", "ecco_model_to_device", "ecco_model_free",
     "ecco_encode", "ecco_decode", "ecco_decode_indices", "ecco_decode_gemv", "ecco_kv_append", "ecco_kv_attend",
+    "ecco_encode_minmax", "ecco_kv_append_minmax",
 ]
 
 
@@ -48,10 +49,12 @@ def lib():
         L.ecco_model_load.argtypes = [vp, sz, C.POINTER(vp)]
         L.ecco_model_to_device.argtypes = [vp, i32]
         L.ecco_encode.argtypes = [vp, vp, sz, vp, vp, vp]
+        L.ecco_encode_minmax.argtypes = [vp, vp, sz, vp, vp, vp]
         L.ecco_decode.argtypes = [vp, vp, vp, sz, vp, vp]
         L.ecco_decode_indices.argtypes = [vp, vp, vp, sz, vp, vp]
         L.ecco_decode_gemv.argtypes = [vp, vp, vp, i32, i32, vp, i32, vp, vp]
         L.ecco_kv_append.argtypes = [vp] * 9 + [i32, i32, i32, vp]
+        L.ecco_kv_append_minmax.argtypes = [vp] * 9 + [i32, i32, i32, vp]
         L.ecco_kv_attend.argtypes = [vp] * 8 + [i32, i32, i32, vp, vp]
         _lib = L
     return _lib
@@ -152,8 +155,7 @@ def ecco_model_to_device(m: Model, device: int = 0) -> Model:
     return m
 
 
-def ecco_encode(m: Model, src, blocks=None, meta=None):
-    """src: CUDA FP16 tensor with numel % 128 == 0.  Returns (blocks uint8 [n,64], meta int32 [n])."""
+def _encode(name: str, m: Model, src, blocks, meta):
     import torch
     n = src.numel() // GROUP
     assert src.numel() % GROUP == 0 and src.dtype == torch.float16
@@ -161,8 +163,18 @@ def ecco_encode(m: Model, src, blocks=None, meta=None):
         blocks = torch.empty((n, BLOCK_BYTES), dtype=torch.uint8, device=src.device)
     if meta is None:
         meta = torch.empty((n,), dtype=torch.int32, device=src.device)
-    _check(lib().ecco_encode(m.handle, _dp(src), n, _dp(blocks), _dp(meta), _stream()), "ecco_encode")
+    _check(getattr(lib(), name)(m.handle, _dp(src), n, _dp(blocks), _dp(meta), _stream()), name)
     return blocks, meta
+
+
+def ecco_encode(m: Model, src, blocks=None, meta=None):
+    """src: CUDA FP16 tensor with numel % 128 == 0.  Returns (blocks uint8 [n,64], meta int32 [n])."""
+    return _encode("ecco_encode", m, src, blocks, meta)
+
+
+def ecco_encode_minmax(m: Model, src, blocks=None, meta=None):
+    """As ecco_encode, with the min/max pattern selector."""
+    return _encode("ecco_encode_minmax", m, src, blocks, meta)
 
 
 def ecco_decode(m: Model, blocks, meta, dst=None):
@@ -197,6 +209,12 @@ def ecco_decode_gemv(m: Model, blocks, meta, rows: int, cols: int, x, y=None):
 def ecco_kv_append(mk: Model, mv: Model, k_new, v_new, k_blocks, k_meta, v_blocks, v_meta, seq_len, B, H, T_max):
     _check(lib().ecco_kv_append(mk.handle, mv.handle, _dp(k_new), _dp(v_new), _dp(k_blocks), _dp(k_meta),
                                 _dp(v_blocks), _dp(v_meta), _dp(seq_len), B, H, T_max, _stream()), "ecco_kv_append")
+
+
+def ecco_kv_append_minmax(mk: Model, mv: Model, k_new, v_new, k_blocks, k_meta, v_blocks, v_meta, seq_len, B, H, T_max):
+    _check(lib().ecco_kv_append_minmax(mk.handle, mv.handle, _dp(k_new), _dp(v_new), _dp(k_blocks), _dp(k_meta),
+                                       _dp(v_blocks), _dp(v_meta), _dp(seq_len), B, H, T_max, _stream()),
+           "ecco_kv_append_minmax")
 
 
 def ecco_kv_attend(mk: Model, mv: Model, q, k_blocks, k_meta, v_blocks, v_meta, seq_len, B, H, T_max, out=None):

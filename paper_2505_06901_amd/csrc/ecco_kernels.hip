@@ -679,10 +679,48 @@ __device__ inline void pack_group(const EncLds& E, uint32_t smax, int best_p, ui
     wave_lds_fence();
 }
 
-// One wavefront encodes one group (hx0, hx1: this lane's two values as FP16 bits).
+// Pattern selector of the online compressor (Section 3.2 "KV Cache Compression", pattern selector of Section 4.3):
+// only the group's least and greatest value are compared with each pattern's ends, taken in the group's scale as
+// fp16(centroid * s):  fitness = (min - first)^2 + (max - last)^2, every operation rounded to FP32 on its own.
+// Lane p rates pattern p (S <= 64); the least fitness wins, the lowest pattern on a tie.  Uniform result.
+__device__ inline int select_minmax(const EncLds& E, int S, float s, float x0, float x1) {
+    const int lane = threadIdx.x & 63;
+    float lo = fminf(x0, x1), hi = fmaxf(x0, x1);
+    for (int m = 1; m < 64; m <<= 1) {
+        lo = fminf(lo, __shfl_xor(lo, m));
+        hi = fmaxf(hi, __shfl_xor(hi, m));
+    }
+    float f = __builtin_inff();
+    if (lane < S) {
+        const float first = half_bits_f(dequant_bits(__half_as_ushort(E.cent[lane * kK]), s));
+        const float last = half_bits_f(dequant_bits(__half_as_ushort(E.cent[lane * kK + kK - 1]), s));
+        const float dlo = __fsub_rn(lo, first), dhi = __fsub_rn(hi, last);
+        f = __fadd_rn(__fmul_rn(dlo, dlo), __fmul_rn(dhi, dhi));
+    }
+    int p = lane;
+    for (int m = 1; m < 64; m <<= 1) {
+        const float fo = __shfl_xor(f, m);
+        const int po = __shfl_xor(p, m);
+        const bool take = fo < f || (fo == f && po < p);
+        f = take ? fo : f;
+        p = take ? po : p;
+    }
+    return __builtin_amdgcn_readfirstlane(p);
+}
+
+// One wavefront encodes one group (hx0, hx1: this lane's two values as FP16 bits).  kMinMax: the pattern comes
+// from the min/max selector and only that pattern's value mapping is done; otherwise every pattern is tried
+// and the least squared error wins.
+template <bool kMinMax>
 __device__ inline void encode_group(const EncLds& E, int S, uint32_t hx0, uint32_t hx1, uint32_t* word, uint32_t* meta) {
     const uint32_t smax = group_scale_bits(hx0, hx1);
-    const EncChoice c = search_patterns(E, 0, S, half_bits_f(smax), half_bits_f(hx0), half_bits_f(hx1));
+    const float s = half_bits_f(smax), x0 = half_bits_f(hx0), x1 = half_bits_f(hx1);
+    int p0 = 0, p1 = S;
+    if (kMinMax) {
+        p0 = select_minmax(E, S, s, x0, x1);
+        p1 = p0 + 1;
+    }
+    const EncChoice c = search_patterns(E, p0, p1, s, x0, x1);
     pack_group(E, smax, c.pattern, c.idx, word, meta);
 }
 
@@ -706,6 +744,7 @@ __device__ inline EncLds setup_enc_lds(unsigned char* smem, const uint32_t* dev,
     return E;
 }
 
+template <bool kMinMax>
 __global__ __launch_bounds__(kEncThreads) void encode_kernel(const uint32_t* __restrict__ dev, int S,
                                                              const uint32_t* __restrict__ src, size_t n_groups,
                                                              uint32_t* __restrict__ blocks, uint32_t* __restrict__ meta) {
@@ -715,7 +754,7 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const uint32_t* __r
     for (size_t g = (size_t)blockIdx.x * kEncWaves + wave; g < n_groups; g += (size_t)gridDim.x * kEncWaves) {
         const uint32_t pair = src[g * (kGroup / 2) + lane];
         uint32_t word, mw;
-        encode_group(E, S, pair & 0xFFFFu, pair >> 16, &word, &mw);
+        encode_group<kMinMax>(E, S, pair & 0xFFFFu, pair >> 16, &word, &mw);
         if (lane < kBlockWords) blocks[g * kBlockWords + lane] = word;
         if (lane == 0) meta[g] = mw;
     }
@@ -762,6 +801,33 @@ __global__ __launch_bounds__(kEncThreads) void kv_append_kernel(const uint32_t* 
         if (w * per < S && cand_sse[w] < cand_sse[win]) win = w;
     uint32_t word, mw;
     pack_group(E, smax, cand_pattern[win], cand_idx[win][lane], &word, &mw);
+    const size_t g = (size_t)bh * T_max + t;
+    uint32_t* blocks = is_v ? v_blocks : k_blocks;
+    uint32_t* meta = is_v ? v_meta : k_meta;
+    if (lane < kBlockWords) blocks[g * kBlockWords + lane] = word;
+    if (lane == 0) meta[g] = mw;
+}
+
+// The append with the min/max selector: grid (ceil(B*H / 4), 2); one wavefront per new group, since the
+// selector leaves a single pattern to map and nothing to split.
+__global__ __launch_bounds__(kEncThreads) void kv_append_minmax_kernel(const uint32_t* __restrict__ dev_k, int Sk,
+                                                                       const uint32_t* __restrict__ dev_v, int Sv,
+                                                                       const uint32_t* __restrict__ k_new, const uint32_t* __restrict__ v_new,
+                                                                       uint32_t* __restrict__ k_blocks, uint32_t* __restrict__ k_meta,
+                                                                       uint32_t* __restrict__ v_blocks, uint32_t* __restrict__ v_meta,
+                                                                       const int32_t* __restrict__ seq_len, int B, int H, int T_max) {
+    extern __shared__ __align__(16) unsigned char smem_enc[];
+    const bool is_v = blockIdx.y != 0;
+    const int S = is_v ? Sv : Sk;
+    EncLds E = setup_enc_lds(smem_enc, is_v ? dev_v : dev_k, S);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int bh = blockIdx.x * kEncWaves + wave;
+    if (bh >= B * H) return;  // no workgroup barrier below
+    const int t = seq_len[bh / H];
+    if (t < 0 || t >= T_max) return;
+    const uint32_t pair = ((is_v ? v_new : k_new) + (size_t)bh * (kGroup / 2))[lane];
+    uint32_t word, mw;
+    encode_group<true>(E, S, pair & 0xFFFFu, pair >> 16, &word, &mw);
     const size_t g = (size_t)bh * T_max + t;
     uint32_t* blocks = is_v ? v_blocks : k_blocks;
     uint32_t* meta = is_v ? v_meta : k_meta;
@@ -976,17 +1042,25 @@ int cu_count(int device) {
 
 extern "C" {
 
-int ecco_encode(const ecco_model* m, const uint16_t* src, size_t n_groups, void* blocks, uint32_t* meta, void* stream) {
+static int encode_common(bool minmax, const ecco_model* m, const uint16_t* src, size_t n_groups, void* blocks, uint32_t* meta, void* stream) {
     if (model_ready(m) != ECCO_OK) return ECCO_EINVAL;
     if (n_groups == 0) return ECCO_OK;  // nothing to do; pointers may be null
     if (!src || !blocks || !meta) return ECCO_EINVAL;
     if (!aligned(blocks, 64) || !aligned(src, 4) || !aligned(meta, 4)) return ECCO_EALIGN;
     const size_t wgs = (n_groups + kEncWaves - 1) / kEncWaves;
     const int grid = (int)std::min<size_t>(wgs, (size_t)cu_count(m->device) * 16);
-    hipLaunchKernelGGL(encode_kernel, dim3(grid), dim3(kEncThreads), enc_lds_bytes(m->S), static_cast<hipStream_t>(stream), m->dev,
+    hipLaunchKernelGGL(minmax ? encode_kernel<true> : encode_kernel<false>, dim3(grid), dim3(kEncThreads), enc_lds_bytes(m->S), static_cast<hipStream_t>(stream), m->dev,
                        m->S, reinterpret_cast<const uint32_t*>(src), n_groups, static_cast<uint32_t*>(blocks), meta);
     ECCO_HIP_CHECK(hipGetLastError());
     return ECCO_OK;
+}
+
+int ecco_encode(const ecco_model* m, const uint16_t* src, size_t n_groups, void* blocks, uint32_t* meta, void* stream) {
+    return encode_common(false, m, src, n_groups, blocks, meta, stream);
+}
+
+int ecco_encode_minmax(const ecco_model* m, const uint16_t* src, size_t n_groups, void* blocks, uint32_t* meta, void* stream) {
+    return encode_common(true, m, src, n_groups, blocks, meta, stream);
 }
 
 static int decode_common(const ecco_model* m, const void* blocks, const uint32_t* meta, size_t n_groups, void* dst,
@@ -1065,20 +1139,33 @@ int ecco_decode_gemv(const ecco_model* m, const void* blocks, const uint32_t* me
     return ECCO_OK;
 }
 
-int ecco_kv_append(const ecco_model* mk, const ecco_model* mv, const uint16_t* k_new, const uint16_t* v_new,
-                   void* k_blocks, uint32_t* k_meta, void* v_blocks, uint32_t* v_meta,
-                   const int32_t* seq_len, int B, int H, int T_max, void* stream) {
+static int kv_append_common(bool minmax, const ecco_model* mk, const ecco_model* mv, const uint16_t* k_new, const uint16_t* v_new,
+                            void* k_blocks, uint32_t* k_meta, void* v_blocks, uint32_t* v_meta,
+                            const int32_t* seq_len, int B, int H, int T_max, void* stream) {
     if (!k_new || !v_new || !k_blocks || !k_meta || !v_blocks || !v_meta || !seq_len) return ECCO_EINVAL;
     if (model_ready(mk) != ECCO_OK || model_ready(mv) != ECCO_OK || mk->device != mv->device) return ECCO_EINVAL;
     if (B <= 0 || H <= 0 || T_max <= 0) return ECCO_ESHAPE;
     if (!aligned(k_blocks, 64) || !aligned(v_blocks, 64) || !aligned(k_new, 4) || !aligned(v_new, 4)) return ECCO_EALIGN;
-    dim3 grid(B * H, 2);
-    hipLaunchKernelGGL(kv_append_kernel, grid, dim3(kEncThreads), enc_lds_bytes(std::max(mk->S, mv->S)),
+    const dim3 grid(minmax ? (B * H + kEncWaves - 1) / kEncWaves : B * H, 2);
+    hipLaunchKernelGGL(minmax ? kv_append_minmax_kernel : kv_append_kernel, grid, dim3(kEncThreads),
+                       enc_lds_bytes(std::max(mk->S, mv->S)),
                        static_cast<hipStream_t>(stream), mk->dev, mk->S, mv->dev, mv->S,
                        reinterpret_cast<const uint32_t*>(k_new), reinterpret_cast<const uint32_t*>(v_new),
                        static_cast<uint32_t*>(k_blocks), k_meta, static_cast<uint32_t*>(v_blocks), v_meta, seq_len, B, H, T_max);
     ECCO_HIP_CHECK(hipGetLastError());
     return ECCO_OK;
+}
+
+int ecco_kv_append(const ecco_model* mk, const ecco_model* mv, const uint16_t* k_new, const uint16_t* v_new,
+                   void* k_blocks, uint32_t* k_meta, void* v_blocks, uint32_t* v_meta,
+                   const int32_t* seq_len, int B, int H, int T_max, void* stream) {
+    return kv_append_common(false, mk, mv, k_new, v_new, k_blocks, k_meta, v_blocks, v_meta, seq_len, B, H, T_max, stream);
+}
+
+int ecco_kv_append_minmax(const ecco_model* mk, const ecco_model* mv, const uint16_t* k_new, const uint16_t* v_new,
+                          void* k_blocks, uint32_t* k_meta, void* v_blocks, uint32_t* v_meta,
+                          const int32_t* seq_len, int B, int H, int T_max, void* stream) {
+    return kv_append_common(true, mk, mv, k_new, v_new, k_blocks, k_meta, v_blocks, v_meta, seq_len, B, H, T_max, stream);
 }
 
 int ecco_kv_attend(const ecco_model* mk, const ecco_model* mv, const uint16_t* q,

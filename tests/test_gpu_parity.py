@@ -267,6 +267,48 @@ def test_kv_append_matches_oracle(dev, oracle):
     assert okm[2].sum() == 0 and okm[0, :, :5].all()
 
 
+def test_minmax_selector_matches_oracle(dev, oracle, tiny):
+    """Min/max pattern selector: blocks and meta words bit-exact against the oracle, bulk and append, S = 16 and 64."""
+    # bulk, weights (S = 16) on a ragged group count; K cache with S = 64 (one lane per pattern, all lanes used)
+    m = tiny["m"]
+    w = tiny["w"].reshape(-1, 128)[: 4 * 61 + 3]
+    ob, om = oracle.encode_minmax(m.centroids, m.code_lens, w.view(np.uint16))
+    blocks, meta = E.ecco_encode_minmax(m, t16(w, dev))
+    assert np.array_equal(np_meta(meta), om) and np.array_equal(np_blocks(blocks), ob)
+    assert not np.array_equal(om, tiny["om"][: om.size])  # the two selectors do differ on this input
+    assert np.array_equal(E.ecco_decode(m, blocks, meta).cpu().numpy().view(np.uint16),
+                          oracle.decode(m.centroids, m.code_lens, ob, om))
+    k, v = W.kv_cache(2, 4, 160, 128, seed=3)
+    m64 = E.ecco_model_to_device(E.ecco_fit_patterns(k[:, :, :96], 64, 12, 3), 0)
+    x = k.reshape(-1, 128).copy()
+    x[7] = 0                                   # all-zero group: scale 0, every fitness 0, pattern 0
+    x[8] = np.float16(0.5)                     # constant group: min = max = absmax
+    x[9] = -np.abs(x[9])                       # all negative
+    ob, om = oracle.encode_minmax(m64.centroids, m64.code_lens, x.view(np.uint16))
+    blocks, meta = E.ecco_encode_minmax(m64, t16(x, dev))
+    assert np.array_equal(np_meta(meta), om) and np.array_equal(np_blocks(blocks), ob)
+    assert (om[7] & 0x3FFFFF) == 0  # scale 0 and pattern 0 (the mode bit depends on the code of index 0)
+    # append: five steps, a full sequence writes nothing; B*H not a multiple of the wavefronts per workgroup
+    B, H, T = 3, 5, 9
+    k, v, mk, mv = _kv_setup(dev, oracle, B, H, T, 8)
+    kb = torch.zeros((B, H, T, 64), dtype=torch.uint8, device=dev); km = torch.zeros((B, H, T), dtype=torch.int32, device=dev)
+    vb = torch.zeros_like(kb); vm = torch.zeros_like(km)
+    okb = np.zeros((B, H, T, 64), np.uint8); okm = np.zeros((B, H, T), np.uint32)
+    ovb = np.zeros_like(okb); ovm = np.zeros_like(okm)
+    seq = np.array([0, 4, T], np.int32)
+    for step in range(5):
+        cur = np.minimum(seq + step, T).astype(np.int32)
+        tok = np.minimum(cur, T - 1)
+        kn = np.stack([k[b, :, tok[b]] for b in range(B)]); vn = np.stack([v[b, :, tok[b]] for b in range(B)])
+        E.ecco_kv_append_minmax(mk, mv, t16(kn, dev), t16(vn, dev), kb, km, vb, vm, ti32(cur, dev), B, H, T)
+        oracle.kv_append(mk.centroids, mk.code_lens, mv.centroids, mv.code_lens, kn.view(np.uint16), vn.view(np.uint16),
+                         okb, okm, ovb, ovm, cur, B, H, T, minmax=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(kb.cpu().numpy(), okb) and np.array_equal(km.cpu().numpy().view(np.uint32), okm)
+    assert np.array_equal(vb.cpu().numpy(), ovb) and np.array_equal(vm.cpu().numpy().view(np.uint32), ovm)
+    assert okm[2].sum() == 0 and okm[0, :, :5].all()
+
+
 def test_kv_attend_matches_oracle(dev, oracle):
     B, H, T = 4, 3, 700  # several 256-token chunks and a ragged tail
     k, v, mk, mv = _kv_setup(dev, oracle, B, H, T, 16)
