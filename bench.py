@@ -72,7 +72,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true", help="launch every call from Python with its own event pair instead of replaying a HIP graph")
-    ap.add_argument("--only", default="", help="comma list of rows to run (kv_append,decode,gemv1,gemv8,gemv16,kv_attend)")
+    ap.add_argument("--only", default="", help="comma list of rows to run (kv_append,decode,gemv1,gemv8,gemv16,kv_attend; "
+                    "on request only: kv_append_minmax, encode, encode_minmax -- the bulk encoders run over the K cache)")
+    ap.add_argument("--selector-quality", action="store_true",
+                    help="add the reconstruction error of the min/max pattern selector against the least-squared-error search on the K and V caches")
     ap.add_argument("--workload", default="proj7b", choices=["proj7b", "mlp_up", "mlp_down", "proj70b"])
     ap.add_argument("--sweep", action="store_true", help="add an ecco_decode sweep over block counts 2^14..2^22 (as far as the workload has blocks)")
     args = ap.parse_args()
@@ -113,14 +116,36 @@ def main():
     # ---- KV cache ---------------------------------------------------------------------------------
     kc = W.CONFIGS["kv"]
     B, H, T = kc["batch"], kc["heads"], kc["tokens"]
-    kv_needed = want("kv_append") or want("kv_attend")
+    extra_rows = [r for r in ("kv_append_minmax", "encode", "encode_minmax") if r in only]
+    kv_needed = want("kv_append") or want("kv_attend") or bool(extra_rows) or args.selector_quality
     if kv_needed:
         k, v = W.kv_cache(B, H, T, 128, kc["seeds"][0])
         cal = kc["calib_tokens"]
         mk = E.ecco_model_to_device(E.ecco_fit_patterns(k[:, :, :cal], kc["S"], 12, kc["seeds"][0]), 0)
         mv = E.ecco_model_to_device(E.ecco_fit_patterns(v[:, :, :cal], kc["S"], 12, kc["seeds"][0] + 1), 0)
-        kb0, km0 = E.ecco_encode(mk, torch.from_numpy(k).to(dev))
+        k_dev = torch.from_numpy(k).to(dev)
+        kb0, km0 = E.ecco_encode(mk, k_dev)
         vb0, vm0 = E.ecco_encode(mv, torch.from_numpy(v).to(dev))
+        selector_quality = None
+        if args.selector_quality:
+            selector_quality = {}
+            for name, model, src, fb, fm in (("K", mk, k_dev, kb0, km0), ("V", mv, torch.from_numpy(v).to(dev), vb0, vm0)):
+                x = src.reshape(-1, 128).float()
+                mb, mm = E.ecco_encode_minmax(model, src)
+                err_full = (E.ecco_decode(model, fb, fm).float() - x).square().sum(dim=1)
+                err_mm = (E.ecco_decode(model, mb, mm).float() - x).square().sum(dim=1)
+                power = x.square().sum().item()
+                selector_quality[name] = {
+                    "rel_mse_least_squares": err_full.sum().item() / power, "rel_mse_minmax": err_mm.sum().item() / power,
+                    "mse_ratio": err_mm.sum().item() / err_full.sum().item(),
+                    "same_pattern_fraction": float((((fm >> 16) & 63) == ((mm >> 16) & 63)).float().mean()),
+                    "raw_block_fraction_least_squares": float(((fm >> 22) & 1).float().mean()),
+                    "raw_block_fraction_minmax": float(((mm >> 22) & 1).float().mean())}
+                del x, mb, mm, err_full, err_mm
+        if not ("encode" in only or "encode_minmax" in only):
+            del k_dev
+        else:
+            enc_blocks, enc_meta = torch.empty_like(kb0), torch.empty_like(km0)
         kv_copies = 10  # 10 x 143 MB of compressed K+V
         kbs = [kb0.view(B, H, T, 64)] + [kb0.view(B, H, T, 64).clone() for _ in range(kv_copies - 1)]
         kms = [km0.view(B, H, T)] + [km0.view(B, H, T).clone() for _ in range(kv_copies - 1)]
@@ -136,8 +161,7 @@ def main():
     torch.cuda.synchronize()
 
     # ---- the step -----------------------------------------------------------------------------------
-    row_names = [r for r in ("kv_append", "decode", "gemv1", "gemv8", "gemv16", "kv_attend") if want(r)]
-    launches = {"kv_append": 1, "decode": 1, "gemv1": 1, "gemv8": 1, "gemv16": 1, "kv_attend": 1}
+    row_names = [r for r in ("kv_append", "decode", "gemv1", "gemv8", "gemv16", "kv_attend") if want(r)] + extra_rows
     counter = [0]
 
     def next_copy(n):
@@ -148,6 +172,13 @@ def main():
         if row == "kv_append":
             c = next_copy(kv_copies)
             E.ecco_kv_append(mk, mv, k_new, v_new, kbs[c], kms[c], vbs[c], vms[c], seq_app, B, H, T)
+        elif row == "kv_append_minmax":
+            c = next_copy(kv_copies)
+            E.ecco_kv_append_minmax(mk, mv, k_new, v_new, kbs[c], kms[c], vbs[c], vms[c], seq_app, B, H, T)
+        elif row == "encode":
+            E.ecco_encode(mk, k_dev, enc_blocks, enc_meta)
+        elif row == "encode_minmax":
+            E.ecco_encode_minmax(mk, k_dev, enc_blocks, enc_meta)
         elif row == "decode":
             c = next_copy(n_copies)
             E.ecco_decode(m, wb[c], wm[c], dec_out)
@@ -214,14 +245,14 @@ def main():
         # per-row duration: a graph of one launch per rotating copy of that row's input, replayed
         ms = {}
         for row in row_names:
-            n = kv_copies if row.startswith("kv_") else n_copies
+            n = 2 if row.startswith("encode") else kv_copies if row.startswith("kv_") else n_copies
             def one_round(row=row, n=n):
                 for _ in range(n):
                     run_row(row)
             g = capture(one_round)
             g.replay()
             torch.cuda.synchronize()
-            replays = max(1, int(np.ceil(max(args.steps, 100) / n)))
+            replays = 2 if row.startswith("encode") else max(1, int(np.ceil(max(args.steps, 100) / n)))
             ms[row] = timed_replays(g, replays) / (replays * n)
             del g
 
@@ -287,8 +318,11 @@ def main():
         elif r == "decode":
             d["GBps_total_traffic"] = n_groups * (BYTES_PER_GROUP + 256) / (ms[r] * 1e-3) / 1e9
             d["GBps_compressed"] = comp_bytes / (ms[r] * 1e-3) / 1e9
-        elif r == "kv_append":
+        elif r.startswith("kv_append"):
             d["groups_per_s"] = 2 * B * H / (ms[r] * 1e-3)
+        elif r.startswith("encode"):
+            d["groups_per_s"] = B * H * T / (ms[r] * 1e-3)
+            d["GBps_fp16_in_plus_blocks_out"] = B * H * T * (256 + BYTES_PER_GROUP) / (ms[r] * 1e-3) / 1e9
         elif r == "kv_attend":
             d["steps_per_s"] = 1.0 / (ms[r] * 1e-3)
             d["GBps_compressed"] = 2 * B * H * T * BYTES_PER_GROUP / (ms[r] * 1e-3) / 1e9
@@ -323,6 +357,8 @@ def main():
     }
     if sweep is not None:
         out["decode_sweep"] = sweep
+    if kv_needed and selector_quality is not None:
+        out["selector_quality"] = selector_quality
     if not args.no_cpu_baseline and want("gemv1"):
         out["cpu_baseline"] = cpu_baseline(m, blocks0.cpu().numpy(), meta0.cpu().numpy().view(np.uint32), rows, cols,
                                            xs[1].cpu().numpy())

@@ -248,6 +248,18 @@ __device__ __forceinline__ float wave_sum(float t) {
     return (read_lane(t, 0) + read_lane(t, 16)) + (read_lane(t, 32) + read_lane(t, 48));
 }
 
+// the same walk for any associative, commutative, exact operation (minimum, maximum): the order does not matter
+template <class T, class Op>
+__device__ __forceinline__ T wave_all(T v, Op op) {
+    float t = __builtin_bit_cast(float, v);
+    const auto f = [&](float a, float b) { return __builtin_bit_cast(float, op(__builtin_bit_cast(T, a), __builtin_bit_cast(T, b))); };
+    t = f(t, dpp_mov<0xB1>(t));
+    t = f(t, dpp_mov<0x4E>(t));
+    t = f(t, dpp_mov<0x141>(t));
+    t = f(t, dpp_mov<0x140>(t));
+    return __builtin_bit_cast(T, f(f(read_lane(t, 0), read_lane(t, 16)), f(read_lane(t, 32), read_lane(t, 48))));
+}
+
 struct UnitLoad {
     uint4 v0, v1;
     uint32_t meta;
@@ -602,9 +614,7 @@ struct EncLds {
 
 // The group's scale: the largest magnitude among the 128 values (two per lane), as an FP16 bit pattern.
 __device__ inline uint32_t group_scale_bits(uint32_t hx0, uint32_t hx1) {
-    uint32_t smax = max(hx0 & 0x7FFFu, hx1 & 0x7FFFu);
-    for (int m = 1; m < 64; m <<= 1) smax = max(smax, (uint32_t)__shfl_xor((int)smax, m));
-    return smax;
+    return wave_all(max(hx0 & 0x7FFFu, hx1 & 0x7FFFu), [](uint32_t a, uint32_t b) { return max(a, b); });
 }
 
 struct EncChoice {
@@ -685,11 +695,8 @@ __device__ inline void pack_group(const EncLds& E, uint32_t smax, int best_p, ui
 // Lane p rates pattern p (S <= 64); the least fitness wins, the lowest pattern on a tie.  Uniform result.
 __device__ inline int select_minmax(const EncLds& E, int S, float s, float x0, float x1) {
     const int lane = threadIdx.x & 63;
-    float lo = fminf(x0, x1), hi = fmaxf(x0, x1);
-    for (int m = 1; m < 64; m <<= 1) {
-        lo = fminf(lo, __shfl_xor(lo, m));
-        hi = fmaxf(hi, __shfl_xor(hi, m));
-    }
+    const float lo = wave_all(fminf(x0, x1), [](float a, float b) { return fminf(a, b); });
+    const float hi = wave_all(fmaxf(x0, x1), [](float a, float b) { return fmaxf(a, b); });
     float f = __builtin_inff();
     if (lane < S) {
         const float first = half_bits_f(dequant_bits(__half_as_ushort(E.cent[lane * kK]), s));
@@ -697,15 +704,9 @@ __device__ inline int select_minmax(const EncLds& E, int S, float s, float x0, f
         const float dlo = __fsub_rn(lo, first), dhi = __fsub_rn(hi, last);
         f = __fadd_rn(__fmul_rn(dlo, dlo), __fmul_rn(dhi, dhi));
     }
-    int p = lane;
-    for (int m = 1; m < 64; m <<= 1) {
-        const float fo = __shfl_xor(f, m);
-        const int po = __shfl_xor(p, m);
-        const bool take = fo < f || (fo == f && po < p);
-        f = take ? fo : f;
-        p = take ? po : p;
-    }
-    return __builtin_amdgcn_readfirstlane(p);
+    const float least = wave_all(f, [](float a, float b) { return fminf(a, b); });
+    // lowest lane holding the least fitness (no lane does if the input held a NaN, against the contract: pattern 0 then)
+    return max(__ffsll((long long)__ballot(f == least)) - 1, 0);
 }
 
 // One wavefront encodes one group (hx0, hx1: this lane's two values as FP16 bits).  kMinMax: the pattern comes
