@@ -9,6 +9,7 @@
 //            online compressor's min/max pattern selector (Section 3.2 "KV Cache Compression")
 //   decode   Section 4.2 (pattern retrieval, Huffman decode, centroid x scale)
 //   gemv / attention: the consumers of the decompressed values (Section 2.1), in double.
+//   act      the 2x activation codec (Section 3.2 "Activation Compression", low-ratio units of Sections 4.2, 4.3)
 //
 // Parity status:
 //   fp16 helpers, dequant rule ........ pinned (exhaustive, against integer arithmetic and numpy)
@@ -16,6 +17,9 @@
 //   encode / decode ................... pinned (brute force on tiny inputs, round trip, uniform 4-bit special case)
 //   min/max pattern selector .......... pinned (hand-worked example, exact rational brute force, mirror symmetry,
 //                                       single-pattern case equals the least-squared-error encoder)
+//   2x activation codec ............... pinned (reconstruction rule against exact rationals for every code, hand-packed
+//                                       block, power-of-two scale = plain round-to-nearest integers, constant and
+//                                       extreme groups, error bound of a uniform quantiser)
 //   k-means ........................... pinned (monotone objective, Lloyd-Max quantiser of a Gaussian)
 //   gemv / attention .................. pinned (unit vectors, ones, seq_len 1, q = 0)
 //   fitted pattern VALUES and code LENGTHS for a given tensor: parity unpinned -- the paper prints
@@ -522,6 +526,113 @@ void oracle_decode(const uint16_t* centroids, const uint8_t* lens, int S, const 
         Meta mt = unpack_meta(meta[g], S);
         for (int i = 0; i < G; ++i)
             dst[(size_t)g * G + i] = oracle_dequant(centroids[mt.pattern * K + idx[i]], mt.scale);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// 2x activation codec: uniform integer quantisation with a zero point, 7 bits per value, the scale
+// and the zero point spread over the spare bit of every byte (Section 3.2 "Activation Compression";
+// decompressor and compressor of Sections 4.2 and 4.3).  The paper fixes the widths (7-bit data,
+// 16-bit scale, 16-bit zero point, 512-bit block) and that the codes are sign-extended; this
+// build's reading of the rest:
+//   s = fp16( (max - min) / 127 )            difference and quotient in fp32
+//   z = fp16( min + 64 * s )                 the value of code 0; fp32 sum
+//   q = round-to-nearest-even( (x - z) * (1 / s) ), clamped to -64..63       fp32, each step rounded;
+//       s = 0 (constant group): q = 0;  a code whose reconstruction would not be finite moves
+//       towards 0 (at most twice) -- only possible next to the largest FP16 magnitudes
+//   x' = fp16( q * s + z )                   exact value, one rounding
+// Every finite FP16 value is an integer multiple of 2^-24, so the last rule is done in integers.
+static int64_t half_scaled(uint16_t h) {  // value * 2^24 of a finite fp16
+    int e = (h >> 10) & 0x1F, m = h & 0x3FF;
+    int64_t a = e == 0 ? m : ((int64_t)(m | 0x400) << (e - 1));
+    return (h & 0x8000) ? -a : a;
+}
+
+static uint16_t half_from_scaled(int64_t n) {  // fp16 nearest (ties to even) to n * 2^-24, n != 0
+    uint16_t sign = n < 0 ? 0x8000 : 0;
+    uint64_t a = (uint64_t)(n < 0 ? -n : n);
+    if (a < 2048) return (uint16_t)(sign | a);  // subnormals and the first binade: bit pattern = a
+    int t = 63;
+    while (!((a >> t) & 1)) --t;
+    int shift = t - 10;
+    uint64_t mant = a >> shift, rem = a & ((1ull << shift) - 1), half = 1ull << (shift - 1);
+    if (rem > half || (rem == half && (mant & 1))) ++mant;
+    if (mant == 2048) { mant = 1024; ++shift; }
+    int e = shift + 1;
+    if (e >= 31) return (uint16_t)(sign | 0x7C00);
+    return (uint16_t)(sign | (e << 10) | (mant - 1024));
+}
+
+uint16_t oracle_act_dequant(int q, uint16_t s_bits, uint16_t z_bits) {
+    int64_t n = (int64_t)q * half_scaled(s_bits) + half_scaled(z_bits);
+    if (n != 0) return half_from_scaled(n);
+    // an exact zero: -0 only if both addends are -0 (IEEE 754 sum rule); the product of code 0 is +0 * s
+    bool prod_is_zero = q == 0 || (s_bits & 0x7FFF) == 0;
+    bool prod_neg = (q < 0) != ((s_bits & 0x8000) != 0);
+    bool z_neg_zero = z_bits == 0x8000;
+    return (prod_is_zero && prod_neg && z_neg_zero) ? 0x8000 : 0x0000;
+}
+
+void oracle_act_params(const uint16_t* x, uint16_t* s_bits, uint16_t* z_bits) {
+    float lo = oracle_h2f(x[0]), hi = lo;
+    for (int i = 1; i < ORACLE_ACT_GROUP; ++i) {
+        float v = oracle_h2f(x[i]);
+        if (v < lo) lo = v;
+        if (v > hi) hi = v;
+    }
+    float range = hi - lo;
+    float step = range / 127.0f;
+    *s_bits = oracle_f2h(step);
+    float s = oracle_h2f(*s_bits);
+    float scaled = 64.0f * s;
+    float zero = lo + scaled;
+    *z_bits = oracle_f2h(zero);
+}
+
+static bool half_is_finite(uint16_t h) { return (h & 0x7C00) != 0x7C00; }
+
+void oracle_act_encode(const uint16_t* src, size_t n_groups, uint8_t* blocks) {
+#pragma omp parallel for num_threads(g_threads) schedule(static)
+    for (long g = 0; g < (long)n_groups; ++g) {
+        const uint16_t* x = src + (size_t)g * ORACLE_ACT_GROUP;
+        uint8_t* blk = blocks + (size_t)g * ORACLE_BLOCK_BYTES;
+        uint16_t s_bits, z_bits;
+        oracle_act_params(x, &s_bits, &z_bits);
+        float s = oracle_h2f(s_bits), z = oracle_h2f(z_bits);
+        float inv = s == 0.0f ? 0.0f : 1.0f / s;
+        uint32_t side = (uint32_t)s_bits | ((uint32_t)z_bits << 16);
+        for (int i = 0; i < ORACLE_ACT_GROUP; ++i) {
+            int q = 0;
+            if (s != 0.0f) {
+                float d = oracle_h2f(x[i]) - z;
+                float u = d * inv;
+                float r = std::nearbyint(u);  // default rounding mode: to nearest, ties to even
+                if (r < -64.0f) r = -64.0f;
+                if (r > 63.0f) r = 63.0f;
+                q = (int)r;
+                for (int it = 0; it < 2; ++it)
+                    if (!half_is_finite(oracle_act_dequant(q, s_bits, z_bits))) q += q > 0 ? -1 : 1;
+            }
+            int side_bit = i < 32 ? (int)((side >> i) & 1u) : 0;
+            blk[i] = (uint8_t)((q & 0x7F) | (side_bit << 7));
+        }
+    }
+}
+
+void oracle_act_decode(const uint8_t* blocks, size_t n_groups, uint16_t* dst) {
+#pragma omp parallel for num_threads(g_threads) schedule(static)
+    for (long g = 0; g < (long)n_groups; ++g) {
+        const uint8_t* blk = blocks + (size_t)g * ORACLE_BLOCK_BYTES;
+        uint32_t side = 0;
+        for (int i = 0; i < 32; ++i) side |= (uint32_t)(blk[i] >> 7) << i;
+        uint16_t s_bits = (uint16_t)(side & 0xFFFFu), z_bits = (uint16_t)(side >> 16);
+        for (int i = 0; i < ORACLE_ACT_GROUP; ++i) {
+            int q = blk[i] & 0x7F;
+            if (q & 0x40) q -= 128;  // sign extension of the 7-bit code
+            // a block the encoder never writes (scale or zero point not finite) has no defined values: NaN here
+            dst[(size_t)g * ORACLE_ACT_GROUP + i] =
+                (half_is_finite(s_bits) && half_is_finite(z_bits)) ? oracle_act_dequant(q, s_bits, z_bits) : (uint16_t)0x7E00;
+        }
     }
 }
 

@@ -80,6 +80,19 @@ void oracle_decode_indices(const uint8_t* lens, int S, const uint8_t* blocks, co
 void oracle_decode(const uint16_t* centroids, const uint8_t* lens, int S, const uint8_t* blocks,
                    const uint32_t* meta, size_t n_groups, uint16_t* dst /* n_groups*128 fp16 */);
 
+/* ---- 2x activation codec (Section 3.2 "Activation Compression", Section 4.2 / 4.3 low-ratio units) ----
+ * 64 FP16 values -> one 64-byte block: byte i = 7-bit two's-complement code q_i in bits 6:0, one
+ * metadata bit in bit 7.  The metadata bits of bytes 0..15 are the FP16 scale s (bit i of s in byte i),
+ * those of bytes 16..31 the FP16 zero point z, those of bytes 32..63 are 0.  Reconstruction:
+ * x_i = fp16( q_i * s + z ), the exact value rounded once (what a fused FP16 multiply-add gives). */
+enum { ORACLE_ACT_GROUP = 64 };
+/* the reconstruction rule for one code (q in -64..63; s, z finite FP16 bit patterns) */
+uint16_t oracle_act_dequant(int q, uint16_t s_bits, uint16_t z_bits);
+/* scale and zero point of one group of 64 values */
+void oracle_act_params(const uint16_t* x, uint16_t* s_bits, uint16_t* z_bits);
+void oracle_act_encode(const uint16_t* src, size_t n_groups, uint8_t* blocks /* n_groups*64 */);
+void oracle_act_decode(const uint8_t* blocks, size_t n_groups, uint16_t* dst /* n_groups*64 */);
+
 /* ---- consumers -------------------------------------------------------------------------- */
 /* y[b][r] = sum_c w[r][c] * x[b][c], accumulated in double over the decoded fp16 weights */
 void oracle_gemv(const uint16_t* centroids, const uint8_t* lens, int S, const uint8_t* blocks,

@@ -233,3 +233,38 @@ def kv_attend(ck, lk, cv, lv, q, k_blocks, k_meta, v_blocks, v_meta, seq_len, B,
                            _p(q), _p(k_blocks), _p(k_meta), _p(v_blocks), _p(v_meta), _p(seq_len),
                            C.c_int(B), C.c_int(H), C.c_int(T_max), _p(out))
     return out
+
+
+ACT_GROUP = 64
+
+
+def act_dequant(q: int, s_bits: int, z_bits: int) -> int:
+    L = lib()
+    L.oracle_act_dequant.restype = C.c_uint16
+    L.oracle_act_dequant.argtypes = [C.c_int, C.c_uint16, C.c_uint16]
+    return int(L.oracle_act_dequant(q, s_bits, z_bits))
+
+
+def act_params(x_u16):
+    x = _c(x_u16, np.uint16).reshape(-1)
+    assert x.size == ACT_GROUP
+    s, z = C.c_uint16(0), C.c_uint16(0)
+    lib().oracle_act_params(_p(x), C.byref(s), C.byref(z))
+    return int(s.value), int(z.value)
+
+
+def act_encode(src_u16):
+    src = _c(src_u16, np.uint16).reshape(-1)
+    assert src.size % ACT_GROUP == 0
+    n = src.size // ACT_GROUP
+    blocks = np.zeros((n, BLOCK_BYTES), np.uint8)
+    lib().oracle_act_encode(_p(src), C.c_size_t(n), _p(blocks))
+    return blocks
+
+
+def act_decode(blocks):
+    blocks = _c(blocks, np.uint8).reshape(-1, BLOCK_BYTES)
+    n = blocks.shape[0]
+    dst = np.zeros((n, ACT_GROUP), np.uint16)
+    lib().oracle_act_decode(_p(blocks), C.c_size_t(n), _p(dst))
+    return dst

@@ -642,3 +642,117 @@ def test_kv_append_and_attend_special_cases(oracle, tiny):
     # seq_len 0 gives zeros
     o = oracle.kv_attend(cent, lens, cent, lens, q.view(np.uint16), kb, km, vb, vm, np.zeros(B, np.int32), B, H, T)
     assert not o.any()
+
+
+# --------------------------------------------------------------------------------------------
+# 2x activation codec (Section 3.2 "Activation Compression"; Sections 4.2, 4.3 low-ratio units)
+def _act_unpack(block):
+    """Codes, scale bits and zero-point bits of one block, read straight from the format statement."""
+    side = 0
+    for i in range(32):
+        side |= (int(block[i]) >> 7) << i
+    q = [(int(b) & 0x7F) - (128 if int(b) & 0x40 else 0) for b in block]
+    return q, side & 0xFFFF, side >> 16
+
+
+def test_act_constants(oracle):
+    c = _constants()
+    assert oracle.ACT_GROUP * (c["act_data_bits"] + 1) == 8 * c["block_bytes"]      # 64 values x 8 bits = 512
+    assert c["act_scale_bits"] + c["act_zero_point_bits"] <= oracle.ACT_GROUP          # one spare bit per byte holds them
+    assert 2 * oracle.ACT_GROUP // c["block_bytes"] == 2                             # the 2x ratio
+
+
+def test_act_dequant_rule_exact_rational(oracle):
+    """fp16(q*s + z) is the exact value rounded once: every code, many (s, z) pairs, exact rationals."""
+    rng = np.random.default_rng(11)
+    pairs = [(0x3400, 0x0000), (0x0001, 0x0001), (0x0001, 0x8001), (0x6408, 0x6040), (0x2851, 0xB150), (0x03FF, 0x0400),
+             (0x3C00, 0x6BFF), (0xB400, 0x3C00), (0x0000, 0x4248)]
+    while len(pairs) < 160:
+        sb = int(rng.integers(0, 0x6410))                 # scales up to about 1030
+        zb = int(rng.integers(0, 0x7C00)) | (0x8000 if rng.random() < 0.5 else 0)
+        pairs.append((sb, zb))
+    for sb, zb in pairs:
+        sf, zf = half_to_fraction(sb), half_to_fraction(zb)
+        for q in range(-64, 64):
+            exact = q * sf + zf
+            want = round_fraction_to_half(exact)
+            got = oracle.act_dequant(q, sb, zb)
+            if exact == 0:
+                assert (got & 0x7FFF) == 0
+            else:
+                assert got == want, (q, hex(sb), hex(zb))
+
+
+def test_act_hand_packed_block(oracle):
+    """Everything exact: s = 0.25, lo = -16, hi = 15.75 = lo + 127 s, so z = 0 and q = x / s."""
+    x = np.array([-16 + 0.5 * i for i in range(63)] + [15.75], np.float16)
+    sb, zb = oracle.act_params(x.view(np.uint16))
+    assert (sb, zb) == (0x3400, 0x0000)
+    blk = oracle.act_encode(x.view(np.uint16))[0]
+    side_bits = {10, 12, 13}                             # 0x3400 = bits 10, 12, 13 of the scale; zero point 0
+    for i in range(64):
+        q = -64 + 2 * i if i < 63 else 63
+        assert blk[i] == ((q & 0x7F) | (0x80 if i in side_bits else 0)), i
+    assert np.array_equal(oracle.act_decode(blk).view(np.float16)[0], x)
+    # the spare bits of bytes 32..63 are reserved: set, they change nothing
+    blk2 = blk.copy(); blk2[32:] |= 0x80
+    assert np.array_equal(oracle.act_decode(blk2), oracle.act_decode(blk))
+    # a shuffled group has the same parameters and the codes move with the values
+    perm = np.random.default_rng(1).permutation(64)
+    blk3 = oracle.act_encode(x[perm].view(np.uint16))[0]
+    assert _act_unpack(blk3)[1:] == (0x3400, 0)
+    assert [_act_unpack(blk3)[0][j] for j in range(64)] == [_act_unpack(blk)[0][perm[j]] for j in range(64)]
+
+
+def test_act_power_of_two_scale_is_plain_rounding(oracle):
+    """With s a power of two and z = 0 the codec is symmetric integer rounding: q = rint(x / s), ties to even."""
+    rng = np.random.default_rng(12)
+    for k in (-3, 0, 4):
+        s = 2.0 ** k
+        x = rng.uniform(-63.4 * s, 62.4 * s, 64)
+        x[0], x[1] = -64 * s, 63 * s                      # pins min and max: range 127 s, zero point 0
+        x[2:6] = np.array([0.5, 1.5, -2.5, 7.5]) * s      # exact ties
+        x = x.astype(np.float16)
+        blk = oracle.act_encode(x.view(np.uint16))[0]
+        q, sb, zb = _act_unpack(blk)
+        assert half_to_fraction(sb) == Fraction(2) ** k and (zb & 0x7FFF) == 0
+        want = np.rint(x.astype(np.float64) / s).astype(int)
+        assert q == list(want)
+        assert q[2:6] == [0, 2, -2, 8]
+        dec = oracle.act_decode(blk).view(np.float16)[0]
+        assert np.array_equal(dec.astype(np.float64), want * s)
+
+
+def test_act_roundtrip_bound_and_degenerate_groups(oracle):
+    rng = np.random.default_rng(13)
+    groups = [rng.normal(0, 1, 64), rng.normal(3, 0.01, 64), rng.uniform(-1e-3, 1e-3, 64), np.abs(rng.normal(0, 5, 64)),
+              rng.normal(0, 1, 64) ** 3 * 100, np.full(64, 0.3), np.zeros(64), np.full(64, -65504.0),
+              np.concatenate([[65504.0, -65504.0], rng.uniform(-65504, 65504, 62)]),
+              np.concatenate([[65504.0, 60000.0], rng.uniform(60000, 65504, 62)]),
+              np.concatenate([[6e-8, 0.0], np.zeros(62)]), np.concatenate([[1000.0, 1000.5], np.full(62, 1000.0)])]
+    x = np.array(groups).astype(np.float16)
+    blocks = oracle.act_encode(x.view(np.uint16))
+    dec = oracle.act_decode(blocks)
+    assert (((dec >> 10) & 0x1F) != 31).all()             # finite in, finite out
+    for g in range(x.shape[0]):
+        q, sb, zb = _act_unpack(blocks[g])
+        assert (sb, zb) == oracle.act_params(x[g].view(np.uint16))
+        sf = float(half_to_fraction(sb))
+        xg = x[g].astype(np.float64)
+        dg = dec[g].view(np.float16).astype(np.float64)
+        assert all(int(dec[g, i]) == oracle.act_dequant(q[i], sb, zb) for i in range(64))
+        # uniform quantiser: half a step, plus the FP16 rounding of the zero point and of the result
+        ulp = 2.0 ** (max(int(np.floor(np.log2(np.abs(xg).max()))), -14) - 10) if np.abs(xg).max() > 0 else 0.0
+        # (one more step where the nearest code would have reconstructed beyond the largest finite FP16 value)
+        step_back = sf if np.abs(xg).max() + sf >= 65520 else 0.0
+        assert np.abs(dg - xg).max() <= 0.501 * sf + 1.0 * ulp + 65 * sf * 2.0 ** -11 + step_back, g
+        # order is kept: a larger value never gets a smaller code
+        order = np.argsort(xg, kind="stable")
+        assert (np.diff(np.array(q)[order]) >= 0).all()
+        if sf == 0.0:                                      # constant group (or a range below the smallest step): code 0 everywhere
+            assert not any(q) and (dg == xg.min()).all()
+    assert np.array_equal(dec[5].view(np.float16), x[5]) and np.array_equal(dec[7].view(np.float16), x[7])
+    # at the top of the FP16 range the nearest code can reconstruct to infinity; the encoder then steps back
+    q8, s8, z8 = _act_unpack(blocks[8])
+    assert (s8, z8) == (0x6408, 0x6040)                    # 1032 and 544: code 63 would give 65560, beyond 65504
+    assert oracle.act_dequant(63, s8, z8) == 0x7C00 and max(q8) == 62 and q8[0] == 62 and q8[1] == -64
