@@ -164,6 +164,25 @@ int ecco_kv_append_minmax(const ecco_model* mk, const ecco_model* mv,
                           void* k_blocks, uint32_t* k_meta, void* v_blocks, uint32_t* v_meta,
                           const int32_t* seq_len, int B, int H, int T_max, void* stream);
 
+/* ---- 2x activation codec (Section 3.2 "Activation Compression"; low-ratio units of Sections 4.2, 4.3) ----------
+ * Uniform integer quantisation with a zero point, 7 bits per value: 64 FP16 values (128 bytes) become one 64-byte
+ * block, no side data, no model.
+ *   byte i of a block:  bits 6:0  the two's-complement code q_i (-64..63) of value i;  bit 7  one metadata bit.
+ *   The metadata bits of bytes 0..15 are the FP16 scale s (bit i of s in byte i), those of bytes 16..31 the FP16
+ *   zero point z (bit i-16 of z in byte i), those of bytes 32..63 are written 0 and ignored by the decoder.
+ *   Reconstruction:  x_i = fp16( q_i * s + z ), the exact value rounded once (a fused FP16 multiply-add).
+ *   Encoder, per group of 64 consecutive values (all finite):
+ *     s = fp16((max - min) / 127),  z = fp16(min + 64 s)           FP32 operations, each rounded on its own
+ *     q_i = round-to-nearest-even((x_i - z) * (1 / s)) clamped to -64..63;  s = 0 (constant group): q_i = 0;
+ *     a code whose reconstruction would be infinite (only next to +-65504) moves one step towards 0, at most twice.
+ *   The paper fixes the widths (7 data bits, 16-bit scale and zero point in the eighth bits, 512-bit block) and the
+ *   sign extension; bit order, the formulas for s, z and q and the reserved upper half are this library's reading.
+ *   src / dst   device, n_groups * 64 FP16, 16-byte aligned;   blocks   device, n_groups * 64 bytes, 64-byte aligned.
+ * A block whose scale or zero point is not finite (never written by the encoder) decodes to unspecified values.
+ * Errors: EINVAL (null pointer), ESHAPE (n_groups > 2^40), EALIGN, EHIP.  n_groups == 0 returns OK and touches nothing. */
+int ecco_act_encode(const uint16_t* src_fp16, size_t n_groups, void* blocks, void* stream);
+int ecco_act_decode(const void* blocks, size_t n_groups, uint16_t* dst_fp16, void* stream);
+
 /* Single-query attention over the compressed caches (Section 2.1): per (b,h), scores
  * q.K_t / sqrt(128) for t < seq_len[b], softmax, out = sum_t p_t V_t.  No mask beyond seq_len.
  *   q  device [B][H][128] FP16, 16-byte aligned;  out  device [B][H][128] FP32 (zeros where seq_len[b] <= 0).

@@ -19,7 +19,7 @@ EXPORTS = [
     "ecco_strerror", "ecco_fit_patterns", "ecco_model_create", "ecco_model_save", "ecco_model_load",
     "ecco_model_S", "ecco_model_centroids", "ecco_model_code_lens", "ecco_model_to_device", "ecco_model_free",
     "ecco_encode", "ecco_decode", "ecco_decode_indices", "ecco_decode_gemv", "ecco_kv_append", "ecco_kv_attend",
-    "ecco_encode_minmax", "ecco_kv_append_minmax",
+    "ecco_encode_minmax", "ecco_kv_append_minmax", "ecco_act_encode", "ecco_act_decode",
 ]
 
 
@@ -56,6 +56,8 @@ def lib():
         L.ecco_kv_append.argtypes = [vp] * 9 + [i32, i32, i32, vp]
         L.ecco_kv_append_minmax.argtypes = [vp] * 9 + [i32, i32, i32, vp]
         L.ecco_kv_attend.argtypes = [vp] * 8 + [i32, i32, i32, vp, vp]
+        L.ecco_act_encode.argtypes = [vp, sz, vp, vp]
+        L.ecco_act_decode.argtypes = [vp, sz, vp, vp]
         _lib = L
     return _lib
 
@@ -224,3 +226,26 @@ def ecco_kv_attend(mk: Model, mv: Model, q, k_blocks, k_meta, v_blocks, v_meta, 
     _check(lib().ecco_kv_attend(mk.handle, mv.handle, _dp(q), _dp(k_blocks), _dp(k_meta), _dp(v_blocks), _dp(v_meta),
                                 _dp(seq_len), B, H, T_max, _dp(out), _stream()), "ecco_kv_attend")
     return out
+
+
+ACT_GROUP = 64
+
+
+def ecco_act_encode(src, blocks=None):
+    """src: CUDA FP16 tensor with numel % 64 == 0.  Returns blocks uint8 [n, 64]."""
+    import torch
+    assert src.dtype == torch.float16 and src.numel() % ACT_GROUP == 0
+    n = src.numel() // ACT_GROUP
+    if blocks is None:
+        blocks = torch.empty((n, BLOCK_BYTES), dtype=torch.uint8, device=src.device)
+    _check(lib().ecco_act_encode(_dp(src), n, _dp(blocks), _stream()), "ecco_act_encode")
+    return blocks
+
+
+def ecco_act_decode(blocks, dst=None):
+    import torch
+    n = blocks.numel() // BLOCK_BYTES
+    if dst is None:
+        dst = torch.empty((n, ACT_GROUP), dtype=torch.float16, device=blocks.device)
+    _check(lib().ecco_act_decode(_dp(blocks), n, _dp(dst), _stream()), "ecco_act_decode")
+    return dst

@@ -309,6 +309,54 @@ def test_minmax_selector_matches_oracle(dev, oracle, tiny):
     assert okm[2].sum() == 0 and okm[0, :, :5].all()
 
 
+def test_act_codec_matches_oracle(dev, oracle):
+    """2x activation codec: encoded blocks and decoded FP16 bit-exact; edge groups; arbitrary bytes; statuses."""
+    rng = np.random.default_rng(31)
+    edge = [np.full(64, 0.3), np.zeros(64), np.full(64, -65504.0),
+            np.concatenate([[65504.0, -65504.0], rng.uniform(-65504, 65504, 62)]),
+            np.concatenate([[65504.0, 60000.0], rng.uniform(60000, 65504, 62)]),
+            np.concatenate([[6e-8, 0.0], np.zeros(62)]), np.concatenate([[1000.0, 1000.5], np.full(62, 1000.0)]),
+            np.concatenate([[-6e-8, 6e-8], rng.uniform(-3e-6, 3e-6, 62)]), -np.abs(rng.normal(0, 3, 64)),
+            np.array([-16 + 0.5 * i for i in range(63)] + [15.75])]
+    n = 8192 * 64 + 4099   # more pieces than one pass of the grid, and a ragged tail
+    x = W.activation(n, 64, 104)
+    x[: len(edge)] = np.array(edge).astype(np.float16)
+    scale = (10.0 ** rng.uniform(-4, 3, n)).astype(np.float32)          # group magnitudes over seven decades
+    x[len(edge):] = (x[len(edge):].astype(np.float32) * scale[len(edge):, None]).astype(np.float16)
+    x[40:60] += np.float16(7.0)                                          # groups away from zero: the zero point matters
+    want_blocks = oracle.act_encode(x.view(np.uint16))
+    blocks = E.ecco_act_encode(t16(x, dev))
+    torch.cuda.synchronize()
+    got_blocks = blocks.cpu().numpy()
+    bad = np.nonzero((got_blocks != want_blocks).any(axis=1))[0]
+    assert bad.size == 0, (bad[:8], got_blocks[bad[0]], want_blocks[bad[0]])
+    want = oracle.act_decode(want_blocks)
+    got = E.ecco_act_decode(blocks).cpu().numpy().view(np.uint16)
+    assert np.array_equal(got, want)
+    assert (((got >> 10) & 0x1F) != 31).all()
+    # arbitrary bytes: any block with a finite scale and zero point decodes as the rule says (infinities included)
+    junk = rng.integers(0, 256, (4096, 64), dtype=np.uint8)
+    junk[:64, 32:] = 0xFF                                                # reserved bits set: ignored
+    side = np.zeros(4096, np.uint32)
+    for i in range(32):
+        side |= (junk[:, i].astype(np.uint32) >> 7) << i
+    ok = (((side >> 10) & 0x1F) != 31) & (((side >> 26) & 0x1F) != 31)
+    assert ok.sum() > 3000
+    got = E.ecco_act_decode(tu8(junk, dev)).cpu().numpy().view(np.uint16)
+    want = oracle.act_decode(junk)
+    assert np.array_equal(got[ok], want[ok])
+    # nothing to do / bad arguments
+    E.ecco_act_encode(torch.empty((0, 64), dtype=torch.float16, device=dev))
+    mis = torch.empty(64 + 8, dtype=torch.float16, device=dev)[4:68]
+    with pytest.raises(E.EccoError) as e:
+        E.ecco_act_encode(mis)
+    assert e.value.status == -3
+    misb = torch.empty(128, dtype=torch.uint8, device=dev)[16:80]
+    with pytest.raises(E.EccoError) as e:
+        E.ecco_act_decode(misb)
+    assert e.value.status == -3
+
+
 def test_kv_attend_matches_oracle(dev, oracle):
     B, H, T = 4, 3, 700  # several 256-token chunks and a ragged tail
     k, v, mk, mv = _kv_setup(dev, oracle, B, H, T, 16)
