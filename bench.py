@@ -73,7 +73,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true", help="launch every call from Python with its own event pair instead of replaying a HIP graph")
     ap.add_argument("--only", default="", help="comma list of rows to run (kv_append,decode,gemv1,gemv8,gemv16,kv_attend; "
-                    "on request only: kv_append_minmax, encode, encode_minmax -- the bulk encoders run over the K cache)")
+                    "on request only: kv_append_minmax, encode, encode_minmax -- the bulk encoders run over the K cache -- "
+                    "and act_encode, act_decode -- the 2x activation codec on 32768 x 4096 activations)")
     ap.add_argument("--selector-quality", action="store_true",
                     help="add the reconstruction error of the min/max pattern selector against the least-squared-error search on the K and V caches")
     ap.add_argument("--workload", default="proj7b", choices=["proj7b", "mlp_up", "mlp_down", "proj70b"])
@@ -117,6 +118,9 @@ def main():
     kc = W.CONFIGS["kv"]
     B, H, T = kc["batch"], kc["heads"], kc["tokens"]
     extra_rows = [r for r in ("kv_append_minmax", "encode", "encode_minmax") if r in only]
+    act_rows = [r for r in ("act_encode", "act_decode") if r in only]
+    if act_rows:
+        act_rows.append("copy_reference")  # a plain device copy of the same FP16 tensor: the practical HBM ceiling beside the codec
     kv_needed = want("kv_append") or want("kv_attend") or bool(extra_rows) or args.selector_quality
     if kv_needed:
         k, v = W.kv_cache(B, H, T, 128, kc["seeds"][0])
@@ -160,8 +164,20 @@ def main():
         del k, v
     torch.cuda.synchronize()
 
+    # ---- activations for the 2x codec: 32768 tokens x 4096 channels, N(0,1) times a per-channel magnitude ----------
+    if act_rows:
+        act_tokens, act_hidden = 32768, 4096
+        base = torch.from_numpy(W.activation(1024, act_hidden, kc["q_seed"] + 1)).to(dev).float()
+        chan = torch.from_numpy((10.0 ** np.random.default_rng(5).uniform(-1, 1, act_hidden)).astype(np.float32)).to(dev)
+        act_src = (base.repeat(act_tokens // 1024, 1) * chan).to(torch.float16).contiguous()   # 256 MiB of FP16
+        act_groups = act_src.numel() // 64
+        act_blocks = E.ecco_act_encode(act_src)                                                  # 128 MiB
+        act_dst = torch.empty_like(act_src)
+        del base
+    torch.cuda.synchronize()
+
     # ---- the step -----------------------------------------------------------------------------------
-    row_names = [r for r in ("kv_append", "decode", "gemv1", "gemv8", "gemv16", "kv_attend") if want(r)] + extra_rows
+    row_names = [r for r in ("kv_append", "decode", "gemv1", "gemv8", "gemv16", "kv_attend") if want(r)] + extra_rows + act_rows
     counter = [0]
 
     def next_copy(n):
@@ -175,6 +191,12 @@ def main():
         elif row == "kv_append_minmax":
             c = next_copy(kv_copies)
             E.ecco_kv_append_minmax(mk, mv, k_new, v_new, kbs[c], kms[c], vbs[c], vms[c], seq_app, B, H, T)
+        elif row == "act_encode":
+            E.ecco_act_encode(act_src, act_blocks)
+        elif row == "act_decode":
+            E.ecco_act_decode(act_blocks, act_dst)
+        elif row == "copy_reference":
+            act_dst.copy_(act_src)
         elif row == "encode":
             E.ecco_encode(mk, k_dev, enc_blocks, enc_meta)
         elif row == "encode_minmax":
@@ -245,14 +267,14 @@ def main():
         # per-row duration: a graph of one launch per rotating copy of that row's input, replayed
         ms = {}
         for row in row_names:
-            n = 2 if row.startswith("encode") else kv_copies if row.startswith("kv_") else n_copies
+            n = 2 if row.startswith("encode") else 4 if row.startswith("act_") or row == "copy_reference" else kv_copies if row.startswith("kv_") else n_copies
             def one_round(row=row, n=n):
                 for _ in range(n):
                     run_row(row)
             g = capture(one_round)
             g.replay()
             torch.cuda.synchronize()
-            replays = 2 if row.startswith("encode") else max(1, int(np.ceil(max(args.steps, 100) / n)))
+            replays = 2 if row.startswith("encode") else 5 if row.startswith("act_") or row == "copy_reference" else max(1, int(np.ceil(max(args.steps, 100) / n)))
             ms[row] = timed_replays(g, replays) / (replays * n)
             del g
 
@@ -320,6 +342,13 @@ def main():
             d["GBps_compressed"] = comp_bytes / (ms[r] * 1e-3) / 1e9
         elif r.startswith("kv_append"):
             d["groups_per_s"] = 2 * B * H / (ms[r] * 1e-3)
+        elif r == "copy_reference":
+            d["GBps_total_traffic"] = 2 * act_src.numel() * 2 / (ms[r] * 1e-3) / 1e9
+            d["pct_hbm_peak"] = 100.0 * d["GBps_total_traffic"] / HBM_PEAK_GBS
+        elif r.startswith("act_"):
+            d["groups_per_s"] = act_groups / (ms[r] * 1e-3)
+            d["GBps_total_traffic"] = act_groups * 192 / (ms[r] * 1e-3) / 1e9   # 128 B of FP16 + 64 B block per group
+            d["pct_hbm_peak"] = 100.0 * d["GBps_total_traffic"] / HBM_PEAK_GBS
         elif r.startswith("encode"):
             d["groups_per_s"] = B * H * T / (ms[r] * 1e-3)
             d["GBps_fp16_in_plus_blocks_out"] = B * H * T * (256 + BYTES_PER_GROUP) / (ms[r] * 1e-3) / 1e9

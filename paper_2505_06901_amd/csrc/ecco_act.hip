@@ -2,11 +2,12 @@
 // 64-byte block (Section 3.2 "Activation Compression"; the low-ratio decompressor and compressor of
 // Sections 4.2 and 4.3).  Format and rules are stated in include/ecco.h.
 //
-// Both kernels are plain streaming kernels: a lane owns one 16-byte piece of a block (16 values), the
-// four lanes of a quad own one block, and the only cross-lane traffic is inside the quad (DPP): the
-// minimum / maximum of the group on the way in, the scale and the zero point -- gathered from the spare
-// bits of pieces 0 and 1 -- on the way out.  Loads and stores are 16 bytes per lane, consecutive lanes on
-// consecutive addresses for the compressed side, 32 bytes per lane in two 16-byte halves for the FP16 side.
+// Both kernels are plain streaming kernels: a lane owns one 8-byte piece of a block (8 values), eight
+// lanes own one block, and the only cross-lane traffic is among those eight (DPP): the minimum / maximum
+// of the group on the way in, the scale and the zero point -- gathered from the spare bits of pieces
+// 0..3 -- on the way out.  Every load and store instruction covers consecutive addresses with
+// consecutive lanes (8 bytes per lane on the compressed side, 16 on the FP16 side); 16-byte pieces with
+// two half-dense FP16 stores per lane ran at 4.7 instead of 5.6 TB/s.
 // The decoder follows the paper's two-operation scheme: the 7-bit code is placed in the mantissa of an
 // FP16 number with a fixed exponent (a value of 1088 + q, exact), and one packed subtraction plus one
 // packed fused multiply-add give fp16(q * s + z) with a single rounding.
@@ -24,7 +25,7 @@ namespace {
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 
 constexpr int kActThreads = 256;
-constexpr int kPiecesPerBlock = ECCO_BLOCK_BYTES / 16;  // 4 lanes per group
+constexpr int kPiecesPerBlock = ECCO_BLOCK_BYTES / 8;  // 8 lanes per group
 
 template <int kCtrl>
 __device__ __forceinline__ uint32_t quad_dpp(uint32_t v) {
@@ -53,29 +54,27 @@ __device__ __forceinline__ uint32_t dequant_pair(uint32_t d, half2_t s2, half2_t
     return __builtin_bit_cast(uint32_t, __builtin_elementwise_fma(q2, s2, z2));
 }
 
-__global__ __launch_bounds__(kActThreads) void act_decode_kernel(const uint4* __restrict__ blocks, size_t n_pieces,
-                                                                 uint4* __restrict__ dst) {
+__global__ __launch_bounds__(kActThreads) void act_decode_kernel(const uint2* __restrict__ blocks, size_t n_pieces,
+                                                                  uint4* __restrict__ dst) {
     const size_t stride = (size_t)gridDim.x * kActThreads;
-    for (size_t i = (size_t)blockIdx.x * kActThreads + threadIdx.x; i < n_pieces; i += stride) {  // whole quads pass or fail the bound
-        const uint4 w = blocks[i];
-        const uint32_t side = spare_bits(w.x) | (spare_bits(w.y) << 4) | (spare_bits(w.z) << 8) | (spare_bits(w.w) << 12);
-        const uint32_t sb = quad_dpp<0x00>(side), zb = quad_dpp<0x55>(side);  // piece 0: scale, piece 1: zero point
+    for (size_t i = (size_t)blockIdx.x * kActThreads + threadIdx.x; i < n_pieces; i += stride) {  // whole groups of 8 lanes pass or fail
+        const uint2 w = blocks[i];
+        const uint32_t j = (uint32_t)i & 7u;
+        // pieces 0..3 hold the 32 metadata bits, a byte each: OR them over the first quad, then hand them to the second
+        uint32_t side = j < 4u ? (spare_bits(w.x) | (spare_bits(w.y) << 4)) << (8u * j) : 0u;
+        side |= quad_dpp<0xB1>(side);
+        side |= quad_dpp<0x4E>(side);
+        side |= quad_dpp<0x141>(side);  // mirror within 8 lanes
+        const uint32_t sb = side & 0xFFFFu, zb = side >> 16;
         const half2_t s2 = __builtin_bit_cast(half2_t, sb | (sb << 16)), z2 = __builtin_bit_cast(half2_t, zb | (zb << 16));
-        uint4 lo, hi;
-        uint32_t d = w.x ^ 0x40404040u;  // two's complement code -> code + 64
-        lo.x = dequant_pair<0x0C010C00u>(d, s2, z2);
-        lo.y = dequant_pair<0x0C030C02u>(d, s2, z2);
+        uint4 o;
+        uint32_t d = w.x ^ 0x40404040u;
+        o.x = dequant_pair<0x0C010C00u>(d, s2, z2);
+        o.y = dequant_pair<0x0C030C02u>(d, s2, z2);
         d = w.y ^ 0x40404040u;
-        lo.z = dequant_pair<0x0C010C00u>(d, s2, z2);
-        lo.w = dequant_pair<0x0C030C02u>(d, s2, z2);
-        d = w.z ^ 0x40404040u;
-        hi.x = dequant_pair<0x0C010C00u>(d, s2, z2);
-        hi.y = dequant_pair<0x0C030C02u>(d, s2, z2);
-        d = w.w ^ 0x40404040u;
-        hi.z = dequant_pair<0x0C010C00u>(d, s2, z2);
-        hi.w = dequant_pair<0x0C030C02u>(d, s2, z2);
-        dst[2 * i] = lo;
-        dst[2 * i + 1] = hi;
+        o.z = dequant_pair<0x0C010C00u>(d, s2, z2);
+        o.w = dequant_pair<0x0C030C02u>(d, s2, z2);
+        dst[i] = o;
     }
 }
 
@@ -87,36 +86,38 @@ __device__ __forceinline__ uint32_t to_half_bits(float f) {
 }
 
 __global__ __launch_bounds__(kActThreads) void act_encode_kernel(const uint4* __restrict__ src, size_t n_pieces,
-                                                                 uint4* __restrict__ blocks) {
+                                                                 uint2* __restrict__ blocks) {
     const size_t stride = (size_t)gridDim.x * kActThreads;
-    for (size_t i = (size_t)blockIdx.x * kActThreads + threadIdx.x; i < n_pieces; i += stride) {
-        const uint4 a = src[2 * i], b = src[2 * i + 1];
-        float x[16];
-        const uint32_t raw[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+    for (size_t i = (size_t)blockIdx.x * kActThreads + threadIdx.x; i < n_pieces; i += stride) {  // whole groups of 8 lanes pass or fail
+        const uint4 a = src[i];
+        const uint32_t raw[4] = {a.x, a.y, a.z, a.w};
+        float x[8];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
+        for (int k = 0; k < 4; ++k) {
             x[2 * k] = half_lo(raw[k]);
             x[2 * k + 1] = half_hi(raw[k]);
         }
         float lo = x[0], hi = x[0];
 #pragma unroll
-        for (int k = 1; k < 16; ++k) {
+        for (int k = 1; k < 8; ++k) {
             lo = fminf(lo, x[k]);
             hi = fmaxf(hi, x[k]);
         }
-        lo = fminf(lo, quad_dpp<0xB1>(lo));  // quad_perm [1,0,3,2]
+        lo = fminf(lo, quad_dpp<0xB1>(lo));   // quad_perm [1,0,3,2]
         hi = fmaxf(hi, quad_dpp<0xB1>(hi));
-        lo = fminf(lo, quad_dpp<0x4E>(lo));  // quad_perm [2,3,0,1]
+        lo = fminf(lo, quad_dpp<0x4E>(lo));   // quad_perm [2,3,0,1]
         hi = fmaxf(hi, quad_dpp<0x4E>(hi));
+        lo = fminf(lo, quad_dpp<0x141>(lo));  // mirror within 8 lanes
+        hi = fmaxf(hi, quad_dpp<0x141>(hi));
         // s = fp16((max - min) / 127), z = fp16(min + 64 s): every step rounded to FP32 on its own
         const uint32_t sb = to_half_bits(__fdiv_rn(__fsub_rn(hi, lo), 127.0f));
         const float s = half_lo(sb);
         const uint32_t zb = to_half_bits(__fadd_rn(lo, __fmul_rn(64.0f, s)));
         const float z = half_lo(zb);
         const float inv = s == 0.0f ? 0.0f : __fdiv_rn(1.0f, s);
-        float r[16];
+        float r[8];
 #pragma unroll
-        for (int k = 0; k < 16; ++k) {
+        for (int k = 0; k < 8; ++k) {
             // nearest code, ties to even, clamped to -64..63; s = 0: (x - z) * 0 = 0
             r[k] = fminf(fmaxf(rintf(__fmul_rn(__fsub_rn(x[k], z), inv)), -64.0f), 63.0f);
         }
@@ -124,7 +125,7 @@ __global__ __launch_bounds__(kActThreads) void act_encode_kernel(const uint4* __
             // only next to the largest FP16 magnitudes can a code reconstruct to infinity: step towards 0
             const _Float16 sh = __builtin_bit_cast(_Float16, (unsigned short)sb), zh = __builtin_bit_cast(_Float16, (unsigned short)zb);
 #pragma unroll
-            for (int k = 0; k < 16; ++k) {
+            for (int k = 0; k < 8; ++k) {
                 for (int it = 0; it < 2; ++it) {
                     const _Float16 v = __builtin_fmaf16((_Float16)r[k], sh, zh);
                     const bool inf = ((uint32_t)__builtin_bit_cast(unsigned short, v) & 0x7FFFu) == 0x7C00u;
@@ -132,18 +133,18 @@ __global__ __launch_bounds__(kActThreads) void act_encode_kernel(const uint4* __
                 }
             }
         }
-        // piece 0 of the block carries the scale in its spare bits, piece 1 the zero point
-        const uint32_t piece = (uint32_t)i & (kPiecesPerBlock - 1);
-        const uint32_t side = piece == 0 ? sb : piece == 1 ? zb : 0u;
-        uint32_t out[4];
+        // pieces 0..3 of the block carry a byte each of (scale | zero point << 16) in their spare bits
+        const uint32_t j = (uint32_t)i & 7u;
+        const uint32_t side = j < 4u ? ((sb | (zb << 16)) >> (8u * j)) & 0xFFu : 0u;
+        uint32_t out[2];
 #pragma unroll
-        for (int dw = 0; dw < 4; ++dw) {
+        for (int dw = 0; dw < 2; ++dw) {
             uint32_t v = 0;
 #pragma unroll
             for (int k = 0; k < 4; ++k) v = __builtin_amdgcn_cvt_pk_u8_f32(r[4 * dw + k] + 64.0f, k, v);  // code + 64 in 0..127
             out[dw] = (v ^ 0x40404040u) | spread_bits((side >> (4 * dw)) & 0xFu);  // back to two's complement, 7 bits
         }
-        blocks[i] = make_uint4(out[0], out[1], out[2], out[3]);
+        blocks[i] = make_uint2(out[0], out[1]);
     }
 }
 
@@ -165,7 +166,7 @@ int ecco_act_encode(const uint16_t* src, size_t n_groups, void* blocks, void* st
     if (!aligned(src, 16) || !aligned(blocks, 64)) return ECCO_EALIGN;
     const size_t n_pieces = n_groups * kPiecesPerBlock;
     hipLaunchKernelGGL(act_encode_kernel, dim3(act_grid(n_pieces)), dim3(kActThreads), 0, static_cast<hipStream_t>(stream),
-                       reinterpret_cast<const uint4*>(src), n_pieces, static_cast<uint4*>(blocks));
+                       reinterpret_cast<const uint4*>(src), n_pieces, static_cast<uint2*>(blocks));
     ECCO_HIP_CHECK(hipGetLastError());
     return ECCO_OK;
 }
@@ -177,7 +178,7 @@ int ecco_act_decode(const void* blocks, size_t n_groups, uint16_t* dst, void* st
     if (!aligned(blocks, 64) || !aligned(dst, 16)) return ECCO_EALIGN;
     const size_t n_pieces = n_groups * kPiecesPerBlock;
     hipLaunchKernelGGL(act_decode_kernel, dim3(act_grid(n_pieces)), dim3(kActThreads), 0, static_cast<hipStream_t>(stream),
-                       static_cast<const uint4*>(blocks), n_pieces, reinterpret_cast<uint4*>(dst));
+                       static_cast<const uint2*>(blocks), n_pieces, reinterpret_cast<uint4*>(dst));
     ECCO_HIP_CHECK(hipGetLastError());
     return ECCO_OK;
 }
