@@ -699,10 +699,14 @@ void oracle_kv_append_minmax(const uint16_t* ck, const uint8_t* lk, int Sk, cons
 
 // Scaled dot-product attention for one query token per sequence (Section 2.1): scores
 // q.K_t / sqrt(d) over the first seq_len tokens, softmax, weighted sum of V_t.  Double throughout.
-void oracle_kv_attend(const uint16_t* ck, const uint8_t* lk, int Sk, const uint16_t* cv, const uint8_t* lv, int Sv,
-                      const uint16_t* q, const uint8_t* k_blocks, const uint32_t* k_meta,
-                      const uint8_t* v_blocks, const uint32_t* v_meta,
-                      const int32_t* seq_len, int B, int H, int T_max, double* out) {
+//
+// With grouped queries (Section 5.3 "Performance Evaluation": models with grouped-query attention) Hq query heads share Hkv
+// key/value heads: query head h reads the cache of head h / (Hq / Hkv).  Hq = Hkv is the plain case.
+static void attend_heads(const uint16_t* ck, const uint8_t* lk, int Sk, const uint16_t* cv, const uint8_t* lv, int Sv,
+                         const uint16_t* q, const uint8_t* k_blocks, const uint32_t* k_meta,
+                         const uint8_t* v_blocks, const uint32_t* v_meta,
+                         const int32_t* seq_len, int B, int H, int Hkv, int T_max, double* out) {
+    const int per_kv = H / Hkv;  // query heads per key/value head
     std::vector<uint16_t> codes_k((size_t)Sk * K), codes_v((size_t)Sv * K);
     for (int p = 0; p < Sk; ++p) oracle_canonical_codes(lk + p * K, K, codes_k.data() + p * K);
     for (int p = 0; p < Sv; ++p) oracle_canonical_codes(lv + p * K, K, codes_v.data() + p * K);
@@ -718,7 +722,7 @@ void oracle_kv_attend(const uint16_t* ck, const uint8_t* lk, int Sk, const uint1
         double qd[G];
         for (int d = 0; d < G; ++d) qd[d] = (double)oracle_h2f(q[(size_t)bh * G + d]);
         for (int t = 0; t < T; ++t) {
-            size_t g = (size_t)bh * T_max + t;
+            size_t g = ((size_t)b * Hkv + (bh % H) / per_kv) * T_max + t;
             uint8_t idx[G];
             decode_one(lk, codes_k.data(), Sk, k_blocks + g * ORACLE_BLOCK_BYTES, k_meta[g], idx);
             Meta mt = unpack_meta(k_meta[g], Sk);
@@ -732,7 +736,7 @@ void oracle_kv_attend(const uint16_t* ck, const uint8_t* lk, int Sk, const uint1
         double denom = 0.0;
         for (int t = 0; t < T; ++t) { score[(size_t)t] = std::exp(score[(size_t)t] - mx); denom += score[(size_t)t]; }
         for (int t = 0; t < T; ++t) {
-            size_t g = (size_t)bh * T_max + t;
+            size_t g = ((size_t)b * Hkv + (bh % H) / per_kv) * T_max + t;
             uint8_t idx[G];
             decode_one(lv, codes_v.data(), Sv, v_blocks + g * ORACLE_BLOCK_BYTES, v_meta[g], idx);
             Meta mt = unpack_meta(v_meta[g], Sv);
@@ -741,6 +745,20 @@ void oracle_kv_attend(const uint16_t* ck, const uint8_t* lk, int Sk, const uint1
                 o[d] += pt * (double)oracle_h2f(oracle_dequant(cv[mt.pattern * K + idx[d]], mt.scale));
         }
     }
+}
+
+void oracle_kv_attend(const uint16_t* ck, const uint8_t* lk, int Sk, const uint16_t* cv, const uint8_t* lv, int Sv,
+                      const uint16_t* q, const uint8_t* k_blocks, const uint32_t* k_meta,
+                      const uint8_t* v_blocks, const uint32_t* v_meta,
+                      const int32_t* seq_len, int B, int H, int T_max, double* out) {
+    attend_heads(ck, lk, Sk, cv, lv, Sv, q, k_blocks, k_meta, v_blocks, v_meta, seq_len, B, H, H, T_max, out);
+}
+
+void oracle_kv_attend_gqa(const uint16_t* ck, const uint8_t* lk, int Sk, const uint16_t* cv, const uint8_t* lv, int Sv,
+                          const uint16_t* q, const uint8_t* k_blocks, const uint32_t* k_meta,
+                          const uint8_t* v_blocks, const uint32_t* v_meta,
+                          const int32_t* seq_len, int B, int Hq, int Hkv, int T_max, double* out) {
+    attend_heads(ck, lk, Sk, cv, lv, Sv, q, k_blocks, k_meta, v_blocks, v_meta, seq_len, B, Hq, Hkv, T_max, out);
 }
 
 // ------------------------------------------------------------------------------------------

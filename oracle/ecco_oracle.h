@@ -115,6 +115,13 @@ void oracle_kv_attend(const uint16_t* ck, const uint8_t* lk, int Sk, const uint1
                       const uint8_t* v_blocks, const uint32_t* v_meta,
                       const int32_t* seq_len, int B, int H, int T_max, double* out);
 
+/* grouped-query form: q and out [B][Hq][128], caches [B][Hkv][T_max]; query head h uses cache head h / (Hq / Hkv);
+ * Hq must be a multiple of Hkv */
+void oracle_kv_attend_gqa(const uint16_t* ck, const uint8_t* lk, int Sk, const uint16_t* cv, const uint8_t* lv, int Sv,
+                          const uint16_t* q, const uint8_t* k_blocks, const uint32_t* k_meta,
+                          const uint8_t* v_blocks, const uint32_t* v_meta,
+                          const int32_t* seq_len, int B, int Hq, int Hkv, int T_max, double* out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -235,6 +235,22 @@ def kv_attend(ck, lk, cv, lv, q, k_blocks, k_meta, v_blocks, v_meta, seq_len, B,
     return out
 
 
+def kv_attend_gqa(ck, lk, cv, lv, q, k_blocks, k_meta, v_blocks, v_meta, seq_len, B, Hq, Hkv, T_max):
+    assert Hq % Hkv == 0
+    ck, cv = _c(ck, np.uint16), _c(cv, np.uint16)
+    lk, lv = _c(lk, np.uint8), _c(lv, np.uint8)
+    q = _c(q, np.uint16)
+    seq_len = _c(seq_len, np.int32)
+    k_blocks, v_blocks = _c(k_blocks, np.uint8), _c(v_blocks, np.uint8)
+    k_meta, v_meta = _c(k_meta, np.uint32), _c(v_meta, np.uint32)
+    assert q.size == B * Hq * GROUP and k_meta.size == B * Hkv * T_max == v_meta.size
+    out = np.zeros((B, Hq, GROUP), np.float64)
+    lib().oracle_kv_attend_gqa(_p(ck), _p(lk), C.c_int(ck.size // K), _p(cv), _p(lv), C.c_int(cv.size // K),
+                               _p(q), _p(k_blocks), _p(k_meta), _p(v_blocks), _p(v_meta), _p(seq_len),
+                               C.c_int(B), C.c_int(Hq), C.c_int(Hkv), C.c_int(T_max), _p(out))
+    return out
+
+
 ACT_GROUP = 64
 
 

@@ -756,3 +756,36 @@ def test_act_roundtrip_bound_and_degenerate_groups(oracle):
     q8, s8, z8 = _act_unpack(blocks[8])
     assert (s8, z8) == (0x6408, 0x6040)                    # 1032 and 544: code 63 would give 65560, beyond 65504
     assert oracle.act_dequant(63, s8, z8) == 0x7C00 and max(q8) == 62 and q8[0] == 62 and q8[1] == -64
+
+
+# --------------------------------------------------------------------------------------------
+# grouped-query attention: query head h reads the cache of head h / (Hq / Hkv)
+def test_gqa_attend_reduces_to_textbook_attention(oracle, tiny):
+    from paper_2505_06901_amd import workloads as W
+    cent, lens = tiny["cent"], tiny["lens"]
+    B, Hkv, grp, T = 2, 3, 4, 7
+    Hq = Hkv * grp
+    k, v = W.kv_cache(B, Hkv, T, 128, seed=19)
+    kb, km = oracle.encode(cent, lens, k.view(np.uint16))
+    vb, vm = oracle.encode(cent, lens, v.view(np.uint16))
+    q = W.activation(B * Hq, 128, 7).reshape(B, Hq, 128)
+    seq = np.array([T, 3], np.int32)
+    o = oracle.kv_attend_gqa(cent, lens, cent, lens, q.view(np.uint16), kb, km, vb, vm, seq, B, Hq, Hkv, T)
+    # numpy softmax attention on the decoded tensors, every query head paired with its cache head by hand
+    kdec = oracle.decode(cent, lens, kb, km).view(np.float16).astype(np.float64).reshape(B, Hkv, T, 128)
+    vdec = oracle.decode(cent, lens, vb, vm).view(np.float16).astype(np.float64).reshape(B, Hkv, T, 128)
+    for b in range(B):
+        for h in range(Hq):
+            kk, vv = kdec[b, h // grp, : seq[b]], vdec[b, h // grp, : seq[b]]
+            sc = kk @ q[b, h].astype(np.float64) / np.sqrt(128.0)
+            pr = np.exp(sc - sc.max()); pr /= pr.sum()
+            assert np.allclose(o[b, h], pr @ vv, rtol=1e-12, atol=1e-14), (b, h)
+    # the same through the plain routine on caches with every key/value head written out grp times
+    rep = lambda a, shape: np.repeat(a.reshape(shape), grp, axis=1)
+    o2 = oracle.kv_attend(cent, lens, cent, lens, q.view(np.uint16), rep(kb, (B, Hkv, T, 64)), rep(km, (B, Hkv, T)),
+                          rep(vb, (B, Hkv, T, 64)), rep(vm, (B, Hkv, T)), seq, B, Hq, T)
+    assert np.array_equal(o, o2)
+    # one query head per cache head is the plain case
+    q1 = np.ascontiguousarray(q[:, :Hkv])
+    assert np.array_equal(oracle.kv_attend_gqa(cent, lens, cent, lens, q1.view(np.uint16), kb, km, vb, vm, seq, B, Hkv, Hkv, T),
+                          oracle.kv_attend(cent, lens, cent, lens, q1.view(np.uint16), kb, km, vb, vm, seq, B, Hkv, T))
