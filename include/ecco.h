@@ -191,6 +191,25 @@ int ecco_kv_attend(const ecco_model* mk, const ecco_model* mv, const uint16_t* q
                    const void* k_blocks, const uint32_t* k_meta, const void* v_blocks, const uint32_t* v_meta,
                    const int32_t* seq_len, int B, int H, int T_max, float* out, void* stream);
 
+/* Grouped-query form of ecco_kv_attend, split over the tokens (Section 5.3: with grouped-query attention several
+ * query heads share one key/value head and the matrix-vector products become small matrix products).
+ *   q, out      device, [B][Hq][128] (FP16, 16-byte aligned / FP32);  caches  [B][Hkv][T_max] blocks and meta words
+ *   Hq % Hkv == 0, Hq / Hkv <= 16; query head h reads the cache of head h / (Hq / Hkv).
+ *   n_splits    1..256: each (sequence, key/value head) is cut into n_splits token ranges handled by separate
+ *               workgroups (use it when B * Hkv is well below the number of compute units);  with n_splits > 1
+ *               `workspace` (device, 16-byte aligned, ecco_kv_attend_gqa_workspace(B, Hq, n_splits) bytes, owned by the
+ *               caller, contents irrelevant before and after) receives the partial results and a second small kernel
+ *               merges them;  with n_splits == 1 workspace may be null.
+ * Every K and V block is decoded once for all query heads of its group; products run on the matrix cores with the
+ * probabilities rounded to FP16 (the denominator sums the rounded values).  Slots of the cache at or behind seq_len
+ * may be uninitialised.  Calls that share a workspace must not overlap.
+ * Errors: EINVAL, ESHAPE (sizes, Hq % Hkv, group > 16, n_splits), EALIGN, EHIP. */
+size_t ecco_kv_attend_gqa_workspace(int B, int Hq, int n_splits);
+int ecco_kv_attend_gqa(const ecco_model* mk, const ecco_model* mv, const uint16_t* q,
+                       const void* k_blocks, const uint32_t* k_meta, const void* v_blocks, const uint32_t* v_meta,
+                       const int32_t* seq_len, int B, int Hq, int Hkv, int T_max, int n_splits, void* workspace,
+                       float* out, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

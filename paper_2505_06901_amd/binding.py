@@ -20,6 +20,7 @@ EXPORTS = [
     "ecco_model_S", "ecco_model_centroids", "ecco_model_code_lens", "ecco_model_to_device", "ecco_model_free",
     "ecco_encode", "ecco_decode", "ecco_decode_indices", "ecco_decode_gemv", "ecco_kv_append", "ecco_kv_attend",
     "ecco_encode_minmax", "ecco_kv_append_minmax", "ecco_act_encode", "ecco_act_decode",
+    "ecco_kv_attend_gqa", "ecco_kv_attend_gqa_workspace",
 ]
 
 
@@ -57,6 +58,9 @@ def lib():
         L.ecco_kv_append_minmax.argtypes = [vp] * 9 + [i32, i32, i32, vp]
         L.ecco_kv_attend.argtypes = [vp] * 8 + [i32, i32, i32, vp, vp]
         L.ecco_act_encode.argtypes = [vp, sz, vp, vp]
+        L.ecco_kv_attend_gqa.argtypes = [vp] * 8 + [i32, i32, i32, i32, i32, vp, vp, vp]
+        L.ecco_kv_attend_gqa_workspace.argtypes = [i32, i32, i32]
+        L.ecco_kv_attend_gqa_workspace.restype = sz
         L.ecco_act_decode.argtypes = [vp, sz, vp, vp]
         _lib = L
     return _lib
@@ -225,6 +229,20 @@ def ecco_kv_attend(mk: Model, mv: Model, q, k_blocks, k_meta, v_blocks, v_meta, 
         out = torch.empty((B, H, GROUP), dtype=torch.float32, device=q.device)
     _check(lib().ecco_kv_attend(mk.handle, mv.handle, _dp(q), _dp(k_blocks), _dp(k_meta), _dp(v_blocks), _dp(v_meta),
                                 _dp(seq_len), B, H, T_max, _dp(out), _stream()), "ecco_kv_attend")
+    return out
+
+
+def ecco_kv_attend_gqa(mk: Model, mv: Model, q, k_blocks, k_meta, v_blocks, v_meta, seq_len, B, Hq, Hkv, T_max,
+                       n_splits: int = 1, workspace=None, out=None):
+    """q [B, Hq, 128] FP16; caches [B, Hkv, T_max]; workspace: uint8/float tensor of ecco_kv_attend_gqa_workspace bytes."""
+    import torch
+    if out is None:
+        out = torch.empty((B, Hq, GROUP), dtype=torch.float32, device=q.device)
+    if n_splits > 1 and workspace is None:
+        workspace = torch.empty((int(lib().ecco_kv_attend_gqa_workspace(B, Hq, n_splits)),), dtype=torch.uint8, device=q.device)
+    _check(lib().ecco_kv_attend_gqa(mk.handle, mv.handle, _dp(q), _dp(k_blocks), _dp(k_meta), _dp(v_blocks), _dp(v_meta),
+                                    _dp(seq_len), B, Hq, Hkv, T_max, n_splits, _dp(workspace), _dp(out), _stream()),
+           "ecco_kv_attend_gqa")
     return out
 
 

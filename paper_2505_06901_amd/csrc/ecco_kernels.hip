@@ -973,7 +973,9 @@ __global__ __launch_bounds__(kLongV ? 512 : kAttnThreads) void kv_attend_kernel(
             if (u < units) pre = load_unit(v_blocks, v_meta, bh, T_max, unit0 + u, lane);
             for (; u < units; u += waves) {
                 store_unit(wbuf, pre, lane);
-                const uint32_t mw = pre.meta;
+                // a slot past the sequence end may hold anything (the cache behind seq_len need not be initialised):
+                // its scale is taken as 0, so that its values are zeros and not, say, NaN times a zero weight
+                const uint32_t mw = (u * kUnitBlocks + blk < span) ? pre.meta : (pre.meta & 0xFFFF0000u);
                 if (u + waves < units) pre = load_unit(v_blocks, v_meta, bh, T_max, unit0 + u + waves, lane);
                 const Lane L = lane_setup(TV, mw, Sv);
                 const _Float16 sh = __builtin_bit_cast(_Float16, (unsigned short)(mw & 0xFFFFu));
@@ -1014,6 +1016,266 @@ __global__ __launch_bounds__(kLongV ? 512 : kAttnThreads) void kv_attend_kernel(
         }
     }
     if (tid < kGroup) out[(size_t)bh * kGroup + tid] = T > 0 ? my_out / run_den : 0.0f;
+}
+
+// ---- grouped-query attention over compressed K / V, split over the tokens ---------------------------------
+// Several query heads share one key/value head (Section 5.3: with grouped-query attention the batched
+// matrix-vector products become small matrix products).  One workgroup of 8 wavefronts per (sequence,
+// key/value head, token split) decodes every K and V block of its token range once and serves all
+// grp = Hq / Hkv query heads of the group with it, on the matrix cores:
+//   scores  S[token][head] = sum_dim K[token][dim] q[head][dim]:  v_mfma_f32_32x32x16_f16 with the 32 tokens
+//           of a unit as rows; lane l decodes chain l / 32 of token l % 32, which is exactly the A layout (row
+//           l % 32, eight consecutive k per lane, k group l / 32) once the 16 k of a step are taken to be
+//           dimensions 8j..8j+7 of chain 0 and of chain 1; B holds the queries (head l % 32, zero past grp).
+//   output  O[dim][head] = sum_token V[token][dim] P[head][token]: here the reduction runs over the tokens, so the
+//           decoded values have to be turned: every 16 values the wavefront writes a 32 dims x 32 tokens FP16 tile
+//           to its private LDS buffer (neighbouring lanes first swap halves so that each writes two tokens of one
+//           dimension), reads it back as A operands (row = dimension, eight tokens per lane) and multiplies with
+//           the FP16 probabilities; the four 32 x 32 accumulator tiles (64 registers) live across the spans.
+// The sequence is walked in spans; per span the scores go to LDS, each head's running maximum and
+// denominator are updated (one wavefront per head), the accumulators of a lane -- all of one head -- are
+// rescaled, and the probabilities are stored as FP16 (the denominator sums the rounded values).  With one
+// split the result is normalised and written; otherwise (maximum, denominator, unnormalised output) of the
+// split go to the caller's workspace and kv_attend_combine_kernel merges the splits.
+constexpr int kGqaThreads = 512;
+constexpr int kGqaWaves = kGqaThreads / 64;
+constexpr int kGqaMaxGroup = 16;
+constexpr int kTileStride = 20;                 // words per row of the transposition tile: 32 tokens (16 words) + 4 of padding
+constexpr int kTileWords = 32 * kTileStride;
+constexpr int kGqaSpanBudget = 7680;            // query heads x tokens of a span kept in LDS (FP32 scores + FP16 probabilities)
+typedef float float16_t __attribute__((ext_vector_type(16)));
+
+__host__ __device__ constexpr int gqa_span(int grp) { return (kGqaSpanBudget / grp) & ~(kUnitBlocks - 1); }
+__host__ __device__ constexpr int gqa_score_stride(int span) { return span + 1; }   // words; odd, so that heads fall on different banks
+__host__ __device__ constexpr int gqa_prob_stride(int span) { return span + 8; }    // halves; rows stay 16-byte aligned
+// LDS words of the span's scores (FP32, rounded up to a 16-byte boundary) and probabilities (FP16); the same region
+// holds the cross-wavefront sum of one accumulator tile at the end
+__host__ __device__ constexpr int gqa_score_words(int grp, int span) { return (grp * gqa_score_stride(span) + 3) & ~3; }
+__host__ __device__ constexpr int gqa_shared_words(int grp, int span) {
+    const int a = gqa_score_words(grp, span) + (grp * gqa_prob_stride(span) + 1) / 2, b = kGqaWaves * 16 * 64;
+    return a > b ? a : b;
+}
+constexpr int kGqaStateWords = 64;  // running maximum, denominator and rescale factor per query head
+inline size_t gqa_lds_bytes(int Sk, int Sv, int grp) {
+    return (table_words(std::max(Sk, Sv)) + (size_t)kGqaWaves * (kUnitWords + kTileWords) + kGqaStateWords +
+            gqa_shared_words(grp, gqa_span(grp))) * 4;
+}
+
+template <bool kLongK, bool kLongV>
+__global__ __launch_bounds__(kGqaThreads) void kv_attend_gqa_kernel(const uint32_t* __restrict__ dev_k, int Sk,
+                                                                    const uint32_t* __restrict__ dev_v, int Sv,
+                                                                    const uint16_t* __restrict__ q,
+                                                                    const uint4* __restrict__ k_blocks, const uint32_t* __restrict__ k_meta,
+                                                                    const uint4* __restrict__ v_blocks, const uint32_t* __restrict__ v_meta,
+                                                                    const int32_t* __restrict__ seq_len, int Hq, int Hkv, int T_max,
+                                                                    float* __restrict__ out, float* __restrict__ ws) {
+    extern __shared__ __align__(16) uint32_t smem[];
+    const int Smax = max(Sk, Sv);
+    const int grp = Hq / Hkv, span_max = gqa_span(grp);
+    const int sstride = gqa_score_stride(span_max), pstride = gqa_prob_stride(span_max);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    uint32_t* wbuf = smem + table_words(Smax) + wave * kUnitWords;
+    uint32_t* tile = smem + table_words(Smax) + kGqaWaves * kUnitWords + wave * kTileWords;
+    float* st_max = reinterpret_cast<float*>(smem + table_words(Smax) + kGqaWaves * (kUnitWords + kTileWords));
+    float* st_den = st_max + kGqaMaxGroup;
+    float* st_alpha = st_den + kGqaMaxGroup;
+    uint32_t* shared0 = smem + table_words(Smax) + kGqaWaves * (kUnitWords + kTileWords) + kGqaStateWords;
+    float* scores = reinterpret_cast<float*>(shared0);                                             // [grp][sstride]
+    _Float16* probs = reinterpret_cast<_Float16*>(shared0 + gqa_score_words(grp, span_max));       // [grp][pstride]
+    float* red = reinterpret_cast<float*>(shared0);                                                // [wavefront][16][64], after the last span
+    if (lane < kUnitBlocks) wbuf[lane * kStride + kBlockWords] = 0u;
+    if (lane == 0) wbuf[kUnitBlocks * kStride] = 0u;
+    if (tid < kGqaMaxGroup) {
+        st_max[tid] = -INFINITY;
+        st_den[tid] = 0.0f;
+        st_alpha[tid] = 1.0f;
+    }
+
+    const int bkv = blockIdx.x, b = bkv / Hkv, hkv = bkv - b * Hkv;
+    const int n_splits = gridDim.y, split = blockIdx.y;
+    const int T = max(0, min(seq_len[b], T_max));
+    const int units_total = (T + kUnitBlocks - 1) / kUnitBlocks;
+    const int units_per_split = (units_total + n_splits - 1) / n_splits;
+    const int t_begin = min(T, split * units_per_split * kUnitBlocks), t_end = min(T, (split + 1) * units_per_split * kUnitBlocks);
+    const int blk = lane & (kUnitBlocks - 1), half = lane >> 5;   // token of the unit and chain of this lane; also MFMA row / column and k group
+    const bool head_ok = blk < grp;
+    const size_t q_row = ((size_t)b * Hq + (size_t)hkv * grp + (head_ok ? blk : 0)) * kGroup;
+    const float inv_sqrt_d = 0.08838834764831845f;  // 1 / sqrt(128)
+    const uint32_t swap_sel = (lane & 1) ? 0x03020706u : 0x05040100u;  // odd lanes keep the high halves, even lanes the low halves
+    float16_t o[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[j][i] = 0.0f;
+
+    for (int s0 = t_begin; s0 < t_end; s0 += span_max) {
+        const int span = min(span_max, t_end - s0);
+        const int units = (span + kUnitBlocks - 1) / kUnitBlocks, unit0 = s0 / kUnitBlocks;  // s0 is a multiple of 32
+        // ---- scores of the span, all query heads of the group
+        __syncthreads();
+        const Tables TK = stage_tables(smem, dev_k, Sk);
+        __syncthreads();
+        {
+            uint4 bq[kHalf / 8];  // B operands: the query of head blk, dimensions 64 * half + 8j .. + 7
+            const uint4* qsrc = reinterpret_cast<const uint4*>(q + q_row + half * kHalf);
+            asm volatile("" : "+v"(qsrc));  // reloaded per span rather than kept alive across the V phase
+#pragma unroll
+            for (int j = 0; j < kHalf / 8; ++j) bq[j] = head_ok ? qsrc[j] : make_uint4(0u, 0u, 0u, 0u);
+            int u = wave;
+            UnitLoad pre;
+            if (u < units) pre = load_unit(k_blocks, k_meta, bkv, T_max, unit0 + u, lane);
+            for (; u < units; u += kGqaWaves) {
+                store_unit(wbuf, pre, lane);
+                const uint32_t mw = pre.meta;
+                if (u + kGqaWaves < units) pre = load_unit(k_blocks, k_meta, bkv, T_max, unit0 + u + kGqaWaves, lane);
+                const Lane L = lane_setup(TK, mw, Sk);
+                const _Float16 sh = __builtin_bit_cast(_Float16, (unsigned short)(mw & 0xFFFFu));
+                const half2_t s2 = {sh, sh};
+                uint32_t pk[4];
+                float16_t acc;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[i] = 0.0f;
+                decode_chain<kLongK, kHalf>(wbuf + blk * kStride, half ? L.second_start : 0u, L, [&](int i, uint32_t e) {
+                    if ((i & 1) == 0) {
+                        pk[(i >> 1) & 3] = e >> 16;
+                        return;
+                    }
+                    pk[(i >> 1) & 3] = __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2_t, pk[(i >> 1) & 3] | (e & 0xFFFF0000u)) * s2);
+                    if ((i & 7) != 7) return;
+                    const uint4 av = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8_t, av), __builtin_bit_cast(half8_t, bq[i >> 3]), acc, 0, 0, 0);
+                });
+                // accumulator layout of the 32 x 32 tile: register i of lane l is row 8 * (i / 4) + 4 * (l / 32) + i % 4, column l % 32
+                if (head_ok) {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int t = u * kUnitBlocks + 8 * (i >> 2) + 4 * half + (i & 3);
+                        scores[blk * sstride + t] = t < span ? acc[i] * inv_sqrt_d : -INFINITY;
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        // ---- running softmax, one wavefront per query head
+        for (int g = wave; g < grp; g += kGqaWaves) {
+            const int n = units * kUnitBlocks;
+            float mx = -INFINITY;
+            for (int t = lane; t < n; t += 64) mx = fmaxf(mx, scores[g * sstride + t]);
+            mx = wave_all(mx, [](float a, float c) { return fmaxf(a, c); });
+            const float old_max = st_max[g], new_max = fmaxf(old_max, mx);
+            float den = 0.0f;
+            for (int t = lane; t < n; t += 64) {
+                const _Float16 ph = (_Float16)__expf(scores[g * sstride + t] - new_max);  // 0 for the tokens past the span
+                probs[g * pstride + t] = ph;
+                den += (float)ph;
+            }
+            den = wave_sum(den);
+            if (lane == 0) {
+                const float alpha = (old_max == -INFINITY) ? 0.0f : __expf(old_max - new_max);
+                st_alpha[g] = alpha;
+                st_den[g] = st_den[g] * alpha + den;
+                st_max[g] = new_max;
+            }
+        }
+        // ---- weighted sum of V over the span
+        __syncthreads();
+        const Tables TV = stage_tables(smem, dev_v, Sv);
+        __syncthreads();
+        {
+            const float alpha = head_ok ? st_alpha[blk] : 1.0f;  // every accumulator of a lane belongs to head l % 32
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) o[j][i] *= alpha;
+            int u = wave;
+            UnitLoad pre;
+            if (u < units) pre = load_unit(v_blocks, v_meta, bkv, T_max, unit0 + u, lane);
+            for (; u < units; u += kGqaWaves) {
+                store_unit(wbuf, pre, lane);
+                // a slot past the range may hold anything: scale 0, so that its values are zeros (NaN * 0 would poison the sum)
+                const uint32_t mw = (u * kUnitBlocks + blk < span) ? pre.meta : (pre.meta & 0xFFFF0000u);
+                if (u + kGqaWaves < units) pre = load_unit(v_blocks, v_meta, bkv, T_max, unit0 + u + kGqaWaves, lane);
+                const Lane L = lane_setup(TV, mw, Sv);
+                const _Float16 sh = __builtin_bit_cast(_Float16, (unsigned short)(mw & 0xFFFFu));
+                const half2_t s2 = {sh, sh};
+                // B operands: probabilities of head blk for tokens 16 ks + 8 * half .. + 7 of the unit
+                uint4 pb[2];
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks)
+                    pb[ks] = head_ok ? *reinterpret_cast<const uint4*>(probs + blk * pstride + u * kUnitBlocks + 16 * ks + 8 * half)
+                                     : make_uint4(0u, 0u, 0u, 0u);
+                uint32_t pk[8];
+                decode_chain<kLongV, kHalf>(wbuf + blk * kStride, half ? L.second_start : 0u, L, [&](int i, uint32_t e) {
+                    if ((i & 1) == 0) {
+                        pk[(i >> 1) & 7] = e >> 16;
+                        return;
+                    }
+                    pk[(i >> 1) & 7] = __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2_t, pk[(i >> 1) & 7] | (e & 0xFFFF0000u)) * s2);
+                    if ((i & 15) != 15) return;
+                    // 16 values of this lane's token -> rows 16 * half + r of the tile (dimension 64 * half + 16 * (i / 16) + r);
+                    // an even lane takes dimension 2 r2 of its own and its neighbour's token, the odd neighbour dimension 2 r2 + 1
+                    wave_lds_fence();
+#pragma unroll
+                    for (int r2 = 0; r2 < 8; ++r2) {
+                        const uint32_t other = (uint32_t)__builtin_amdgcn_mov_dpp((int)pk[r2], 0xB1, 0xF, 0xF, true);  // quad_perm [1,0,3,2]
+                        tile[(16 * half + 2 * r2 + (lane & 1)) * kTileStride + (blk >> 1)] = __builtin_amdgcn_perm(other, pk[r2], swap_sel);
+                    }
+                    wave_lds_fence();
+                    const uint4 a0 = *reinterpret_cast<const uint4*>(tile + blk * kTileStride + 4 * half);
+                    const uint4 a1 = *reinterpret_cast<const uint4*>(tile + blk * kTileStride + 8 + 4 * half);
+                    o[i >> 4] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8_t, a0), __builtin_bit_cast(half8_t, pb[0]), o[i >> 4], 0, 0, 0);
+                    o[i >> 4] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8_t, a1), __builtin_bit_cast(half8_t, pb[1]), o[i >> 4], 0, 0, 0);
+                });
+            }
+        }
+    }
+    // ---- sum over the wavefronts, one accumulator tile at a time; tile j row m is dimension 64 * (m / 16) + 16 j + m % 16
+    const size_t part = ((size_t)b * Hq + (size_t)hkv * grp) * n_splits;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 16; ++i) red[(wave * 16 + i) * 64 + lane] = o[j][i];
+        __syncthreads();
+        for (int e = tid; e < 16 * 64; e += kGqaThreads) {
+            float sum = 0.0f;
+            for (int w = 0; w < kGqaWaves; ++w) sum += red[w * 16 * 64 + e];
+            const int i = e >> 6, ln = e & 63, head = ln & 31;
+            if (head >= grp) continue;
+            const int m = 8 * (i >> 2) + 4 * (ln >> 5) + (i & 3);
+            const int dim = 64 * (m >> 4) + 16 * j + (m & 15);
+            if (n_splits == 1) {
+                const float den = st_den[head];
+                out[((size_t)b * Hq + (size_t)hkv * grp + head) * kGroup + dim] = den > 0.0f ? sum / den : 0.0f;
+            } else {
+                ws[((part + (size_t)head * n_splits) + split) * kGroup + dim] = sum;
+            }
+        }
+    }
+    if (n_splits > 1 && tid < grp) {
+        // behind the partial outputs: [B * Hq][n_splits][2] = (maximum, denominator)
+        float* ml = ws + (size_t)gridDim.x / Hkv * Hq * n_splits * kGroup;
+        const size_t at = (part + (size_t)tid * n_splits + split) * 2;
+        ml[at] = st_max[tid];
+        ml[at + 1] = st_den[tid];
+    }
+}
+
+// merges the token splits of one (sequence, query head): grid B * Hq, 128 threads
+__global__ __launch_bounds__(kGroup) void kv_attend_combine_kernel(const float* __restrict__ ws, int n_heads, int n_splits, float* __restrict__ out) {
+    const size_t bh = blockIdx.x;
+    const float* ml = ws + (size_t)n_heads * n_splits * kGroup + bh * n_splits * 2;
+    float mx = -INFINITY;
+    for (int s = 0; s < n_splits; ++s) mx = fmaxf(mx, ml[2 * s]);
+    float num = 0.0f, den = 0.0f;
+    for (int s = 0; s < n_splits; ++s) {
+        if (ml[2 * s] == -INFINITY) continue;  // an empty split
+        const float w = __expf(ml[2 * s] - mx);
+        num += w * ws[(bh * n_splits + s) * kGroup + threadIdx.x];
+        den += w * ml[2 * s + 1];
+    }
+    out[bh * kGroup + threadIdx.x] = den > 0.0f ? num / den : 0.0f;
 }
 
 // ---- host side -----------------------------------------------------------------------------------------
@@ -1167,6 +1429,41 @@ int ecco_kv_append_minmax(const ecco_model* mk, const ecco_model* mv, const uint
                           void* k_blocks, uint32_t* k_meta, void* v_blocks, uint32_t* v_meta,
                           const int32_t* seq_len, int B, int H, int T_max, void* stream) {
     return kv_append_common(true, mk, mv, k_new, v_new, k_blocks, k_meta, v_blocks, v_meta, seq_len, B, H, T_max, stream);
+}
+
+size_t ecco_kv_attend_gqa_workspace(int B, int Hq, int n_splits) {
+    if (B <= 0 || Hq <= 0 || n_splits <= 1) return 0;
+    return (size_t)B * Hq * n_splits * (kGroup + 2) * sizeof(float);
+}
+
+int ecco_kv_attend_gqa(const ecco_model* mk, const ecco_model* mv, const uint16_t* q,
+                       const void* k_blocks, const uint32_t* k_meta, const void* v_blocks, const uint32_t* v_meta,
+                       const int32_t* seq_len, int B, int Hq, int Hkv, int T_max, int n_splits, void* workspace,
+                       float* out, void* stream) {
+    if (!q || !k_blocks || !k_meta || !v_blocks || !v_meta || !seq_len || !out) return ECCO_EINVAL;
+    if (model_ready(mk) != ECCO_OK || model_ready(mv) != ECCO_OK || mk->device != mv->device) return ECCO_EINVAL;
+    if (B <= 0 || Hq <= 0 || Hkv <= 0 || T_max <= 0 || Hq % Hkv != 0 || Hq / Hkv > kGqaMaxGroup) return ECCO_ESHAPE;
+    if (n_splits < 1 || n_splits > 256 || (long long)B * Hkv > 0x7FFFFFFF) return ECCO_ESHAPE;
+    if (n_splits > 1 && !workspace) return ECCO_EINVAL;
+    if (!aligned(k_blocks, 64) || !aligned(v_blocks, 64) || !aligned(q, 16) || !aligned(out, 4) || !aligned(workspace, 16)) return ECCO_EALIGN;
+    const size_t lds = gqa_lds_bytes(mk->S, mv->S, Hq / Hkv);
+    const bool lk = mk->max_len > kPeekBits, lv = mv->max_len > kPeekBits;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    auto launch = [&](auto kernel) -> int {
+        int rc = allow_lds(kernel, lds);
+        if (rc != ECCO_OK) return rc;
+        hipLaunchKernelGGL(kernel, dim3(B * Hkv, n_splits), dim3(kGqaThreads), lds, st, mk->dev, mk->S, mv->dev, mv->S, q,
+                           static_cast<const uint4*>(k_blocks), k_meta, static_cast<const uint4*>(v_blocks), v_meta, seq_len,
+                           Hq, Hkv, T_max, out, static_cast<float*>(workspace));
+        ECCO_HIP_CHECK(hipGetLastError());
+        return ECCO_OK;
+    };
+    const int rc = lk ? (lv ? launch(kv_attend_gqa_kernel<true, true>) : launch(kv_attend_gqa_kernel<true, false>))
+                      : (lv ? launch(kv_attend_gqa_kernel<false, true>) : launch(kv_attend_gqa_kernel<false, false>));
+    if (rc != ECCO_OK || n_splits == 1) return rc;
+    hipLaunchKernelGGL(kv_attend_combine_kernel, dim3(B * Hq), dim3(kGroup), 0, st, static_cast<const float*>(workspace), B * Hq, n_splits, out);
+    ECCO_HIP_CHECK(hipGetLastError());
+    return ECCO_OK;
 }
 
 int ecco_kv_attend(const ecco_model* mk, const ecco_model* mv, const uint16_t* q,

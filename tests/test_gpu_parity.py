@@ -376,6 +376,57 @@ def test_kv_attend_matches_oracle(dev, oracle):
     assert np.allclose(out[1], vdec[1, :, 0].astype(np.float64), rtol=1e-6, atol=1e-9)
 
 
+def test_attend_ignores_cache_behind_seq_len(dev, oracle):
+    """Slots at or behind seq_len may hold anything, NaN scales included: both attention kernels must not read them into the result."""
+    B, H, T = 2, 2, 100
+    k, v, mk, mv = _kv_setup(dev, oracle, B, H, T, 8)
+    kb, km = E.ecco_encode(mk, t16(k, dev)); vb, vm = E.ecco_encode(mv, t16(v, dev))
+    seq = np.array([70, 33], np.int32)
+    q = W.activation(B * H, 128, 105).reshape(B, H, 128)
+    want = oracle.kv_attend(mk.centroids, mk.code_lens, mv.centroids, mv.code_lens, q.view(np.uint16),
+                            np_blocks(kb), np_meta(km), np_blocks(vb), np_meta(vm), seq, B, H, T)
+    kb, vb = kb.view(B, H, T, 64), vb.view(B, H, T, 64)
+    km, vm = km.view(B, H, T), vm.view(B, H, T)
+    for b in range(B):
+        for a in (kb, vb):
+            a[b, :, seq[b]:] = 0xFF
+        for a in (km, vm):
+            a[b, :, seq[b]:] = -1          # every bit set: scale bits 0xFFFF (a NaN), pattern 63, raw flag
+    out = E.ecco_kv_attend(mk, mv, t16(q, dev), kb, km, vb, vm, ti32(seq, dev), B, H, T).cpu().numpy()
+    assert np.isfinite(out).all() and rel_l2(out, want) <= REL_L2
+    out = E.ecco_kv_attend_gqa(mk, mv, t16(q, dev), kb, km, vb, vm, ti32(seq, dev), B, H, H, T, n_splits=3).cpu().numpy()
+    assert np.isfinite(out).all() and rel_l2(out, want) <= REL_L2
+
+
+@pytest.mark.parametrize("grp,n_splits", [(1, 1), (4, 1), (8, 3), (16, 2), (3, 5)])
+def test_kv_attend_gqa_matches_oracle(dev, oracle, grp, n_splits):
+    B, Hkv, T = 3, 2, 1500 if grp >= 8 else 700   # several spans for the larger groups (span = 7680 / group tokens), ragged tails
+    Hq = Hkv * grp
+    k, v, mk, mv = _kv_setup(dev, oracle, B, Hkv, T, 16)
+    kb, km = E.ecco_encode(mk, t16(k, dev)); vb, vm = E.ecco_encode(mv, t16(v, dev))
+    q = W.activation(B * Hq, 128, 106).reshape(B, Hq, 128)
+    seq = np.array([T, 0, 333], np.int32)
+    out = E.ecco_kv_attend_gqa(mk, mv, t16(q, dev), kb, km, vb, vm, ti32(seq, dev), B, Hq, Hkv, T, n_splits=n_splits).cpu().numpy()
+    want = oracle.kv_attend_gqa(mk.centroids, mk.code_lens, mv.centroids, mv.code_lens, q.view(np.uint16),
+                                np_blocks(kb), np_meta(km), np_blocks(vb), np_meta(vm), seq, B, Hq, Hkv, T)
+    assert out.shape == want.shape and not out[1].any()
+    assert rel_l2(out, want) <= REL_L2
+    for b in (0, 2):
+        for h in range(Hq):
+            assert rel_l2(out[b, h], want[b, h]) <= REL_L2, (b, h)
+    if grp == 1 and n_splits == 1:
+        # the plain kernel answers the same question
+        ref = E.ecco_kv_attend(mk, mv, t16(q, dev), kb, km, vb, vm, ti32(seq, dev), B, Hq, T).cpu().numpy()
+        assert rel_l2(out, ref) <= REL_L2
+        # argument errors
+        with pytest.raises(E.EccoError) as e:
+            E.ecco_kv_attend_gqa(mk, mv, t16(q, dev), kb, km, vb, vm, ti32(seq, dev), B, 5, 2, T)
+        assert e.value.status == -2
+        with pytest.raises(E.EccoError) as e:
+            E.ecco_kv_attend_gqa(mk, mv, t16(q, dev), kb, km, vb, vm, ti32(seq, dev), B, 34, 2, T)
+        assert e.value.status == -2
+
+
 # ---------------------------------------------------------------------------------------------------
 # full-size workloads, checked on samples the oracle computes one by one
 def _full_weight_case(dev, oracle, name, which, rows_limit=None, n_sample=1536, batches=(1,)):
