@@ -75,6 +75,8 @@ def main():
     ap.add_argument("--only", default="", help="comma list of rows to run (kv_append,decode,gemv1,gemv8,gemv16,kv_attend; "
                     "on request only: kv_append_minmax, encode, encode_minmax -- the bulk encoders run over the K cache -- "
                     "and act_encode, act_decode -- the 2x activation codec on 32768 x 4096 activations)")
+    ap.add_argument("--gqa-group", type=int, default=4, help="query heads per key/value head of the kv_attend_gqa row (on request: --only kv_attend_gqa)")
+    ap.add_argument("--gqa-splits", type=int, default=0, help="token splits of the kv_attend_gqa row (0: enough to give every compute unit a workgroup)")
     ap.add_argument("--selector-quality", action="store_true",
                     help="add the reconstruction error of the min/max pattern selector against the least-squared-error search on the K and V caches")
     ap.add_argument("--workload", default="proj7b", choices=["proj7b", "mlp_up", "mlp_down", "proj70b"])
@@ -117,7 +119,7 @@ def main():
     # ---- KV cache ---------------------------------------------------------------------------------
     kc = W.CONFIGS["kv"]
     B, H, T = kc["batch"], kc["heads"], kc["tokens"]
-    extra_rows = [r for r in ("kv_append_minmax", "encode", "encode_minmax") if r in only]
+    extra_rows = [r for r in ("kv_append_minmax", "encode", "encode_minmax", "kv_attend_gqa") if r in only]
     act_rows = [r for r in ("act_encode", "act_decode") if r in only]
     if act_rows:
         act_rows.append("copy_reference")  # a plain device copy of the same FP16 tensor: the practical HBM ceiling beside the codec
@@ -161,6 +163,15 @@ def main():
         seq_full = torch.full((B,), T, dtype=torch.int32, device=dev)
         seq_app = torch.full((B,), T - 1, dtype=torch.int32, device=dev)  # append overwrites the last slot
         attn_out = torch.empty((B, H, 128), dtype=torch.float32, device=dev)
+        if "kv_attend_gqa" in only:
+            # the same H query heads over H / group key/value heads: the caches of the first H / group heads of every sequence
+            grp = args.gqa_group
+            Hkv = H // grp
+            gqa_splits = args.gqa_splits or max(1, 256 // (B * Hkv))
+            take = lambda a: [x[:, :Hkv].contiguous() for x in a]
+            gkb, gkm, gvb, gvm = take(kbs), take(kms), take(vbs), take(vms)
+            n_ws = (B * H * gqa_splits * 130 * 4) if gqa_splits > 1 else 16
+            gqa_ws = torch.empty((n_ws,), dtype=torch.uint8, device=dev)
         del k, v
     torch.cuda.synchronize()
 
@@ -197,6 +208,9 @@ def main():
             E.ecco_act_decode(act_blocks, act_dst)
         elif row == "copy_reference":
             act_dst.copy_(act_src)
+        elif row == "kv_attend_gqa":
+            c = next_copy(kv_copies)
+            E.ecco_kv_attend_gqa(mk, mv, q, gkb[c], gkm[c], gvb[c], gvm[c], seq_full, B, H, Hkv, T, gqa_splits, gqa_ws, attn_out)
         elif row == "encode":
             E.ecco_encode(mk, k_dev, enc_blocks, enc_meta)
         elif row == "encode_minmax":
@@ -352,6 +366,10 @@ def main():
         elif r.startswith("encode"):
             d["groups_per_s"] = B * H * T / (ms[r] * 1e-3)
             d["GBps_fp16_in_plus_blocks_out"] = B * H * T * (256 + BYTES_PER_GROUP) / (ms[r] * 1e-3) / 1e9
+        elif r == "kv_attend_gqa":
+            d["steps_per_s"] = 1.0 / (ms[r] * 1e-3)
+            d["GBps_compressed"] = 2 * B * Hkv * T * BYTES_PER_GROUP / (ms[r] * 1e-3) / 1e9
+            d["config"] = {"B": B, "Hq": H, "Hkv": Hkv, "T": T, "n_splits": gqa_splits}
         elif r == "kv_attend":
             d["steps_per_s"] = 1.0 / (ms[r] * 1e-3)
             d["GBps_compressed"] = 2 * B * H * T * BYTES_PER_GROUP / (ms[r] * 1e-3) / 1e9

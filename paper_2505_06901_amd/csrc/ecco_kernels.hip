@@ -1266,14 +1266,18 @@ __global__ __launch_bounds__(kGqaThreads) void kv_attend_gqa_kernel(const uint32
 __global__ __launch_bounds__(kGroup) void kv_attend_combine_kernel(const float* __restrict__ ws, int n_heads, int n_splits, float* __restrict__ out) {
     const size_t bh = blockIdx.x;
     const float* ml = ws + (size_t)n_heads * n_splits * kGroup + bh * n_splits * 2;
+    const float* part = ws + bh * n_splits * kGroup + threadIdx.x;
     float mx = -INFINITY;
     for (int s = 0; s < n_splits; ++s) mx = fmaxf(mx, ml[2 * s]);
+    // no branch in the loop, so that the loads of all splits are in flight together; an empty split
+    // (maximum -inf, zeros) gets weight 0, also when every split is empty (mx = -inf)
     float num = 0.0f, den = 0.0f;
+#pragma unroll 4
     for (int s = 0; s < n_splits; ++s) {
-        if (ml[2 * s] == -INFINITY) continue;  // an empty split
-        const float w = __expf(ml[2 * s] - mx);
-        num += w * ws[(bh * n_splits + s) * kGroup + threadIdx.x];
-        den += w * ml[2 * s + 1];
+        const float m = ml[2 * s], d = ml[2 * s + 1], v = part[(size_t)s * kGroup];
+        const float w = m == -INFINITY ? 0.0f : __expf(m - mx);
+        num += w * v;
+        den += w * d;
     }
     out[bh * kGroup + threadIdx.x] = den > 0.0f ? num / den : 0.0f;
 }
