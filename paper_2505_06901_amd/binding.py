@@ -21,6 +21,9 @@ EXPORTS = [
     "ecco_encode", "ecco_decode", "ecco_decode_indices", "ecco_decode_gemv", "ecco_kv_append", "ecco_kv_attend",
     "ecco_encode_minmax", "ecco_kv_append_minmax", "ecco_act_encode", "ecco_act_decode",
     "ecco_kv_attend_gqa", "ecco_kv_attend_gqa_workspace",
+    "ecco_pb_fit", "ecco_pb_model_create", "ecco_pb_model_S", "ecco_pb_model_texp", "ecco_pb_model_centroids",
+    "ecco_pb_model_code_lens", "ecco_pb_model_kp_lens", "ecco_pb_model_to_device", "ecco_pb_model_free",
+    "ecco_pb_encode", "ecco_pb_decode",
 ]
 
 
@@ -61,6 +64,18 @@ def lib():
         L.ecco_kv_attend_gqa.argtypes = [vp] * 8 + [i32, i32, i32, i32, i32, vp, vp, vp]
         L.ecco_kv_attend_gqa_workspace.argtypes = [i32, i32, i32]
         L.ecco_kv_attend_gqa_workspace.restype = sz
+        L.ecco_pb_fit.argtypes = [vp, sz, i32, u64, C.POINTER(vp)]
+        L.ecco_pb_model_create.argtypes = [vp, vp, vp, i32, i32, C.POINTER(vp)]
+        for name in ("ecco_pb_model_S", "ecco_pb_model_texp", "ecco_pb_model_centroids", "ecco_pb_model_code_lens",
+                     "ecco_pb_model_kp_lens", "ecco_pb_model_free"):
+            getattr(L, name).argtypes = [vp]
+        L.ecco_pb_model_centroids.restype = C.POINTER(C.c_uint16)
+        L.ecco_pb_model_code_lens.restype = C.POINTER(C.c_uint8)
+        L.ecco_pb_model_kp_lens.restype = C.POINTER(C.c_uint8)
+        L.ecco_pb_model_free.restype = None
+        L.ecco_pb_model_to_device.argtypes = [vp, i32]
+        L.ecco_pb_encode.argtypes = [vp, vp, sz, vp, vp]
+        L.ecco_pb_decode.argtypes = [vp, vp, sz, vp, vp]
         L.ecco_act_decode.argtypes = [vp, sz, vp, vp]
         _lib = L
     return _lib
@@ -266,4 +281,89 @@ def ecco_act_decode(blocks, dst=None):
     if dst is None:
         dst = torch.empty((n, ACT_GROUP), dtype=torch.float16, device=blocks.device)
     _check(lib().ecco_act_decode(_dp(blocks), n, _dp(dst), _stream()), "ecco_act_decode")
+    return dst
+
+
+# ---- the self-contained block format (include/ecco_paper_block.h) ------------------------------------------------
+class PbModel:
+    """Owner of an ecco_pb_model handle."""
+
+    def __init__(self, handle):
+        self._h = C.c_void_p(handle)
+
+    def __del__(self):
+        h, self._h = getattr(self, "_h", None), None
+        if h and _lib is not None:
+            _lib.ecco_pb_model_free(h)
+
+    @property
+    def handle(self):
+        return self._h
+
+    @property
+    def S(self) -> int:
+        return int(lib().ecco_pb_model_S(self._h))
+
+    @property
+    def texp(self) -> int:
+        return int(lib().ecco_pb_model_texp(self._h))
+
+    @property
+    def centroids(self) -> np.ndarray:
+        return np.ctypeslib.as_array(lib().ecco_pb_model_centroids(self._h), shape=(self.S, 15)).copy()
+
+    @property
+    def code_lens(self) -> np.ndarray:
+        return np.ctypeslib.as_array(lib().ecco_pb_model_code_lens(self._h), shape=(self.S, 4, 16)).copy()
+
+    @property
+    def kp_lens(self) -> np.ndarray:
+        return np.ctypeslib.as_array(lib().ecco_pb_model_kp_lens(self._h), shape=(self.S,)).copy()
+
+
+def ecco_pb_fit(data, S: int, seed: int = 0) -> PbModel:
+    a = np.ascontiguousarray(data)
+    if a.dtype == np.float16:
+        a = a.view(np.uint16)
+    if a.dtype != np.uint16:
+        raise TypeError("FP16 data expected")
+    out = C.c_void_p(0)
+    _check(lib().ecco_pb_fit(a.ctypes.data_as(C.c_void_p), a.size, S, seed, C.byref(out)), "ecco_pb_fit")
+    return PbModel(out.value)
+
+
+def ecco_pb_model_create(centroids, code_lens, kp_lens, texp: int) -> PbModel:
+    c = np.ascontiguousarray(centroids)
+    if c.dtype == np.float16:
+        c = c.view(np.uint16)
+    c = np.ascontiguousarray(c, dtype=np.uint16)
+    l = np.ascontiguousarray(code_lens, dtype=np.uint8)
+    k = np.ascontiguousarray(kp_lens, dtype=np.uint8)
+    out = C.c_void_p(0)
+    _check(lib().ecco_pb_model_create(c.ctypes.data_as(C.c_void_p), l.ctypes.data_as(C.c_void_p), k.ctypes.data_as(C.c_void_p),
+                                      c.size // 15, int(texp), C.byref(out)), "ecco_pb_model_create")
+    return PbModel(out.value)
+
+
+def ecco_pb_model_to_device(m: PbModel, device: int = 0) -> PbModel:
+    _check(lib().ecco_pb_model_to_device(m.handle, device), "ecco_pb_model_to_device")
+    return m
+
+
+def ecco_pb_encode(m: PbModel, src, blocks=None):
+    import torch
+    assert src.dtype == torch.float16 and src.numel() % GROUP == 0
+    n = src.numel() // GROUP
+    if blocks is None:
+        blocks = torch.empty((n, BLOCK_BYTES), dtype=torch.uint8, device=src.device)
+    _check(lib().ecco_pb_encode(m.handle, _dp(src), n, _dp(blocks), _stream()), "ecco_pb_encode")
+    return blocks
+
+
+def ecco_pb_decode(m: PbModel, blocks, dst=None):
+    import torch
+    n = blocks.numel() // BLOCK_BYTES
+    if dst is None:
+        dst = torch.empty((n, GROUP), dtype=torch.float16, device=blocks.device)
+    _check(lib().ecco_pb_decode(m.handle, _dp(blocks), n, _dp(dst), _stream()), "ecco_pb_decode")
     return dst

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libecco.so")
-SOURCES = ["ecco_fit.cpp", "ecco_model.cpp", "ecco_kernels.hip", "ecco_act.hip"]
+SOURCES = ["ecco_fit.cpp", "ecco_model.cpp", "ecco_pb_model.cpp", "ecco_kernels.hip", "ecco_act.hip", "ecco_pb_kernels.hip"]
 
 
 def _hipcc() -> str:

@@ -1,0 +1,383 @@
+// Decoder and encoder of the self-contained 4x block (include/ecco_paper_block.h) for gfx950.
+//
+// Decoder: the block has one code stream of 128 values behind a variable-length header, so a lane owns a whole
+// block: 64 blocks (4 KB) per wavefront pass, loaded with 16-byte pieces on consecutive addresses into a private
+// LDS buffer (17-word slots) one pass ahead, decoded in lockstep (value i of 64 blocks at a time) with an 8-bit
+// peek into a byte table per (pattern, codebook) -- 4 x S tables of 256 bytes, 64 KB for S = 64 -- and a second
+// small table for the centroid.  Values past the cut (code ends beyond bit 512) become zeros; the lane keeps
+// counting bits, so the test stays true once it fails.  Decoded values leave through a private LDS image, 32 per
+// lane at a time, as 64-byte pieces (four lanes per block).  The padded entries are only known when the stream
+// has been walked to its end: the lane then overwrites those positions in global memory, after the wavefront's
+// earlier stores have completed.
+//
+// Encoder: one wavefront per group, two values per lane, the same search and packing scheme as the other
+// format's encoder (reconstructed centroids in LDS, nearest value by a strict-< scan, balanced FP32 error tree,
+// bit positions by a wavefront scan, payload assembled with LDS atomic OR), plus: the element of largest
+// magnitude takes index 15 and no error; the codebook is the one of least total length; the stream is cut at
+// bit 512; if it ends before, the largest remaining magnitudes are found one by one (a wavefront maximum over a
+// key of magnitude and position) and appended as 15-bit entries.
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+
+#include <algorithm>
+#include <cstdint>
+
+#include "ecco_pb_internal.h"
+
+namespace {
+
+using namespace ecco_pb;
+
+#define ECCO_HIP_CHECK(expr) do { if ((expr) != hipSuccess) return ECCO_EHIP; } while (0)
+
+constexpr int kSlot = kBlockWords + 1;    // LDS words per staged block; the last one is a zero pad
+constexpr int kUnit = 64;                 // blocks per wavefront pass, one per lane
+constexpr int kPayWords = kUnit * kSlot + 4;
+constexpr int kPassValues = 32;           // values per lane between two write-outs
+constexpr int kImgStride = kPassValues / 2 + 1;
+constexpr int kImgWords = 64 * kImgStride;
+constexpr int kDecThreads = 512;
+constexpr int kDecWaves = kDecThreads / 64;
+
+__device__ inline void wave_lds_fence() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+__device__ inline void stage_words(uint32_t* dst, const uint32_t* __restrict__ src, int words) {  // words % 4 == 0, 16-byte aligned
+    const uint4* s = reinterpret_cast<const uint4*>(src);
+    uint4* d = reinterpret_cast<uint4*>(dst);
+    for (int i = threadIdx.x; i < (words >> 2); i += blockDim.x) d[i] = s[i];
+}
+
+inline size_t dec_lds_bytes(int S) { return (DevLayout{S}.decode_words() + (size_t)kDecWaves * (kPayWords + kImgWords)) * 4; }
+
+struct PieceLoad {
+    uint4 v[4];
+};
+__device__ __forceinline__ PieceLoad load_pieces(const uint4* __restrict__ blocks, size_t g0, size_t n_groups, int lane) {
+    PieceLoad L;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int q = lane + 64 * r;  // piece q of the pass: block q / 4, part q % 4
+        const size_t g = min(g0 + (size_t)(q >> 2), n_groups - 1);
+        L.v[r] = blocks[g * 4 + (q & 3)];
+    }
+    return L;
+}
+__device__ __forceinline__ void store_pieces(uint32_t* pay, const PieceLoad& L, int lane) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int q = lane + 64 * r;
+        uint32_t* d = pay + (q >> 2) * kSlot + (q & 3) * 4;
+        d[0] = L.v[r].x; d[1] = L.v[r].y; d[2] = L.v[r].z; d[3] = L.v[r].w;
+    }
+}
+
+__global__ __launch_bounds__(kDecThreads) void pb_decode_kernel(const uint32_t* __restrict__ dev, int S,
+                                                               const uint4* __restrict__ blocks, size_t n_groups,
+                                                               uint16_t* __restrict__ dst) {
+    extern __shared__ __align__(16) uint32_t smem[];
+    const DevLayout D{S};
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint8_t* lut = reinterpret_cast<const uint8_t*>(smem + D.lut());
+    const uint16_t* kplut = reinterpret_cast<const uint16_t*>(smem + D.kplut());
+    const uint16_t* cent = reinterpret_cast<const uint16_t*>(smem + D.cent());
+    const uint16_t* fp8 = reinterpret_cast<const uint16_t*>(smem + D.fp8());
+    uint32_t* pay = smem + D.decode_words() + wave * (kPayWords + kImgWords);
+    uint32_t* img = pay + kPayWords;
+
+    const size_t n_units = (n_groups + kUnit - 1) / kUnit;
+    const size_t first = (size_t)blockIdx.x * kDecWaves + wave, step = (size_t)gridDim.x * kDecWaves;
+    PieceLoad pre;
+    if (first < n_units) pre = load_pieces(blocks, first * kUnit, n_groups, lane);
+    stage_words(smem, dev, (int)D.decode_words());
+    pay[lane * kSlot + kBlockWords] = 0u;
+    if (lane < 4) pay[kUnit * kSlot + lane] = 0u;
+    __syncthreads();
+
+    for (size_t u = first; u < n_units; u += step) {
+        const size_t g0 = u * kUnit;
+        wave_lds_fence();
+        store_pieces(pay, pre, lane);
+        wave_lds_fence();
+        if (u + step < n_units) pre = load_pieces(blocks, (u + step) * kUnit, n_groups, lane);
+        const uint32_t* w = pay + lane * kSlot;
+        const uint32_t w0 = w[0];
+        const uint32_t kpe = kplut[(w0 >> 14) & 0xFFu];
+        const uint32_t p = kpe >> 8;
+        const uint32_t sv = fp8[w0 >> 24];                 // the signed scale, FP16 bits
+        const __half sabs = __ushort_as_half((unsigned short)(sv & 0x7FFFu));
+        const uint8_t* tab = lut + (p * kBooks + ((w0 >> 22) & 3u)) * 256u;
+        const uint16_t* cp = cent + p * 16u;
+        uint32_t fetch = 10u + (kpe & 0xFFu);              // where the next run is fetched from; stops at 512
+        uint32_t reach = fetch;                             // where the codes read so far end; keeps counting past 512
+#pragma unroll 1
+        for (int pass = 0; pass < kGroup / kPassValues; ++pass) {
+            uint32_t packed[kPassValues / 2];
+#pragma unroll
+            for (int i0 = 0; i0 < kPassValues; i0 += 4) {
+                const uint32_t wi = fetch >> 5;
+                uint64_t win = (((uint64_t)w[wi] << 32) | (uint64_t)w[wi + 1]) << (fetch & 31u);
+                uint32_t used = 0;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t e = tab[(uint32_t)(win >> 56)];
+                    const uint32_t len = e & 15u;
+                    reach += len;
+                    used += len;
+                    win <<= len;
+                    const __half prod = __hmul(__ushort_as_half(cp[e >> 4]), sabs);   // one rounding: fp16(c * |s|)
+                    uint32_t val = e >= 0xF0u ? sv : (uint32_t)__half_as_ushort(prod);
+                    val = reach <= (uint32_t)kBlockBits ? val : 0u;                     // a code that ends beyond the block is absent
+                    const int i = i0 + j;
+                    if (i & 1) packed[i >> 1] |= val << 16; else packed[i >> 1] = val;
+                }
+                fetch = min(fetch + used, (uint32_t)kBlockBits);
+            }
+            wave_lds_fence();
+#pragma unroll
+            for (int k = 0; k < kPassValues / 2; ++k) img[lane * kImgStride + k] = packed[k];
+            wave_lds_fence();
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int b = (lane >> 2) + 16 * r, part = lane & 3;
+                const uint32_t* s = img + b * kImgStride + part * 4;
+                const uint4 v = make_uint4(s[0], s[1], s[2], s[3]);
+                if (g0 + b < n_groups) reinterpret_cast<uint4*>(dst)[(g0 + b) * 16 + pass * 4 + part] = v;
+            }
+        }
+        // padded entries: only if all 128 values were present
+        if (reach <= (uint32_t)kBlockBits && g0 + lane < n_groups) {
+            const uint32_t n_out = ((uint32_t)kBlockBits - reach) / kOutlierBits;
+            if (__builtin_amdgcn_ballot_w64(n_out > 0) != 0ull) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the stores above have landed
+            for (uint32_t j = 0; j < n_out; ++j) {
+                const uint32_t at = reach + j * kOutlierBits, wi = at >> 5;
+                const uint64_t win = (((uint64_t)w[wi] << 32) | (uint64_t)w[wi + 1]) << (at & 31u);
+                const uint32_t entry = (uint32_t)(win >> 49);   // 7-bit position, 8-bit float
+                dst[(g0 + lane) * kGroup + (entry >> 8)] = fp8[entry & 0xFFu];
+            }
+        }
+    }
+}
+
+// ---- encoder ---------------------------------------------------------------------------------------------------
+constexpr int kEncThreads = 256;
+constexpr int kEncWaves = kEncThreads / 64;
+constexpr int kBitWords = kBlockWords + 2;
+
+template <int kCtrl>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, kCtrl, 0xF, 0xF, true);
+}
+__device__ __forceinline__ uint32_t lane_u32(uint32_t v, int l) { return (uint32_t)__builtin_amdgcn_readlane((int)v, l); }
+// an associative, commutative, exact operation over the 64 lanes (cross-lane moves inside rows of 16, then the four
+// row results through scalar registers); every lane returns the result
+template <class Op>
+__device__ __forceinline__ uint32_t wave_all_u32(uint32_t t, Op op) {
+    t = op(t, dpp_u32<0xB1>(t));   // quad_perm [1,0,3,2]
+    t = op(t, dpp_u32<0x4E>(t));   // quad_perm [2,3,0,1]
+    t = op(t, dpp_u32<0x141>(t));  // row_half_mirror
+    t = op(t, dpp_u32<0x140>(t));  // row_mirror
+    return op(op(lane_u32(t, 0), lane_u32(t, 16)), op(lane_u32(t, 32), lane_u32(t, 48)));
+}
+// FP32 sum in the balanced tree: aligned blocks of 2, 4, 8, 16 lanes, then (row 0 + row 1) + (row 2 + row 3)
+__device__ __forceinline__ float wave_tree_sum(float t) {
+    const auto f = [](float v) { return __builtin_bit_cast(uint32_t, v); };
+    const auto g = [](uint32_t v) { return __builtin_bit_cast(float, v); };
+    t = __fadd_rn(t, g(dpp_u32<0xB1>(f(t))));
+    t = __fadd_rn(t, g(dpp_u32<0x4E>(f(t))));
+    t = __fadd_rn(t, g(dpp_u32<0x141>(f(t))));
+    t = __fadd_rn(t, g(dpp_u32<0x140>(f(t))));
+    return __fadd_rn(__fadd_rn(g(lane_u32(f(t), 0)), g(lane_u32(f(t), 16))), __fadd_rn(g(lane_u32(f(t), 32)), g(lane_u32(f(t), 48))));
+}
+
+__device__ __forceinline__ float half_bits_f(uint32_t bits) { return __half2float(__ushort_as_half((unsigned short)bits)); }
+
+// v to the format's 8-bit float: nearest, ties to the even code, saturating at +-480
+__device__ __forceinline__ uint32_t fp8_round_dev(float v) {
+    const uint32_t sign = (__float_as_uint(v) >> 24) & 0x80u;
+    const float a = fabsf(v);
+    uint32_t code;
+    if (a < 0.015625f) {
+        code = (uint32_t)rintf(a * 512.0f);  // below 2^-6 the values are multiples of 2^-9; 8 is the smallest normal number
+    } else {
+        const uint32_t b = __float_as_uint(a);
+        const uint32_t r = b + 0x7FFFFu + ((b >> 20) & 1u);  // to three mantissa bits, ties to even
+        const int e = (int)(r >> 23) - 120;
+        code = e > 15 ? 127u : (((uint32_t)e << 3) | ((r >> 20) & 7u));
+    }
+    return sign | code;
+}
+
+inline size_t enc_lds_bytes(int S) { return (DevLayout{S}.encode_words() + (size_t)kEncWaves * ((size_t)S * 16 + kBitWords)) * 4; }
+
+// ORs the low `nbits` of `value` into the block image at stream bit `at`, most significant bit first; bits at or
+// beyond 512 are dropped (the cut)
+__device__ __forceinline__ void put_bits(uint32_t* bits, uint32_t at, uint32_t value, uint32_t nbits) {
+    const uint64_t v = (uint64_t)value << (64u - nbits - (at & 31u));
+    const uint32_t wi = at >> 5;
+    if (wi < (uint32_t)kBlockWords && (uint32_t)(v >> 32) != 0u) atomicOr(&bits[wi], (uint32_t)(v >> 32));
+    if (wi + 1 < (uint32_t)kBlockWords && (uint32_t)v != 0u) atomicOr(&bits[wi + 1], (uint32_t)v);
+}
+
+__global__ __launch_bounds__(kEncThreads) void pb_encode_kernel(const uint32_t* __restrict__ dev, int S, float inv_tscale,
+                                                               const uint32_t* __restrict__ src, size_t n_groups,
+                                                               uint32_t* __restrict__ blocks) {
+    extern __shared__ __align__(16) uint32_t smem[];
+    const DevLayout D{S};
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    stage_words(smem, dev + D.cent(), (int)D.encode_words());
+    __syncthreads();
+    const uint16_t* cent = reinterpret_cast<const uint16_t*>(smem);                                   // [S][16]
+    const uint16_t* fp8 = reinterpret_cast<const uint16_t*>(smem + (D.fp8() - D.cent()));             // [256]
+    const uint32_t* enc = smem + (D.enc() - D.cent());                                                // [S * 4][16]
+    const uint32_t* kpenc = smem + (D.kpenc() - D.cent());                                            // [S]
+    float* recon = reinterpret_cast<float*>(smem + D.encode_words()) + wave * (S * 16 + kBitWords);   // [S][16], this wavefront's
+    uint32_t* bits = reinterpret_cast<uint32_t*>(recon + S * 16);                                     // [18]
+    const auto umax = [](uint32_t a, uint32_t b) { return max(a, b); };
+    const auto uadd = [](uint32_t a, uint32_t b) { return a + b; };
+
+    for (size_t g = (size_t)blockIdx.x * kEncWaves + wave; g < n_groups; g += (size_t)gridDim.x * kEncWaves) {
+        const uint32_t pair = src[g * (kGroup / 2) + lane];
+        const uint32_t hx0 = pair & 0xFFFFu, hx1 = pair >> 16;                   // values 2l and 2l + 1
+        // the element of largest magnitude, first position on ties: largest key of (magnitude, 127 - position)
+        const uint32_t pos0 = 2u * lane, pos1 = pos0 + 1u;
+        uint32_t key0 = ((hx0 & 0x7FFFu) << 7) | (127u - pos0), key1 = ((hx1 & 0x7FFFu) << 7) | (127u - pos1);
+        const uint32_t top = wave_all_u32(max(key0, key1), umax);
+        const uint32_t a = 127u - (top & 127u);
+        const uint32_t xa = lane_u32((a & 1u) ? hx1 : hx0, (int)(a >> 1));
+        const uint32_t s8 = fp8_round_dev(half_bits_f(xa) * inv_tscale);
+        const uint32_t sv = fp8[s8];
+        const float s = half_bits_f(sv & 0x7FFFu);
+        const float x0 = half_bits_f(hx0), x1 = half_bits_f(hx1);
+        const bool is0 = pos0 == a, is1 = pos1 == a;
+        // reconstructed centroids of every pattern
+        for (int i = lane; i < S * 16; i += 64) recon[i] = half_bits_f((uint32_t)__half_as_ushort(__float2half_rn(half_bits_f(cent[i]) * s)));
+        if (lane < kBitWords) bits[lane] = 0u;
+        wave_lds_fence();
+        // pattern of least squared error over the other 127 elements
+        float best_sse = 0.0f;
+        int best_p = 0;
+        uint32_t best_idx = 0;
+        for (int p = 0; p < S; ++p) {
+            const float* r = recon + p * 16;
+            float d0 = fabsf(__fsub_rn(x0, r[0])), d1 = fabsf(__fsub_rn(x1, r[0]));
+            uint32_t k0 = 0, k1 = 0;
+#pragma unroll
+            for (int k = 1; k < kCent; ++k) {
+                const float rk = r[k];
+                const float u = fabsf(__fsub_rn(x0, rk)), v = fabsf(__fsub_rn(x1, rk));
+                const bool c0 = u < d0, c1 = v < d1;  // strict: the lowest index wins a tie
+                k0 = c0 ? (uint32_t)k : k0;
+                k1 = c1 ? (uint32_t)k : k1;
+                d0 = c0 ? u : d0;
+                d1 = c1 ? v : d1;
+            }
+            const float e0 = __fsub_rn(x0, r[k0]), e1 = __fsub_rn(x1, r[k1]);
+            const float q0 = is0 ? 0.0f : __fmul_rn(e0, e0), q1 = is1 ? 0.0f : __fmul_rn(e1, e1);
+            const float sse = wave_tree_sum(__fadd_rn(q0, q1));
+            if (p == 0 || sse < best_sse) {
+                best_sse = sse;
+                best_p = p;
+                best_idx = k0 | (k1 << 4);
+            }
+        }
+        const uint32_t i0 = is0 ? 15u : (best_idx & 15u), i1 = is1 ? 15u : (best_idx >> 4);
+        // the codebook of least total length
+        uint32_t c0 = 0, c1 = 0, best_total = 0;
+        int best_h = 0;
+        for (int h = 0; h < kBooks; ++h) {
+            const uint32_t* t = enc + (best_p * kBooks + h) * kSym;
+            const uint32_t a0 = t[i0], a1 = t[i1];
+            const uint32_t total = wave_all_u32((a0 >> 16) + (a1 >> 16), uadd);
+            if (h == 0 || total < best_total) {
+                best_total = total;
+                best_h = h;
+                c0 = a0;
+                c1 = a1;
+            }
+        }
+        // header, then the codes at their positions (inclusive scan of the lengths over the lanes)
+        const uint32_t kp = kpenc[best_p], base = 10u + (kp >> 16);
+        if (lane == 0) bits[0] = (s8 << 24) | ((uint32_t)best_h << 22) | ((kp & 0xFFFFu) << (22u - (kp >> 16)));
+        wave_lds_fence();
+        const uint32_t l0 = c0 >> 16, l1 = c1 >> 16;
+        uint32_t incl = l0 + l1;
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t o = (uint32_t)__shfl_up((int)incl, d);
+            if (lane >= d) incl += o;
+        }
+        put_bits(bits, base + incl - (l0 + l1), ((c0 & 0xFFFFu) << l1) | (c1 & 0xFFFFu), l0 + l1);
+        const uint32_t end = base + best_total;
+        if (end <= (uint32_t)kBlockBits) {
+            // room left: the largest remaining magnitudes, one per round, as (position, 8-bit float) entries
+            const uint32_t slots = ((uint32_t)kBlockBits - end) / kOutlierBits;
+            key0 = is0 ? 0u : key0 + 1u;
+            key1 = is1 ? 0u : key1 + 1u;
+            for (uint32_t j = 0; j < slots; ++j) {
+                const uint32_t best = wave_all_u32(max(key0, key1), umax);
+                if (best == 0u) break;
+                if (key0 == best || key1 == best) {
+                    const bool first = key0 == best;
+                    const uint32_t v8 = fp8_round_dev((first ? x0 : x1) * inv_tscale);
+                    put_bits(bits, end + j * kOutlierBits, ((first ? pos0 : pos1) << 8) | v8, kOutlierBits);
+                    if (first) key0 = 0u; else key1 = 0u;
+                }
+            }
+        }
+        wave_lds_fence();
+        if (lane < kBlockWords) blocks[g * kBlockWords + lane] = bits[lane];
+        wave_lds_fence();
+    }
+}
+
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+inline int model_ready(const ecco_pb_model* m) { return (m && m->dev && m->device >= 0) ? ECCO_OK : ECCO_EINVAL; }
+
+template <class K>
+int allow_lds(K kernel, size_t bytes) {
+    if (bytes > 64 * 1024)
+        ECCO_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+    return ECCO_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int ecco_pb_encode(const ecco_pb_model* m, const uint16_t* src, size_t n_groups, void* blocks, void* stream) {
+    if (model_ready(m) != ECCO_OK) return ECCO_EINVAL;
+    if (n_groups == 0) return ECCO_OK;
+    if (!src || !blocks) return ECCO_EINVAL;
+    if (!aligned(src, 4) || !aligned(blocks, 64)) return ECCO_EALIGN;
+    const size_t wgs = (n_groups + kEncWaves - 1) / kEncWaves;
+    const int grid = (int)std::min<size_t>(wgs, 256 * 16);
+    float inv_tscale = 1.0f;  // 2^-texp, exact
+    for (int i = 0; i < (m->texp < 0 ? -m->texp : m->texp); ++i) inv_tscale *= m->texp < 0 ? 2.0f : 0.5f;
+    hipLaunchKernelGGL(pb_encode_kernel, dim3(grid), dim3(kEncThreads), enc_lds_bytes(m->S), static_cast<hipStream_t>(stream), m->dev, m->S,
+                       inv_tscale, reinterpret_cast<const uint32_t*>(src), n_groups, static_cast<uint32_t*>(blocks));
+    ECCO_HIP_CHECK(hipGetLastError());
+    return ECCO_OK;
+}
+
+int ecco_pb_decode(const ecco_pb_model* m, const void* blocks, size_t n_groups, uint16_t* dst, void* stream) {
+    if (model_ready(m) != ECCO_OK) return ECCO_EINVAL;
+    if (n_groups == 0) return ECCO_OK;
+    if (!blocks || !dst) return ECCO_EINVAL;
+    if (n_groups >= ((size_t)1 << 31)) return ECCO_ESHAPE;
+    if (!aligned(blocks, 64) || !aligned(dst, 16)) return ECCO_EALIGN;
+    const size_t lds = dec_lds_bytes(m->S);
+    const int rc = allow_lds(pb_decode_kernel, lds);
+    if (rc != ECCO_OK) return rc;
+    const size_t units = (n_groups + kUnit - 1) / kUnit;
+    const int grid = (int)std::min<size_t>((units + kDecWaves - 1) / kDecWaves, 1024);
+    hipLaunchKernelGGL(pb_decode_kernel, dim3(grid), dim3(kDecThreads), lds, static_cast<hipStream_t>(stream), m->dev, m->S,
+                       static_cast<const uint4*>(blocks), n_groups, dst);
+    ECCO_HIP_CHECK(hipGetLastError());
+    return ECCO_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,86 @@
+"""Parity of the self-contained block format (include/ecco_paper_block.h) against its CPU oracle, through the C ABI, on
+one MI355X: encoded blocks and decoded FP16 bit-exact."""
+from __future__ import annotations
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+import paper_2505_06901_amd as E  # noqa: E402
+from paper_2505_06901_amd import workloads as W  # noqa: E402
+from test_paper_block_pins import _groups, _model  # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def dev():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    return torch.device("cuda:0")
+
+
+@pytest.fixture(scope="module")
+def pb():
+    from oracle import paper_block as P
+    return P
+
+
+def _both(pb, om):
+    """The library's model object for an oracle-side model description."""
+    return E.ecco_pb_model_to_device(E.ecco_pb_model_create(om.cent, om.lens, om.kp_lens, om.texp), 0)
+
+
+def _t16(a, dev):
+    return torch.from_numpy(np.ascontiguousarray(a).view(np.float16)).to(dev)
+
+
+def _check_roundtrip(pb, dev, om, m, x):
+    want_blocks = pb.encode(om, x.view(np.uint16))
+    got_blocks = E.ecco_pb_encode(m, _t16(x, dev)).cpu().numpy()
+    bad = np.nonzero((got_blocks != want_blocks).any(axis=1))[0]
+    assert bad.size == 0, (bad[:8], got_blocks[bad[0]], want_blocks[bad[0]])
+    want, n_coded, n_out = pb.decode(om, want_blocks)
+    got = E.ecco_pb_decode(m, torch.from_numpy(want_blocks).to(dev)).cpu().numpy().view(np.uint16)
+    bad = np.nonzero((got != want).any(axis=1))[0]
+    assert bad.size == 0, (bad[:8], n_coded[bad[0]], n_out[bad[0]], np.nonzero(got[bad[0]] != want[bad[0]])[0][:8])
+    return n_coded, n_out
+
+
+def test_hand_models_bit_exact(pb, dev):
+    for S, texp, seed, skew in [(5, -9, 1, 2.4), (1, -6, 2, 1.6), (64, -8, 3, 3.0)]:
+        om = _model(pb, S=S, texp=texp, seed=seed, skew=skew)
+        m = _both(pb, om)
+        x = _groups(seed + 10, 64 * 5 + 37, scale=2.0 ** texp * 40)           # several passes of 64 blocks and a ragged tail
+        x[0] = 0
+        x[1] = np.float16(2.0 ** texp * 480)                                  # every element at the largest scale
+        x[2, 5] = -x[2, 5]; x[2, 77] = -np.abs(x[2]).max() * np.float16(1.0)   # the largest magnitude is negative
+        x[3] = (np.arange(128) - 64).astype(np.float16) * np.float16(2.0 ** texp)
+        x[4, :] = np.float16(6e-8)                                            # below the smallest scale: everything rounds to 0
+        x[5] = np.float16(-0.0)
+        n_coded, n_out = _check_roundtrip(pb, dev, om, m, x)
+        assert (n_coded < 128).any() or S == 1 or skew < 2, "no clipped block in this input"
+        assert (n_out > 0).any(), "no padded block in this input"
+        # arbitrary bytes decode identically
+        junk = np.random.default_rng(seed).integers(0, 256, (64 * 3 + 5, 64), dtype=np.uint8)
+        want, _, _ = pb.decode(om, junk)
+        got = E.ecco_pb_decode(m, torch.from_numpy(junk).to(dev)).cpu().numpy().view(np.uint16)
+        assert np.array_equal(got, want)
+
+
+def test_fitted_model_bit_exact(pb, dev):
+    w = W.config_weight("tiny")                                               # 64 x 1024, N(0, 0.02) with outliers
+    m = E.ecco_pb_model_to_device(E.ecco_pb_fit(w, 16, 0), 0)
+    om = pb.Model(m.centroids, m.code_lens, m.kp_lens, m.texp)
+    assert pb.verify_model(om) == 0
+    n_coded, n_out = _check_roundtrip(pb, dev, om, m, w.reshape(-1, 128))
+    # reconstruction is close: relative squared error of a 15-level non-uniform quantiser with outliers kept in FP8
+    dec = E.ecco_pb_decode(m, E.ecco_pb_encode(m, _t16(w, dev))).float().cpu().numpy().reshape(w.shape)
+    rel = np.square(dec - w.astype(np.float32)).sum() / np.square(w.astype(np.float32)).sum()
+    assert rel < 0.02, rel
+    # argument errors
+    with pytest.raises(E.EccoError) as e:
+        E.ecco_pb_decode(m, torch.empty(128 + 16, dtype=torch.uint8, device=dev)[16:144])
+    assert e.value.status == -3
+    E.ecco_pb_encode(m, torch.empty((0, 128), dtype=torch.float16, device=dev))

@@ -17,9 +17,9 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def test_header_symbols_exported():
-    text = open(os.path.join(ROOT, "include", "ecco.h")).read()
+    text = "".join(open(os.path.join(ROOT, "include", h)).read() for h in sorted(os.listdir(os.path.join(ROOT, "include"))))
     declared = set(re.findall(r"\b(ecco_[a-z_A-Z0-9]+)\s*\(", text))
-    declared -= {"ecco_model", "ecco_status"}  # type names that precede a parenthesis in comments
+    declared -= {"ecco_model", "ecco_status", "ecco_pb_model"}  # type names that precede a parenthesis in comments
     assert declared == set(binding.EXPORTS), declared ^ set(binding.EXPORTS)
     L = binding.lib()
     for name in declared:
@@ -122,3 +122,33 @@ def test_argument_errors_without_gpu(tiny_model):
     assert L.ecco_decode(h, null, fake, 1, fake, null) == -1
     assert L.ecco_model_to_device(null, 0) == -1
     assert L.ecco_model_to_device(h, -1) == -1
+
+
+def test_paper_block_fit_invariants():
+    """The CPU fit of the self-contained block format: a valid model (checked by the oracle's verifier), deterministic."""
+    from oracle import paper_block as P
+    w = W.config_weight("tiny")
+    m = E.ecco_pb_fit(w, 16, 0)
+    om = P.Model(m.centroids, m.code_lens, m.kp_lens, m.texp)
+    assert P.verify_model(om) == 0
+    assert m.S == 16 and -15 <= m.texp <= 7
+    top = float(np.abs(w.astype(np.float32)).max())
+    assert top / 2.0 ** m.texp <= 480 and (m.texp == -15 or top / 2.0 ** (m.texp - 1) > 480)   # the smallest power of two that fits
+    lens = m.code_lens
+    assert lens.min() >= 2 and lens.max() <= 8
+    m2 = E.ecco_pb_fit(w, 16, 0)
+    assert np.array_equal(m2.centroids, m.centroids) and np.array_equal(m2.code_lens, lens) and np.array_equal(m2.kp_lens, m.kp_lens)
+    # the tables survive a trip through ecco_pb_model_create; bad tables are refused
+    m3 = E.ecco_pb_model_create(m.centroids, lens, m.kp_lens, m.texp)
+    assert np.array_equal(m3.centroids, m.centroids)
+    bad = lens.copy(); bad[0, 0, 0] = 1
+    with pytest.raises(E.EccoError) as e:
+        E.ecco_pb_model_create(m.centroids, bad, m.kp_lens, m.texp)
+    assert e.value.status == -5
+    with pytest.raises(E.EccoError) as e:
+        E.ecco_pb_model_create(m.centroids, lens, m.kp_lens, 9)
+    assert e.value.status == -5
+    # codebooks compress: on the fit data nearly all values fit and some blocks have room for padded entries
+    blocks = P.encode(om, w.view(np.uint16))
+    dec, n_coded, n_out = P.decode(om, blocks)
+    assert n_coded.mean() > 120 and (n_out > 0).mean() > 0.05
