@@ -74,7 +74,8 @@ def main():
     ap.add_argument("--eager", action="store_true", help="launch every call from Python with its own event pair instead of replaying a HIP graph")
     ap.add_argument("--only", default="", help="comma list of rows to run (kv_append,decode,gemv1,gemv8,gemv16,kv_attend; "
                     "on request only: kv_append_minmax, encode, encode_minmax -- the bulk encoders run over the K cache -- "
-                    "and act_encode, act_decode -- the 2x activation codec on 32768 x 4096 activations)")
+                    "act_encode, act_decode -- the 2x activation codec on 32768 x 4096 activations -- and pb_encode, pb_decode -- the self-contained "
+                    "block format on the workload's weight matrix)")
     ap.add_argument("--gqa-group", type=int, default=4, help="query heads per key/value head of the kv_attend_gqa row (on request: --only kv_attend_gqa)")
     ap.add_argument("--gqa-splits", type=int, default=0, help="token splits of the kv_attend_gqa row (0: enough to give every compute unit a workgroup)")
     ap.add_argument("--selector-quality", action="store_true",
@@ -120,6 +121,7 @@ def main():
     kc = W.CONFIGS["kv"]
     B, H, T = kc["batch"], kc["heads"], kc["tokens"]
     extra_rows = [r for r in ("kv_append_minmax", "encode", "encode_minmax", "kv_attend_gqa") if r in only]
+    pb_rows = [r for r in ("pb_encode", "pb_decode") if r in only]
     act_rows = [r for r in ("act_encode", "act_decode") if r in only]
     if act_rows:
         act_rows.append("copy_reference")  # a plain device copy of the same FP16 tensor: the practical HBM ceiling beside the codec
@@ -175,6 +177,20 @@ def main():
         del k, v
     torch.cuda.synchronize()
 
+    # ---- the self-contained block format on the same weight matrix ------------------------------------------------------
+    if pb_rows:
+        pbm = E.ecco_pb_model_to_device(E.ecco_pb_fit(w, cfg["S"], cfg["seeds"][which]), 0)
+        w_dev = torch.from_numpy(w).to(dev)
+        pb_blocks = [E.ecco_pb_encode(pbm, w_dev) for _ in range(min(n_copies, 64))]
+        pb_out = torch.empty((n_groups, 128), dtype=torch.float16, device=dev)
+        pb_dec = E.ecco_pb_decode(pbm, pb_blocks[0]).float()
+        wf = w_dev.float().reshape(-1, 128)
+        pb_info = {"rel_mse": float((pb_dec - wf).square().sum() / wf.square().sum()),
+                   "rel_mse_other_format": float((E.ecco_decode(m, blocks0, meta0).float() - wf).square().sum() / wf.square().sum()),
+                   "texp": pbm.texp}
+        del pb_dec, wf
+    torch.cuda.synchronize()
+
     # ---- activations for the 2x codec: 32768 tokens x 4096 channels, N(0,1) times a per-channel magnitude ----------
     if act_rows:
         act_tokens, act_hidden = 32768, 4096
@@ -188,7 +204,7 @@ def main():
     torch.cuda.synchronize()
 
     # ---- the step -----------------------------------------------------------------------------------
-    row_names = [r for r in ("kv_append", "decode", "gemv1", "gemv8", "gemv16", "kv_attend") if want(r)] + extra_rows + act_rows
+    row_names = [r for r in ("kv_append", "decode", "gemv1", "gemv8", "gemv16", "kv_attend") if want(r)] + extra_rows + pb_rows + act_rows
     counter = [0]
 
     def next_copy(n):
@@ -202,6 +218,10 @@ def main():
         elif row == "kv_append_minmax":
             c = next_copy(kv_copies)
             E.ecco_kv_append_minmax(mk, mv, k_new, v_new, kbs[c], kms[c], vbs[c], vms[c], seq_app, B, H, T)
+        elif row == "pb_encode":
+            E.ecco_pb_encode(pbm, w_dev, pb_blocks[next_copy(len(pb_blocks))])
+        elif row == "pb_decode":
+            E.ecco_pb_decode(pbm, pb_blocks[next_copy(len(pb_blocks))], pb_out)
         elif row == "act_encode":
             E.ecco_act_encode(act_src, act_blocks)
         elif row == "act_decode":
@@ -281,7 +301,7 @@ def main():
         # per-row duration: a graph of one launch per rotating copy of that row's input, replayed
         ms = {}
         for row in row_names:
-            n = 2 if row.startswith("encode") else 4 if row.startswith("act_") or row == "copy_reference" else kv_copies if row.startswith("kv_") else n_copies
+            n = 2 if row.startswith("encode") else 4 if row.startswith("act_") or row == "copy_reference" else len(pb_blocks) if row.startswith("pb_") else kv_copies if row.startswith("kv_") else n_copies
             def one_round(row=row, n=n):
                 for _ in range(n):
                     run_row(row)
@@ -356,6 +376,11 @@ def main():
             d["GBps_compressed"] = comp_bytes / (ms[r] * 1e-3) / 1e9
         elif r.startswith("kv_append"):
             d["groups_per_s"] = 2 * B * H / (ms[r] * 1e-3)
+        elif r.startswith("pb_"):
+            d["groups_per_s"] = n_groups / (ms[r] * 1e-3)
+            d["GBps_total_traffic"] = n_groups * (64 + 256) / (ms[r] * 1e-3) / 1e9   # 64-byte block + 256 bytes of FP16
+            d["pct_hbm_peak"] = 100.0 * d["GBps_total_traffic"] / HBM_PEAK_GBS
+            d.update(pb_info)
         elif r == "copy_reference":
             d["GBps_total_traffic"] = 2 * act_src.numel() * 2 / (ms[r] * 1e-3) / 1e9
             d["pct_hbm_peak"] = 100.0 * d["GBps_total_traffic"] / HBM_PEAK_GBS

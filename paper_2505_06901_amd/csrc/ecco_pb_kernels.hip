@@ -115,10 +115,12 @@ __global__ __launch_bounds__(kDecThreads) void pb_decode_kernel(const uint32_t* 
         uint32_t fetch = 10u + (kpe & 0xFFu);              // where the next run is fetched from; stops at 512
         uint32_t reach = fetch;                             // where the codes read so far end; keeps counting past 512
 #pragma unroll 1
-        for (int pass = 0; pass < kGroup / kPassValues; ++pass) {
-            uint32_t packed[kPassValues / 2];
+        for (int pp = 0; pp < kGroup / (2 * kPassValues); ++pp) {
+            // 64 values per lane (one 128-byte line of output), kept in registers, then written out in two rounds right
+            // after each other: the two 64-byte halves of a line reach the L2 together instead of a pass apart
+            uint32_t packed[kPassValues];
 #pragma unroll
-            for (int i0 = 0; i0 < kPassValues; i0 += 4) {
+            for (int i0 = 0; i0 < 2 * kPassValues; i0 += 4) {
                 const uint32_t wi = fetch >> 5;
                 uint64_t win = (((uint64_t)w[wi] << 32) | (uint64_t)w[wi + 1]) << (fetch & 31u);
                 uint32_t used = 0;
@@ -137,16 +139,19 @@ __global__ __launch_bounds__(kDecThreads) void pb_decode_kernel(const uint32_t* 
                 }
                 fetch = min(fetch + used, (uint32_t)kBlockBits);
             }
-            wave_lds_fence();
 #pragma unroll
-            for (int k = 0; k < kPassValues / 2; ++k) img[lane * kImgStride + k] = packed[k];
-            wave_lds_fence();
+            for (int half = 0; half < 2; ++half) {
+                wave_lds_fence();
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int b = (lane >> 2) + 16 * r, part = lane & 3;
-                const uint32_t* s = img + b * kImgStride + part * 4;
-                const uint4 v = make_uint4(s[0], s[1], s[2], s[3]);
-                if (g0 + b < n_groups) reinterpret_cast<uint4*>(dst)[(g0 + b) * 16 + pass * 4 + part] = v;
+                for (int k = 0; k < kPassValues / 2; ++k) img[lane * kImgStride + k] = packed[half * (kPassValues / 2) + k];
+                wave_lds_fence();
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int b = (lane >> 2) + 16 * r, part = lane & 3;
+                    const uint32_t* s = img + b * kImgStride + part * 4;
+                    const uint4 v = make_uint4(s[0], s[1], s[2], s[3]);
+                    if (g0 + b < n_groups) reinterpret_cast<uint4*>(dst)[(g0 + b) * 16 + (2 * pp + half) * 4 + part] = v;
+                }
             }
         }
         // padded entries: only if all 128 values were present
