@@ -84,3 +84,25 @@ def test_fitted_model_bit_exact(pb, dev):
         E.ecco_pb_decode(m, torch.empty(128 + 16, dtype=torch.uint8, device=dev)[16:144])
     assert e.value.status == -3
     E.ecco_pb_encode(m, torch.empty((0, 128), dtype=torch.float16, device=dev))
+
+
+def test_full_projection_sampled(pb, dev):
+    """The 4096 x 4096 projection (131 072 groups), model fitted with S = 64, in the launch shape the benchmark times:
+    sampled blocks against the oracle's encoder, sampled decoded groups against its decoder."""
+    w = W.config_weight("proj7b")
+    m = E.ecco_pb_model_to_device(E.ecco_pb_fit(w, 64, 1), 0)
+    om = pb.Model(m.centroids, m.code_lens, m.kp_lens, m.texp)
+    assert pb.verify_model(om) == 0
+    blocks = E.ecco_pb_encode(m, _t16(w, dev))
+    dec = E.ecco_pb_decode(m, blocks).cpu().numpy().view(np.uint16)
+    blocks = blocks.cpu().numpy()
+    rows = np.sort(np.random.default_rng(11).choice(blocks.shape[0], 1536, replace=False))
+    want_blocks = pb.encode(om, w.reshape(-1, 128)[rows].view(np.uint16))
+    assert np.array_equal(blocks[rows], want_blocks)
+    want, n_coded, n_out = pb.decode(om, want_blocks)
+    assert np.array_equal(dec[rows], want)
+    assert (n_coded < 128).any() and (n_out > 0).any()
+    # whole-output properties: finite values, bounded by the tensor's largest magnitude times the FP8 rounding slack
+    assert (((dec >> 10) & 0x1F) != 31).all()
+    top = float(np.abs(w.astype(np.float32)).max())
+    assert float(np.abs(dec.view(np.float16).astype(np.float32)).max()) <= top * 1.07

@@ -523,6 +523,28 @@ def test_full_kv_cache(dev, oracle):
     # token 7 encoded into slot T-1 must equal its encoding in slot 7 (same values, same model), on all heads
     assert torch.equal(kb2[:, :, T - 1], kb[:, :, 7]) and torch.equal(km2[:, :, T - 1], km[:, :, 7])
     assert torch.equal(vb2[:, :, T - 1], vb[:, :, 7]) and torch.equal(vm2[:, :, T - 1], vm[:, :, 7])
+    # grouped queries in the benchmark's shape: the 32 query heads over the caches of the first 8 heads, 4 token splits;
+    # sampled (sequence, key/value head) groups against the oracle
+    grp, Hkv, splits = 4, H // 4, 4
+    gkb, gkm, gvb, gvm = (a[:, :Hkv].contiguous() for a in (kb, km, vb, vm))
+    outg = E.ecco_kv_attend_gqa(mk, mv, t16(q, dev), gkb, gkm, gvb, gvm, ti32(seq, dev), B, H, Hkv, T, n_splits=splits).cpu().numpy()
+    assert np.isfinite(outg).all()
+    for b, hk in [(0, 0), (2, 7), (3, 3), (4, 5), (5, 1), (7, 6)]:
+        want = oracle.kv_attend_gqa(mk.centroids, mk.code_lens, mv.centroids, mv.code_lens,
+                                    np.ascontiguousarray(q[b, hk * grp:(hk + 1) * grp]).view(np.uint16),
+                                    gkb[b, hk].cpu().numpy(), np_meta(gkm[b, hk]), gvb[b, hk].cpu().numpy(), np_meta(gvm[b, hk]),
+                                    one * seq[b], 1, grp, 1, T)
+        for j in range(grp):
+            assert rel_l2(outg[b, hk * grp + j], want[0, j]) <= REL_L2, (b, hk, j)
+    # the min/max selector over the whole K cache (1 M groups, the bulk launch the benchmark times): sampled groups
+    mb, mm = E.ecco_encode_minmax(mk, t16(k, dev))
+    rows = np.random.default_rng(7).choice(B * H * T, 2048, replace=False)
+    ob, om = oracle.encode_minmax(mk.centroids, mk.code_lens, k.reshape(-1, 128)[rows].view(np.uint16))
+    assert np.array_equal(np_blocks(mb)[rows], ob) and np.array_equal(np_meta(mm)[rows], om)
+    kb3, km3, vb3, vm3 = kb.clone(), km.clone(), vb.clone(), vm.clone()
+    E.ecco_kv_append_minmax(mk, mv, t16(kn, dev), t16(vn, dev), kb3, km3, vb3, vm3, ti32(pos, dev), B, H, T)
+    at = (np.arange(B * H) * T + 7)
+    assert torch.equal(kb3[:, :, T - 1].reshape(-1, 64), mb[torch.from_numpy(at).to(dev)])  # token 7's block by the bulk encoder
 
 
 def test_repeated_launches_are_identical(dev, oracle):
