@@ -262,3 +262,15 @@ void pb_decode(const pb_model* m, const uint8_t* blocks, size_t n_groups, uint16
         if (n_out_out) n_out_out[g] = (uint8_t)n_out;
     }
 }
+
+// the consumer of the decompressed weights (Section 2.1: decode-phase projections are matrix-vector products)
+void pb_gemv(const pb_model* m, const uint8_t* blocks, int rows, int cols, const uint16_t* x, double* y) {
+    const int gpr = cols / G;
+    std::vector<uint16_t> w((size_t)cols);
+    for (int r = 0; r < rows; ++r) {
+        pb_decode(m, blocks + (size_t)r * gpr * PB_BLOCK_BYTES, (size_t)gpr, w.data(), nullptr, nullptr);
+        double acc = 0.0;
+        for (int c = 0; c < cols; ++c) acc += (double)oracle_h2f(w[(size_t)c]) * (double)oracle_h2f(x[c]);
+        y[r] = acc;
+    }
+}

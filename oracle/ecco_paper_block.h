@@ -45,6 +45,9 @@ void pb_encode(const pb_model* m, const uint16_t* src, size_t n_groups, uint8_t*
  * how many outlier entries followed */
 void pb_decode(const pb_model* m, const uint8_t* blocks, size_t n_groups, uint16_t* dst, uint8_t* n_coded, uint8_t* n_outliers);
 
+/* y[r] = sum_c w[r][c] * x[c] over the decoded weights (rows x cols, cols % 128 == 0, blocks row-major), in double */
+void pb_gemv(const pb_model* m, const uint8_t* blocks, int rows, int cols, const uint16_t* x, double* y);
+
 #ifdef __cplusplus
 }
 #endif

@@ -72,3 +72,13 @@ def decode(m: Model, blocks):
     lib().pb_decode(C.byref(m.c), blocks.ctypes.data_as(C.c_void_p), C.c_size_t(n), dst.ctypes.data_as(C.c_void_p),
                     n_coded.ctypes.data_as(C.c_void_p), n_out.ctypes.data_as(C.c_void_p))
     return dst, n_coded, n_out
+
+
+def gemv(m: Model, blocks, rows: int, cols: int, x_u16):
+    blocks = np.ascontiguousarray(blocks, dtype=np.uint8).reshape(-1, BLOCK_BYTES)
+    x = np.ascontiguousarray(x_u16, dtype=np.uint16).reshape(-1)
+    assert cols % GROUP == 0 and x.size == cols and blocks.shape[0] == rows * (cols // GROUP)
+    y = np.zeros(rows, np.float64)
+    lib().pb_gemv(C.byref(m.c), blocks.ctypes.data_as(C.c_void_p), C.c_int(rows), C.c_int(cols), x.ctypes.data_as(C.c_void_p),
+                  y.ctypes.data_as(C.c_void_p))
+    return y

@@ -229,3 +229,16 @@ def test_clipping_is_literal_truncation(pb):
     assert pb.verify_model(pb.Model(cent.view(np.uint16), lens2, np.array([1], np.uint8), -7)) == 6
     lens2 = lens.copy(); lens2[0, 2, 0] = 5
     assert pb.verify_model(pb.Model(cent.view(np.uint16), lens2, np.array([1], np.uint8), -7)) == 7
+
+
+def test_gemv_unit_vectors_pick_decoded_columns(pb):
+    m = _model(pb, S=3, texp=-8, seed=7)
+    rows, cols = 5, 384
+    x = _groups(8, rows * 3).reshape(rows, cols)
+    blocks = pb.encode(m, x.view(np.uint16))
+    dec = pb.decode(m, blocks)[0].view(np.float16).reshape(rows, cols).astype(np.float64)
+    for j in (0, 127, 128, 300, 383):
+        e = np.zeros(cols, np.float16); e[j] = 1
+        assert np.array_equal(pb.gemv(m, blocks, rows, cols, e.view(np.uint16)), dec[:, j])
+    v = np.random.default_rng(1).normal(0, 1, cols).astype(np.float16)
+    assert np.allclose(pb.gemv(m, blocks, rows, cols, v.view(np.uint16)), dec @ v.astype(np.float64), rtol=1e-12, atol=1e-15)
