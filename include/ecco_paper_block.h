@@ -79,6 +79,14 @@ int ecco_pb_encode(const ecco_pb_model* m, const uint16_t* src_fp16, size_t n_gr
  * gives them.  Errors: EINVAL, ESHAPE (n_groups >= 2^31), EALIGN, EHIP. */
 int ecco_pb_decode(const ecco_pb_model* m, const void* blocks, size_t n_groups, uint16_t* dst_fp16, void* stream);
 
+/* GPU.  The decode fused into the consuming matrix-vector product (Section 2.1), batch 1: the FP16 weights never
+ * reach HBM.  W = rows x cols as rows * (cols / 128) blocks, row-major; x device, cols FP16, 16-byte aligned; y device,
+ * rows FP32: y[r] = sum_c W[r][c] * x[c], FP32 accumulation in a fixed order (results are reproducible; no device
+ * memory beyond the arguments is used).  cols % 128 == 0, cols <= 65536.
+ * Errors: EINVAL, ESHAPE, EALIGN, EHIP. */
+int ecco_pb_decode_gemv(const ecco_pb_model* m, const void* blocks, int rows, int cols, const uint16_t* x, float* y,
+                        void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -23,7 +23,7 @@ EXPORTS = [
     "ecco_kv_attend_gqa", "ecco_kv_attend_gqa_workspace",
     "ecco_pb_fit", "ecco_pb_model_create", "ecco_pb_model_S", "ecco_pb_model_texp", "ecco_pb_model_centroids",
     "ecco_pb_model_code_lens", "ecco_pb_model_kp_lens", "ecco_pb_model_to_device", "ecco_pb_model_free",
-    "ecco_pb_encode", "ecco_pb_decode",
+    "ecco_pb_encode", "ecco_pb_decode", "ecco_pb_decode_gemv",
 ]
 
 
@@ -76,6 +76,7 @@ def lib():
         L.ecco_pb_model_to_device.argtypes = [vp, i32]
         L.ecco_pb_encode.argtypes = [vp, vp, sz, vp, vp]
         L.ecco_pb_decode.argtypes = [vp, vp, sz, vp, vp]
+        L.ecco_pb_decode_gemv.argtypes = [vp, vp, i32, i32, vp, vp, vp]
         L.ecco_act_decode.argtypes = [vp, sz, vp, vp]
         _lib = L
     return _lib
@@ -367,3 +368,12 @@ def ecco_pb_decode(m: PbModel, blocks, dst=None):
         dst = torch.empty((n, GROUP), dtype=torch.float16, device=blocks.device)
     _check(lib().ecco_pb_decode(m.handle, _dp(blocks), n, _dp(dst), _stream()), "ecco_pb_decode")
     return dst
+
+
+def ecco_pb_decode_gemv(m: PbModel, blocks, rows: int, cols: int, x, y=None):
+    """x: CUDA FP16 [cols]; returns y FP32 [rows]."""
+    import torch
+    if y is None:
+        y = torch.empty((rows,), dtype=torch.float32, device=x.device)
+    _check(lib().ecco_pb_decode_gemv(m.handle, _dp(blocks), rows, cols, _dp(x), _dp(y), _stream()), "ecco_pb_decode_gemv")
+    return y

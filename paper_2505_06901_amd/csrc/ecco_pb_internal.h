@@ -23,7 +23,7 @@ constexpr int kOutlierBits = 15;
 // Device memory of a model, one allocation, in 32-bit words:
 //   lut     [S * 4][256] bytes   8-bit peek -> (index << 4) | code length, one table per (pattern, codebook)
 //   kplut   [256] 16-bit         8-bit peek -> (pattern << 8) | code length of the pattern id; no match: (S - 1, 8)
-//   cent    [S][16] FP16         centroids; entry 15 unused (zero)
+//   cent    [S][16] FP16         centroids; entry 15 = 1.0 (index 15 stands for the scale itself)
 //   fp8     [256] FP16           value of every 8-bit float times 2^texp
 //   enc     [S * 4][16]          code | length << 16 per index
 //   kpenc   [S] (padded to 4)    code | length << 16 per pattern id

@@ -28,6 +28,8 @@ namespace {
 
 using namespace ecco_pb;
 
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+
 #define ECCO_HIP_CHECK(expr) do { if ((expr) != hipSuccess) return ECCO_EHIP; } while (0)
 
 constexpr int kSlot = kBlockWords + 1;    // LDS words per staged block; the last one is a zero pad
@@ -168,11 +170,6 @@ __global__ __launch_bounds__(kDecThreads) void pb_decode_kernel(const uint32_t* 
     }
 }
 
-// ---- encoder ---------------------------------------------------------------------------------------------------
-constexpr int kEncThreads = 256;
-constexpr int kEncWaves = kEncThreads / 64;
-constexpr int kBitWords = kBlockWords + 2;
-
 template <int kCtrl>
 __device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
     return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, kCtrl, 0xF, 0xF, true);
@@ -198,6 +195,150 @@ __device__ __forceinline__ float wave_tree_sum(float t) {
     t = __fadd_rn(t, g(dpp_u32<0x140>(f(t))));
     return __fadd_rn(__fadd_rn(g(lane_u32(f(t), 0)), g(lane_u32(f(t), 16))), __fadd_rn(g(lane_u32(f(t), 32)), g(lane_u32(f(t), 48))));
 }
+
+// ---- decode fused into the matrix-vector product --------------------------------------------------------------------
+// y = W x without writing W: a workgroup owns a band of rows (its blocks are consecutive in memory); a wavefront
+// takes 64 consecutive blocks of the band at a time, one per lane, exactly as the decoder does.  The lane keeps the
+// 128 activations of its block's column group in 64 registers and adds centroid * x for every value that is present
+// (index 15 counts as +-1); the sum is multiplied by |scale| at the end.  The 128 indices are kept as nibbles in 16
+// registers: when padded entries follow, the lane takes back centroid * x at their positions and adds the entries'
+// own values (times x) instead -- from the last entry to the first, each position once, which is what a sequential
+// reader of the block ends up with.  Per-block sums go to LDS, and each row's blocks are added in a fixed tree.
+constexpr int kGvThreads = 512;
+constexpr int kGvWaves = kGvThreads / 64;
+constexpr int kGvPartFloats = 2048;      // per-block sums of a band: band rows x column groups
+constexpr int kGvXMaxCols = 8192;        // activations are staged in LDS up to this many columns, read through L2 beyond
+constexpr int kNibStride = 17;           // words per lane of the index store (16 + 1)
+
+inline size_t gv_lds_bytes(int S, int cols) {
+    return (DevLayout{S}.decode_words() + (size_t)kGvWaves * (kPayWords + 64 * kNibStride) + kGvPartFloats +
+            (cols <= kGvXMaxCols ? cols / 2 : 0)) * 4;
+}
+
+template <bool kXLds>
+__global__ __launch_bounds__(kGvThreads) void pb_gemv_kernel(const uint32_t* __restrict__ dev, int S,
+                                                             const uint4* __restrict__ blocks, int rows, int gpr, int band,
+                                                             const uint4* __restrict__ x, float* __restrict__ y) {
+    extern __shared__ __align__(16) uint32_t smem[];
+    const DevLayout D{S};
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint8_t* lut = reinterpret_cast<const uint8_t*>(smem + D.lut());
+    const uint16_t* kplut = reinterpret_cast<const uint16_t*>(smem + D.kplut());
+    const uint16_t* cent = reinterpret_cast<const uint16_t*>(smem + D.cent());
+    const uint16_t* fp8 = reinterpret_cast<const uint16_t*>(smem + D.fp8());
+    uint32_t* pay = smem + D.decode_words() + wave * (kPayWords + 64 * kNibStride);
+    uint32_t* nibs = pay + kPayWords + lane * kNibStride;
+    float* part = reinterpret_cast<float*>(smem + D.decode_words() + kGvWaves * (kPayWords + 64 * kNibStride));
+    uint32_t* xl = reinterpret_cast<uint32_t*>(part + kGvPartFloats);
+
+    const int r0 = blockIdx.x * band, nrows = min(band, rows - r0);
+    const size_t base = (size_t)r0 * gpr;                 // first block of the band
+    const int n_blocks = nrows * gpr;                     // <= kGvPartFloats
+    const int n_units = (n_blocks + kUnit - 1) / kUnit;
+    PieceLoad pre;
+    if (wave < n_units) pre = load_pieces(blocks + base * 4, (size_t)wave * kUnit, (size_t)n_blocks, lane);
+    stage_words(smem, dev, (int)D.decode_words());
+    if (kXLds)
+        for (int i = threadIdx.x; i < gpr * 16; i += kGvThreads) reinterpret_cast<uint4*>(xl)[i] = x[i];
+    pay[lane * kSlot + kBlockWords] = 0u;
+    if (lane < 4) pay[kUnit * kSlot + lane] = 0u;
+    __syncthreads();
+
+    for (int u = wave; u < n_units; u += kGvWaves) {
+        wave_lds_fence();
+        store_pieces(pay, pre, lane);
+        wave_lds_fence();
+        if (u + kGvWaves < n_units) pre = load_pieces(blocks + base * 4, (size_t)(u + kGvWaves) * kUnit, (size_t)n_blocks, lane);
+        const int bl = u * kUnit + lane;                  // block of the band; slots past the band hold a copy of its last block
+        const int cg = min(bl, n_blocks - 1) % gpr;       // its column group
+        const uint4* xsrc = kXLds ? reinterpret_cast<const uint4*>(xl) + cg * 16 : x + (size_t)cg * 16;
+        uint32_t xs[kGroup / 4];  // the activations of half a column group at a time
+        const uint32_t* w = pay + lane * kSlot;
+        const uint32_t w0 = w[0];
+        const uint32_t kpe = kplut[(w0 >> 14) & 0xFFu];
+        const uint32_t p = kpe >> 8;
+        const uint32_t sv = fp8[w0 >> 24];
+        const uint8_t* tab = lut + (p * kBooks + ((w0 >> 22) & 3u)) * 256u;
+        const uint16_t* cp = cent + p * 16u;
+        uint32_t fetch = 10u + (kpe & 0xFFu), reach = fetch;
+        float acc = 0.0f, acc15 = 0.0f;
+        uint32_t nib[kGroup / 8];
+#pragma unroll
+        for (int i0 = 0; i0 < kGroup; i0 += 4) {
+            if ((i0 & 63) == 0) {
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const uint4 v = xsrc[(i0 >> 6) * 8 + k];
+                    xs[4 * k] = v.x; xs[4 * k + 1] = v.y; xs[4 * k + 2] = v.z; xs[4 * k + 3] = v.w;
+                }
+            }
+            const uint32_t wi = fetch >> 5;
+            uint64_t win = (((uint64_t)w[wi] << 32) | (uint64_t)w[wi + 1]) << (fetch & 31u);
+            uint32_t used = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int i = i0 + j;
+                const uint32_t e = tab[(uint32_t)(win >> 56)];
+                const uint32_t len = e & 15u, idx = e >> 4;
+                reach += len;
+                used += len;
+                win <<= len;
+                const bool present = reach <= (uint32_t)kBlockBits;
+                // FP16 operands go straight into mixed-precision multiply-adds: the activations stay packed in their
+                // registers (converted ahead of time they would need 128)
+                const half2_t x2 = __builtin_bit_cast(half2_t, xs[(i & 63) >> 1]);
+                const _Float16 xh = (i & 1) ? x2[1] : x2[0];
+                const _Float16 ch = __builtin_bit_cast(_Float16, (unsigned short)(present ? (uint32_t)cp[idx] : 0u));
+                const _Float16 one15 = __builtin_bit_cast(_Float16, (unsigned short)((present && idx == 15u) ? 0x3C00u : 0u));
+                acc = fmaf((float)ch, (float)xh, acc);
+                acc15 = fmaf((float)one15, (float)xh, acc15);
+                nib[i >> 3] = (i & 7) ? ((nib[i >> 3] << 4) | idx) : idx;
+                if ((i & 3) == 3) asm volatile("" : "+v"(acc), "+v"(acc15), "+v"(nib[i >> 3]), "+v"(xs[(i & 63) >> 1]));  // keeps the arithmetic next to its table reads
+            }
+            fetch = min(fetch + used, (uint32_t)kBlockBits);
+        }
+        // index 15 was added as +1: with a negative scale it is -1
+        if (sv & 0x8000u) acc -= 2.0f * acc15;
+        float extra = 0.0f;  // padded entries: absolute values, not multiples of the scale
+        const uint32_t n_out = reach <= (uint32_t)kBlockBits ? ((uint32_t)kBlockBits - reach) / kOutlierBits : 0u;
+        if (__builtin_amdgcn_ballot_w64(n_out > 0u) != 0ull) {
+#pragma unroll
+            for (int k = 0; k < kGroup / 8; ++k) nibs[k] = nib[k];
+            const uint16_t* xh = kXLds ? reinterpret_cast<const uint16_t*>(xl) + cg * kGroup : reinterpret_cast<const uint16_t*>(x) + (size_t)cg * kGroup;
+            uint64_t seen_lo = 0, seen_hi = 0;
+            for (int j = (int)n_out - 1; j >= 0; --j) {
+                const uint32_t at = reach + (uint32_t)j * kOutlierBits, wi = at >> 5;
+                const uint64_t win = (((uint64_t)w[wi] << 32) | (uint64_t)w[wi + 1]) << (at & 31u);
+                const uint32_t entry = (uint32_t)(win >> 49), pos = entry >> 8;
+                const uint64_t bit = 1ull << (pos & 63u);
+                const bool dup = ((pos < 64u ? seen_lo : seen_hi) & bit) != 0ull;
+                if (pos < 64u) seen_lo |= bit; else seen_hi |= bit;
+                if (dup) continue;  // a later entry for this position has been applied already
+                const uint32_t idx = (nibs[pos >> 3] >> (4u * (7u - (pos & 7u)))) & 15u;
+                const float xi = __half2float(__ushort_as_half(xh[pos]));
+                float c = __half2float(__ushort_as_half(cp[idx]));
+                if (idx == 15u && (sv & 0x8000u)) c = -c;
+                acc = fmaf(-c, xi, acc);
+                extra = fmaf(__half2float(__ushort_as_half(fp8[entry & 0xFFu])), xi, extra);
+            }
+        }
+        if (bl < n_blocks) part[bl] = fmaf(acc, __half2float(__ushort_as_half((unsigned short)(sv & 0x7FFFu))), extra);
+    }
+    __syncthreads();
+    // row sums: the blocks of a row in a fixed order (lane-strided partial sums, then the wavefront tree)
+    for (int r = wave; r < nrows; r += kGvWaves) {
+        float sum = 0.0f;
+        for (int c = lane; c < gpr; c += 64) sum += part[r * gpr + c];
+        sum = wave_tree_sum(sum);
+        if (lane == 0) y[r0 + r] = sum;
+    }
+}
+
+// ---- encoder ---------------------------------------------------------------------------------------------------
+constexpr int kEncThreads = 256;
+constexpr int kEncWaves = kEncThreads / 64;
+constexpr int kBitWords = kBlockWords + 2;
 
 __device__ __forceinline__ float half_bits_f(uint32_t bits) { return __half2float(__ushort_as_half((unsigned short)bits)); }
 
@@ -366,6 +507,28 @@ int ecco_pb_encode(const ecco_pb_model* m, const uint16_t* src, size_t n_groups,
                        inv_tscale, reinterpret_cast<const uint32_t*>(src), n_groups, static_cast<uint32_t*>(blocks));
     ECCO_HIP_CHECK(hipGetLastError());
     return ECCO_OK;
+}
+
+int ecco_pb_decode_gemv(const ecco_pb_model* m, const void* blocks, int rows, int cols, const uint16_t* x, float* y, void* stream) {
+    if (model_ready(m) != ECCO_OK || !blocks || !x || !y) return ECCO_EINVAL;
+    if (rows <= 0 || cols <= 0 || cols % kGroup != 0 || cols > 65536) return ECCO_ESHAPE;
+    if (!aligned(blocks, 64) || !aligned(x, 16) || !aligned(y, 4)) return ECCO_EALIGN;
+    const int gpr = cols / kGroup;
+    // a band of rows per workgroup: about one band per compute unit, at most kGvPartFloats blocks
+    int band = std::max(1, (rows + 255) / 256);
+    band = std::min(band, std::max(1, kGvPartFloats / gpr));
+    const int grid = (rows + band - 1) / band;
+    const size_t lds = gv_lds_bytes(m->S, cols);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    auto launch = [&](auto kernel) -> int {
+        const int rc = allow_lds(kernel, lds);
+        if (rc != ECCO_OK) return rc;
+        hipLaunchKernelGGL(kernel, dim3(grid), dim3(kGvThreads), lds, st, m->dev, m->S, static_cast<const uint4*>(blocks), rows, gpr, band,
+                           reinterpret_cast<const uint4*>(x), y);
+        ECCO_HIP_CHECK(hipGetLastError());
+        return ECCO_OK;
+    };
+    return cols <= kGvXMaxCols ? launch(pb_gemv_kernel<true>) : launch(pb_gemv_kernel<false>);
 }
 
 int ecco_pb_decode(const ecco_pb_model* m, const void* blocks, size_t n_groups, uint16_t* dst, void* stream) {

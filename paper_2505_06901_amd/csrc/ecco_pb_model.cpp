@@ -85,7 +85,10 @@ void build_image(const ecco_pb_model* m, uint32_t* img) {
         for (uint32_t j = 0; j < (1u << (8 - l)); ++j) kplut[((uint32_t)m->kp_codes[p] << (8 - l)) + j] = (uint16_t)((p << 8) | l);
     }
     for (int p = 0; p < m->S; ++p)
+    {
         for (int k = 0; k < kCent; ++k) cent[p * 16 + k] = m->cent[p * kCent + k];
+        cent[p * 16 + 15] = 0x3C00;  // index 15 stands for the scale itself: 1.0 times the scale
+    }
     for (int b = 0; b < 256; ++b) fp8[b] = float_to_half_bits((float)std::ldexp(fp8_value((uint8_t)b), m->texp));  // exact
 }
 

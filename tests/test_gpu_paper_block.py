@@ -106,3 +106,40 @@ def test_full_projection_sampled(pb, dev):
     assert (((dec >> 10) & 0x1F) != 31).all()
     top = float(np.abs(w.astype(np.float32)).max())
     assert float(np.abs(dec.view(np.float16).astype(np.float32)).max()) <= top * 1.07
+
+
+def test_fused_gemv_matches_oracle(pb, dev):
+    """Decode fused into the matrix-vector product: rel-L2 <= 1e-3 against the double-precision oracle; ragged shapes, a band
+    that ends inside a pass of 64 blocks, blocks with clipped values and padded entries, arbitrary bytes."""
+    om = _model(pb, S=6, texp=-9, seed=21, skew=2.6)
+    m = _both(pb, om)
+    rng = np.random.default_rng(22)
+    for rows, gpr in [(1, 1), (5, 3), (17, 32), (40, 33), (300, 2), (64, 64), (9, 70), (700, 5)]:
+        cols = gpr * 128
+        w = _groups(rows * 7 + gpr, rows * gpr, scale=2.0 ** -9 * 30).reshape(rows, cols)
+        blocks = pb.encode(om, w.view(np.uint16))
+        x = W.activation(1, cols, 200 + gpr).reshape(cols)
+        want = pb.gemv(om, blocks, rows, cols, x.view(np.uint16))
+        got = E.ecco_pb_decode_gemv(m, torch.from_numpy(blocks).to(dev), rows, cols, _t16(x, dev)).cpu().numpy()
+        err = np.linalg.norm(got - want) / max(np.linalg.norm(want), 1e-300)
+        assert got.shape == (rows,) and err <= 1e-3, (rows, gpr, err)
+    # arbitrary bytes (repeated positions among the padded entries included): same values as a sequential reader
+    rows, gpr = 37, 4
+    junk = rng.integers(0, 256, (rows * gpr, 64), dtype=np.uint8)
+    x = W.activation(1, gpr * 128, 300).reshape(-1)
+    want = pb.gemv(om, junk, rows, gpr * 128, x.view(np.uint16))
+    got = E.ecco_pb_decode_gemv(m, torch.from_numpy(junk).to(dev), rows, gpr * 128, _t16(x, dev)).cpu().numpy()
+    assert np.linalg.norm(got - want) / np.linalg.norm(want) <= 1e-3
+    # unit vectors pick single decoded columns, padded entries included
+    w = _groups(5, 8 * 2, scale=2.0 ** -9 * 30).reshape(8, 256)
+    blocks = pb.encode(om, w.view(np.uint16))
+    dec, n_coded, n_out = pb.decode(om, blocks)
+    assert (n_out > 0).any()
+    dec = dec.view(np.float16).reshape(8, 256).astype(np.float64)
+    for j in (0, 100, 128, 255):
+        e = np.zeros(256, np.float16); e[j] = 1
+        got = E.ecco_pb_decode_gemv(m, torch.from_numpy(blocks).to(dev), 8, 256, _t16(e, dev)).cpu().numpy()
+        assert np.allclose(got, dec[:, j], rtol=2e-3, atol=1e-9), j
+    with pytest.raises(E.EccoError) as e:
+        E.ecco_pb_decode_gemv(m, torch.from_numpy(blocks).to(dev), 8, 200, _t16(np.zeros(200, np.float16), dev))
+    assert e.value.status == -2
