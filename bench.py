@@ -74,7 +74,7 @@ def main():
     ap.add_argument("--eager", action="store_true", help="launch every call from Python with its own event pair instead of replaying a HIP graph")
     ap.add_argument("--only", default="", help="comma list of rows to run (kv_append,decode,gemv1,gemv8,gemv16,kv_attend; "
                     "on request only: kv_append_minmax, encode, encode_minmax -- the bulk encoders run over the K cache -- "
-                    "act_encode, act_decode -- the 2x activation codec on 32768 x 4096 activations -- and pb_encode, pb_decode -- the self-contained "
+                    "act_encode, act_decode -- the 2x activation codec on 32768 x 4096 activations -- and pb_encode, pb_decode, pb_gemv1 -- the self-contained "
                     "block format on the workload's weight matrix)")
     ap.add_argument("--gqa-group", type=int, default=4, help="query heads per key/value head of the kv_attend_gqa row (on request: --only kv_attend_gqa)")
     ap.add_argument("--gqa-splits", type=int, default=0, help="token splits of the kv_attend_gqa row (0: enough to give every compute unit a workgroup)")
@@ -121,7 +121,7 @@ def main():
     kc = W.CONFIGS["kv"]
     B, H, T = kc["batch"], kc["heads"], kc["tokens"]
     extra_rows = [r for r in ("kv_append_minmax", "encode", "encode_minmax", "kv_attend_gqa") if r in only]
-    pb_rows = [r for r in ("pb_encode", "pb_decode") if r in only]
+    pb_rows = [r for r in ("pb_encode", "pb_decode", "pb_gemv1") if r in only]
     act_rows = [r for r in ("act_encode", "act_decode") if r in only]
     if act_rows:
         act_rows.append("copy_reference")  # a plain device copy of the same FP16 tensor: the practical HBM ceiling beside the codec
@@ -220,6 +220,8 @@ def main():
             E.ecco_kv_append_minmax(mk, mv, k_new, v_new, kbs[c], kms[c], vbs[c], vms[c], seq_app, B, H, T)
         elif row == "pb_encode":
             E.ecco_pb_encode(pbm, w_dev, pb_blocks[next_copy(len(pb_blocks))])
+        elif row == "pb_gemv1":
+            E.ecco_pb_decode_gemv(pbm, pb_blocks[next_copy(len(pb_blocks))], rows, cols, xs[1], ys[1])
         elif row == "pb_decode":
             E.ecco_pb_decode(pbm, pb_blocks[next_copy(len(pb_blocks))], pb_out)
         elif row == "act_encode":
@@ -376,6 +378,10 @@ def main():
             d["GBps_compressed"] = comp_bytes / (ms[r] * 1e-3) / 1e9
         elif r.startswith("kv_append"):
             d["groups_per_s"] = 2 * B * H / (ms[r] * 1e-3)
+        elif r == "pb_gemv1":
+            d["GBps_compressed"] = n_groups * 64 / (ms[r] * 1e-3) / 1e9   # 64-byte blocks, nothing beside them
+            d["pct_hbm_peak"] = 100.0 * d["GBps_compressed"] / HBM_PEAK_GBS
+            d["gemv_tokens_per_s"] = 1.0 / (ms[r] * 1e-3)
         elif r.startswith("pb_"):
             d["groups_per_s"] = n_groups / (ms[r] * 1e-3)
             d["GBps_total_traffic"] = n_groups * (64 + 256) / (ms[r] * 1e-3) / 1e9   # 64-byte block + 256 bytes of FP16

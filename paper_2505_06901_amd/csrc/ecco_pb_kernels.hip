@@ -21,6 +21,7 @@
 
 #include <algorithm>
 #include <cstdint>
+#include <type_traits>
 
 #include "ecco_pb_internal.h"
 
@@ -38,6 +39,8 @@ constexpr int kPayWords = kUnit * kSlot + 4;
 constexpr int kPassValues = 32;           // values per lane between two write-outs
 constexpr int kImgStride = kPassValues / 2 + 1;
 constexpr int kImgWords = 64 * kImgStride;
+// the header takes at most 18 bits and a code at most 8: value i ends at or before bit 18 + 8 (i + 1), inside the block for i <= 60
+constexpr int kAlwaysPresent = (kBlockBits - 18) / kMaxLen;
 constexpr int kDecThreads = 512;
 constexpr int kDecWaves = kDecThreads / 64;
 
@@ -262,7 +265,7 @@ __global__ __launch_bounds__(kGvThreads) void pb_gemv_kernel(const uint32_t* __r
         const uint8_t* tab = lut + (p * kBooks + ((w0 >> 22) & 3u)) * 256u;
         const uint16_t* cp = cent + p * 16u;
         uint32_t fetch = 10u + (kpe & 0xFFu), reach = fetch;
-        float acc = 0.0f, acc15 = 0.0f;
+        float acc = 0.0f;
         uint32_t nib[kGroup / 8];
 #pragma unroll
         for (int i0 = 0; i0 < kGroup; i0 += 4) {
@@ -275,37 +278,51 @@ __global__ __launch_bounds__(kGvThreads) void pb_gemv_kernel(const uint32_t* __r
             }
             const uint32_t wi = fetch >> 5;
             uint64_t win = (((uint64_t)w[wi] << 32) | (uint64_t)w[wi + 1]) << (fetch & 31u);
-            uint32_t used = 0;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int i = i0 + j;
                 const uint32_t e = tab[(uint32_t)(win >> 56)];
                 const uint32_t len = e & 15u, idx = e >> 4;
                 reach += len;
-                used += len;
                 win <<= len;
-                const bool present = reach <= (uint32_t)kBlockBits;
                 // FP16 operands go straight into mixed-precision multiply-adds: the activations stay packed in their
                 // registers (converted ahead of time they would need 128)
                 const half2_t x2 = __builtin_bit_cast(half2_t, xs[(i & 63) >> 1]);
                 const _Float16 xh = (i & 1) ? x2[1] : x2[0];
-                const _Float16 ch = __builtin_bit_cast(_Float16, (unsigned short)(present ? (uint32_t)cp[idx] : 0u));
-                const _Float16 one15 = __builtin_bit_cast(_Float16, (unsigned short)((present && idx == 15u) ? 0x3C00u : 0u));
-                acc = fmaf((float)ch, (float)xh, acc);
-                acc15 = fmaf((float)one15, (float)xh, acc15);
-                nib[i >> 3] = (i & 7) ? ((nib[i >> 3] << 4) | idx) : idx;
-                if ((i & 3) == 3) asm volatile("" : "+v"(acc), "+v"(acc15), "+v"(nib[i >> 3]), "+v"(xs[(i & 63) >> 1]));  // keeps the arithmetic next to its table reads
+                uint32_t cb = cp[idx], keep = idx;
+                if (i >= kAlwaysPresent) {  // only these values can lie beyond the cut: they then count as zero and as index 0
+                    const bool present = reach <= (uint32_t)kBlockBits;
+                    cb = present ? cb : 0u;
+                    keep = present ? idx : 0u;
+                }
+                acc = fmaf((float)__builtin_bit_cast(_Float16, (unsigned short)cb), (float)xh, acc);
+                nib[i >> 3] = (i & 7) ? ((nib[i >> 3] << 4) | keep) : keep;
+                if ((i & 3) == 3) asm volatile("" : "+v"(acc), "+v"(nib[i >> 3]), "+v"(xs[(i & 63) >> 1]));  // keeps the arithmetic next to its table reads
             }
-            fetch = min(fetch + used, (uint32_t)kBlockBits);
+            fetch = min(reach, (uint32_t)kBlockBits);
         }
-        // index 15 was added as +1: with a negative scale it is -1
-        if (sv & 0x8000u) acc -= 2.0f * acc15;
+        const uint16_t* xh16 = kXLds ? reinterpret_cast<const uint16_t*>(xl) + cg * kGroup : reinterpret_cast<const uint16_t*>(x) + (size_t)cg * kGroup;
+        if (sv & 0x8000u) {
+            // index 15 was added as +1 times its activation; the scale is negative, so it is -1: find the positions with
+            // index 15 (all four bits of the nibble set; an absent value was recorded as index 0, unless it really is
+            // index 0 ... which is not 15 either) and take twice their activations back
+#pragma unroll
+            for (int k = 0; k < kGroup / 8; ++k) {
+                uint32_t hit = nib[k] & (nib[k] >> 1) & (nib[k] >> 2) & (nib[k] >> 3) & 0x11111111u;
+                while (hit) {
+                    const uint32_t b = 31u - (uint32_t)__builtin_clz(hit);   // bit 4 * (7 - position in the register)
+                    hit &= ~(1u << b);
+                    const uint32_t pos = 8u * k + (7u - (b >> 2));
+                    acc = fmaf(-2.0f, __half2float(__ushort_as_half(xh16[pos])), acc);
+                }
+            }
+        }
         float extra = 0.0f;  // padded entries: absolute values, not multiples of the scale
         const uint32_t n_out = reach <= (uint32_t)kBlockBits ? ((uint32_t)kBlockBits - reach) / kOutlierBits : 0u;
         if (__builtin_amdgcn_ballot_w64(n_out > 0u) != 0ull) {
 #pragma unroll
             for (int k = 0; k < kGroup / 8; ++k) nibs[k] = nib[k];
-            const uint16_t* xh = kXLds ? reinterpret_cast<const uint16_t*>(xl) + cg * kGroup : reinterpret_cast<const uint16_t*>(x) + (size_t)cg * kGroup;
+            const uint16_t* xh = xh16;
             uint64_t seen_lo = 0, seen_hi = 0;
             for (int j = (int)n_out - 1; j >= 0; --j) {
                 const uint32_t at = reach + (uint32_t)j * kOutlierBits, wi = at >> 5;

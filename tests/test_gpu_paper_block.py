@@ -102,6 +102,14 @@ def test_full_projection_sampled(pb, dev):
     want, n_coded, n_out = pb.decode(om, want_blocks)
     assert np.array_equal(dec[rows], want)
     assert (n_coded < 128).any() and (n_out > 0).any()
+    # the fused matrix-vector product on the whole matrix: sampled rows against the oracle, every row against the GPU's own decode
+    x = W.activation(1, 4096, 101).reshape(-1)
+    y = E.ecco_pb_decode_gemv(m, torch.from_numpy(blocks).to(dev), 4096, 4096, _t16(x, dev)).cpu().numpy()
+    ref = dec.view(np.float16).reshape(4096, 4096).astype(np.float64) @ x.astype(np.float64)
+    assert np.linalg.norm(y - ref) / np.linalg.norm(ref) <= 1e-3
+    for r in (0, 1, 2047, 4095):
+        want = pb.gemv(om, blocks[r * 32:(r + 1) * 32], 1, 4096, x.view(np.uint16))
+        assert abs(y[r] - want[0]) <= 1e-3 * max(abs(want[0]), np.abs(ref).mean())
     # whole-output properties: finite values, bounded by the tensor's largest magnitude times the FP8 rounding slack
     assert (((dec >> 10) & 0x1F) != 31).all()
     top = float(np.abs(w.astype(np.float32)).max())
