@@ -38,6 +38,13 @@ __device__ __forceinline__ uint32_t dequant_bits(uint32_t cent_bits, float s) {
     return __half_as_ushort(__float2half_rn(half_bits_f(cent_bits) * s));
 }
 
+// orders the LDS accesses of one wavefront (private buffers need no workgroup barrier)
+__device__ inline void wave_lds_fence() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // ---- LDS tables -------------------------------------------------------------------------------------
 struct Tables {
     const uint32_t* lut;      // [S][256]
@@ -404,9 +411,8 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_kernel(const uint32_t* __re
 // images and 32-byte pieces measured slower, also on small inputs).
 constexpr int kDecWaves = 12;
 struct DecCfg {
-    static constexpr int kPass = 32;                               // values per chain and pass
-    static constexpr int kPieces = kPass / 8;                      // 16-byte pieces per segment and pass
-    static constexpr int kImageWords = 64 * kPieces * 4;           // 64 segments
+    static constexpr int kLinePieces = kHalf / 8;                  // 16-byte pieces of a chain's 128 output bytes
+    static constexpr int kImageWords = 32 * kLinePieces * 4;       // 32 lines at a time
     static constexpr int kWaveWords = kUnitWords + kImageWords;    // private LDS of a wavefront
 };
 inline size_t decode_lds_bytes(int S) { return (table_words(S) + (size_t)kDecWaves * DecCfg::kWaveWords) * 4; }
@@ -454,7 +460,7 @@ __global__ __launch_bounds__(kDecWaves * 64) void decode_kernel(const uint32_t* 
             uint8_t* obase = static_cast<uint8_t*>(dst) + (size_t)u * kUnitBlocks * kGroup * 2;  // the unit's 8 KB of output
             const _Float16 sh = __builtin_bit_cast(_Float16, (unsigned short)(mw & 0xFFFFu));
             const half2_t s2 = {sh, sh};
-            uint32_t acc[4] = {0, 0, 0, 0};
+            uint32_t vals[kHalf / 2];  // the chain's 64 values = one 128-byte line of output
             uint32_t pk = 0;
             decode_chain<kLong, kHalf>(w, start, L, [&](int i, uint32_t e) {
                 if ((i & 1) == 0) {
@@ -462,20 +468,30 @@ __global__ __launch_bounds__(kDecWaves * 64) void decode_kernel(const uint32_t* 
                     return;
                 }
                 // fp16(centroid * scale) for two values: the packed FP16 product rounds once, like the FP32 rule
-                acc[(i >> 1) & 3] = __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2_t, pk | (e & 0xFFFF0000u)) * s2);
-                if ((i & 7) != 7) return;
-                const int c = (i >> 3) & (Cfg::kPieces - 1);
-                image[seg * Cfg::kPieces + (c ^ ((seg >> 2) & (Cfg::kPieces - 1)))] = make_uint4(acc[0], acc[1], acc[2], acc[3]);
-                if ((i & (Cfg::kPass - 1)) != Cfg::kPass - 1) return;
-                const int pass = i / Cfg::kPass;
-#pragma unroll
-                for (int k = 0; k < Cfg::kPieces; ++k) {
-                    const int n = k * 64 + lane, s = n / Cfg::kPieces, cc = n & (Cfg::kPieces - 1);
-                    const uint4 v = image[s * Cfg::kPieces + (cc ^ ((s >> 2) & (Cfg::kPieces - 1)))];
-                    if (u * kUnitBlocks + (s >> 1) < n_groups)
-                        *reinterpret_cast<uint4*>(obase + s * (kHalf * 2) + pass * (Cfg::kPass * 2) + cc * 16) = v;
-                }
+                vals[i >> 1] = __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2_t, pk | (e & 0xFFFF0000u)) * s2);
+                if ((i & 7) == 7) asm volatile("" : "+v"(vals[i >> 1]));  // finished here, not gathered at the end of the chain
             });
+            // Write-out in whole 128-byte lines: a store instruction that leaves half a line for later costs a second
+            // write of that line.  First the 32 lanes with the first chains put their lines into the image (32 rows of
+            // eight 16-byte pieces, piece k of row r at column k ^ (r & 7)) and all 64 lanes store them, eight lanes per
+            // line; then the same for the second chains.
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                wave_lds_fence();
+                if (half == h) {
+#pragma unroll
+                    for (int k = 0; k < Cfg::kLinePieces; ++k)
+                        image[blk * Cfg::kLinePieces + (k ^ (blk & 7))] = make_uint4(vals[4 * k], vals[4 * k + 1], vals[4 * k + 2], vals[4 * k + 3]);
+                }
+                wave_lds_fence();
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int row = (lane >> 3) + 8 * r, part = lane & 7;
+                    const uint4 v = image[row * Cfg::kLinePieces + (part ^ (row & 7))];
+                    if (u * kUnitBlocks + row < n_groups)
+                        *reinterpret_cast<uint4*>(obase + row * (kGroup * 2) + h * (kHalf * 2) + part * 16) = v;
+                }
+            }
         }
     }
 }
@@ -599,11 +615,6 @@ __global__ __launch_bounds__(kGemvThreads) void gemm_kernel(const uint32_t* __re
 constexpr int kEncThreads = 256;
 constexpr int kEncWaves = kEncThreads / 64;
 
-__device__ inline void wave_lds_fence() {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
 
 struct EncLds {
     const __half* cent;     // [S][16]

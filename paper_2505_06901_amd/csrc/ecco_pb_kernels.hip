@@ -37,8 +37,7 @@ constexpr int kSlot = kBlockWords + 1;    // LDS words per staged block; the las
 constexpr int kUnit = 64;                 // blocks per wavefront pass, one per lane
 constexpr int kPayWords = kUnit * kSlot + 4;
 constexpr int kPassValues = 32;           // values per lane between two write-outs
-constexpr int kImgStride = kPassValues / 2 + 1;
-constexpr int kImgWords = 64 * kImgStride;
+constexpr int kImgWords = 32 * 32;        // the write-out image: 32 lines of 128 bytes
 // the header takes at most 18 bits and a code at most 8: value i ends at or before bit 18 + 8 (i + 1), inside the block for i <= 60
 constexpr int kAlwaysPresent = (kBlockBits - 18) / kMaxLen;
 constexpr int kDecThreads = 512;
@@ -121,8 +120,8 @@ __global__ __launch_bounds__(kDecThreads) void pb_decode_kernel(const uint32_t* 
         uint32_t reach = fetch;                             // where the codes read so far end; keeps counting past 512
 #pragma unroll 1
         for (int pp = 0; pp < kGroup / (2 * kPassValues); ++pp) {
-            // 64 values per lane (one 128-byte line of output), kept in registers, then written out in two rounds right
-            // after each other: the two 64-byte halves of a line reach the L2 together instead of a pass apart
+            // 64 values per lane = one 128-byte line of output, kept in registers until the line is complete: a store
+            // instruction that leaves half a line for later costs a second write of that line
             uint32_t packed[kPassValues];
 #pragma unroll
             for (int i0 = 0; i0 < 2 * kPassValues; i0 += 4) {
@@ -144,18 +143,25 @@ __global__ __launch_bounds__(kDecThreads) void pb_decode_kernel(const uint32_t* 
                 }
                 fetch = min(fetch + used, (uint32_t)kBlockBits);
             }
+            // write-out: the lines of lanes 0..31, then of lanes 32..63, through the image (32 rows of eight 16-byte
+            // pieces, piece k of row r at column k ^ (r & 7)); every store instruction carries whole lines, 8 lanes each
+            uint4* image = reinterpret_cast<uint4*>(img);
 #pragma unroll
-            for (int half = 0; half < 2; ++half) {
+            for (int h = 0; h < 2; ++h) {
                 wave_lds_fence();
+                if ((lane >> 5) == h) {
+                    const int row = lane & 31;
 #pragma unroll
-                for (int k = 0; k < kPassValues / 2; ++k) img[lane * kImgStride + k] = packed[half * (kPassValues / 2) + k];
+                    for (int k = 0; k < 8; ++k)
+                        image[row * 8 + (k ^ (row & 7))] = make_uint4(packed[4 * k], packed[4 * k + 1], packed[4 * k + 2], packed[4 * k + 3]);
+                }
                 wave_lds_fence();
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const int b = (lane >> 2) + 16 * r, part = lane & 3;
-                    const uint32_t* s = img + b * kImgStride + part * 4;
-                    const uint4 v = make_uint4(s[0], s[1], s[2], s[3]);
-                    if (g0 + b < n_groups) reinterpret_cast<uint4*>(dst)[(g0 + b) * 16 + (2 * pp + half) * 4 + part] = v;
+                    const int row = (lane >> 3) + 8 * r, part = lane & 7;
+                    const uint4 v = image[row * 8 + (part ^ (row & 7))];
+                    const size_t b = g0 + 32 * h + row;
+                    if (b < n_groups) reinterpret_cast<uint4*>(dst)[b * 16 + pp * 8 + part] = v;
                 }
             }
         }
