@@ -645,17 +645,19 @@ __device__ inline EncChoice search_patterns(const EncLds& E, int p0, int p1, flo
     EncChoice best{0.0f, p0, 0u};
     for (int p = p0; p < p1; ++p) {
         const float* r = E.recon + p * kK;
+        // The reconstructed values ascend with k, and FP32 rounding is monotone, so |x - r[k]| falls (weakly) up to its
+        // least value and rises (weakly) after it: the first index of the least distance -- what a scan with a strict <
+        // finds -- is the last k at which the distance strictly drops.  One compare and one select per candidate.
         float d0 = fabsf(__fsub_rn(x0, r[0])), d1 = fabsf(__fsub_rn(x1, r[0]));
         uint32_t k0 = 0, k1 = 0;
 #pragma unroll
         for (int k = 1; k < kK; ++k) {
             const float rk = r[k];
             const float a = fabsf(__fsub_rn(x0, rk)), b = fabsf(__fsub_rn(x1, rk));
-            const bool c0 = a < d0, c1 = b < d1;  // strict: the lowest index wins a tie
-            k0 = c0 ? (uint32_t)k : k0;
-            k1 = c1 ? (uint32_t)k : k1;
-            d0 = c0 ? a : d0;
-            d1 = c1 ? b : d1;
+            k0 = a < d0 ? (uint32_t)k : k0;
+            k1 = b < d1 ? (uint32_t)k : k1;
+            d0 = a;
+            d1 = b;
         }
         const float e0 = __fsub_rn(x0, r[k0]), e1 = __fsub_rn(x1, r[k1]);
         // tree level 0: values 2l and 2l+1; levels 1..6 over the lanes: aligned blocks of 2, 4, 8, 16 lanes by

@@ -433,17 +433,19 @@ __global__ __launch_bounds__(kEncThreads) void pb_encode_kernel(const uint32_t* 
         uint32_t best_idx = 0;
         for (int p = 0; p < S; ++p) {
             const float* r = recon + p * 16;
+            // the reconstructed values ascend with k and FP32 rounding is monotone, so the distance falls (weakly) to its
+            // least value and rises (weakly) after it: the first index of the least distance -- what a scan with a strict <
+            // finds -- is the last k at which the distance strictly drops
             float d0 = fabsf(__fsub_rn(x0, r[0])), d1 = fabsf(__fsub_rn(x1, r[0]));
             uint32_t k0 = 0, k1 = 0;
 #pragma unroll
             for (int k = 1; k < kCent; ++k) {
                 const float rk = r[k];
                 const float u = fabsf(__fsub_rn(x0, rk)), v = fabsf(__fsub_rn(x1, rk));
-                const bool c0 = u < d0, c1 = v < d1;  // strict: the lowest index wins a tie
-                k0 = c0 ? (uint32_t)k : k0;
-                k1 = c1 ? (uint32_t)k : k1;
-                d0 = c0 ? u : d0;
-                d1 = c1 ? v : d1;
+                k0 = u < d0 ? (uint32_t)k : k0;
+                k1 = v < d1 ? (uint32_t)k : k1;
+                d0 = u;
+                d1 = v;
             }
             const float e0 = __fsub_rn(x0, r[k0]), e1 = __fsub_rn(x1, r[k1]);
             const float q0 = is0 ? 0.0f : __fmul_rn(e0, e0), q1 = is1 ? 0.0f : __fmul_rn(e1, e1);
