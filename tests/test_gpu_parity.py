@@ -154,6 +154,28 @@ def test_long_codes_all_paths(dev, oracle):
     assert rel_l2(y, want) <= REL_L2
 
 
+def test_long_codes_in_attention(dev, oracle):
+    """Models whose codes reach 12 bits, for K, for V and for both: the long-code variants of both attention kernels."""
+    B, H, T = 2, 2, 150
+    short = _kv_setup(dev, oracle, B, H, T, 8)
+    k, v = short[0], short[1]
+    cent, lens, probs = _skewed_model(oracle, 5, 3)
+    long_m = E.ecco_model_to_device(E.ecco_model_create(cent, lens), 0)
+    kl = _skewed_data(cent, probs, B * H * T, 4).reshape(B, H, T, 128)
+    vl = _skewed_data(cent, probs, B * H * T, 5).reshape(B, H, T, 128)
+    q = W.activation(B * H * 2, 128, 107).reshape(B, 2 * H, 128)
+    seq = np.array([T, 77], np.int32)
+    for mk, mv, kk, vv in [(long_m, short[3], kl, v), (short[2], long_m, k, vl), (long_m, long_m, kl, vl)]:
+        kb, km = E.ecco_encode(mk, t16(kk, dev)); vb, vm = E.ecco_encode(mv, t16(vv, dev))
+        args = (np_blocks(kb), np_meta(km), np_blocks(vb), np_meta(vm), seq)
+        want = oracle.kv_attend(mk.centroids, mk.code_lens, mv.centroids, mv.code_lens, np.ascontiguousarray(q[:, :H]).view(np.uint16), *args, B, H, T)
+        out = E.ecco_kv_attend(mk, mv, t16(q[:, :H], dev), kb, km, vb, vm, ti32(seq, dev), B, H, T).cpu().numpy()
+        assert rel_l2(out, want) <= REL_L2
+        want = oracle.kv_attend_gqa(mk.centroids, mk.code_lens, mv.centroids, mv.code_lens, q.view(np.uint16), *args, B, 2 * H, H, T)
+        out = E.ecco_kv_attend_gqa(mk, mv, t16(q, dev), kb, km, vb, vm, ti32(seq, dev), B, 2 * H, H, T, n_splits=2).cpu().numpy()
+        assert rel_l2(out, want) <= REL_L2
+
+
 def test_corrupt_blocks_decode_like_oracle(dev, oracle):
     S = 5
     cent, lens, _ = _skewed_model(oracle, S, 3)
