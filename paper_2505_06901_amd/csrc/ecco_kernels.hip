@@ -437,7 +437,7 @@ __global__ __launch_bounds__(kDecWaves * 64) void decode_kernel(const uint32_t* 
     int u = blockIdx.x * units_per_wg + wave;
     UnitLoad pre;
     if (u < u_end) pre = load_unit(blocks, meta, 0, n_groups, u, lane);
-    const int blk = lane & (kUnitBlocks - 1), half = lane >> 5, seg = blk * 2 + half;  // segment = 128 output bytes
+    const int blk = lane & (kUnitBlocks - 1), half = lane >> 5;  // block of the unit and chain of this lane
     for (; u < u_end; u += kDecWaves) {
         store_unit(wbuf, pre, lane);
         const uint32_t mw = pre.meta;
