@@ -76,6 +76,8 @@ def main():
                     "on request only: kv_append_minmax, encode, encode_minmax -- the bulk encoders run over the K cache -- "
                     "act_encode, act_decode -- the 2x activation codec on 32768 x 4096 activations -- and pb_encode, pb_decode, pb_gemv1 -- the self-contained "
                     "block format on the workload's weight matrix)")
+    ap.add_argument("--kv-batch", type=int, default=0, help="sequences of the KV rows (default: the workload's 8)")
+    ap.add_argument("--kv-tokens", type=int, default=0, help="tokens per sequence of the KV rows (default: the workload's 4096)")
     ap.add_argument("--gqa-group", type=int, default=4, help="query heads per key/value head of the kv_attend_gqa row (on request: --only kv_attend_gqa)")
     ap.add_argument("--gqa-splits", type=int, default=0, help="token splits of the kv_attend_gqa row (0: enough to give every compute unit a workgroup)")
     ap.add_argument("--selector-quality", action="store_true",
@@ -119,7 +121,7 @@ def main():
 
     # ---- KV cache ---------------------------------------------------------------------------------
     kc = W.CONFIGS["kv"]
-    B, H, T = kc["batch"], kc["heads"], kc["tokens"]
+    B, H, T = args.kv_batch or kc["batch"], kc["heads"], args.kv_tokens or kc["tokens"]
     extra_rows = [r for r in ("kv_append_minmax", "encode", "encode_minmax", "kv_attend_gqa") if r in only]
     pb_rows = [r for r in ("pb_encode", "pb_decode", "pb_gemv1") if r in only]
     act_rows = [r for r in ("act_encode", "act_decode") if r in only]

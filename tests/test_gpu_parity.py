@@ -449,6 +449,23 @@ def test_kv_attend_gqa_matches_oracle(dev, oracle, grp, n_splits):
         assert e.value.status == -2
 
 
+def test_gqa_long_context(dev, oracle):
+    """One sequence of 20 000 tokens, 8 query heads over 2 key/value heads, 16 token splits (several spans per split)."""
+    B, Hkv, grp, T = 1, 2, 4, 20000
+    k, v = W.kv_cache(B, Hkv, T, 128, seed=13)
+    mk = E.ecco_model_to_device(E.ecco_fit_patterns(k[:, :, :512], 16, 12, 3), 0)
+    mv = E.ecco_model_to_device(E.ecco_fit_patterns(v[:, :, :512], 16, 12, 4), 0)
+    kb, km = E.ecco_encode(mk, t16(k, dev)); vb, vm = E.ecco_encode(mv, t16(v, dev))
+    q = W.activation(B * Hkv * grp, 128, 108).reshape(B, Hkv * grp, 128)
+    for seq_len, splits in [(T, 16), (T - 4321, 3), (T, 1)]:
+        seq = np.array([seq_len], np.int32)
+        out = E.ecco_kv_attend_gqa(mk, mv, t16(q, dev), kb, km, vb, vm, ti32(seq, dev), B, Hkv * grp, Hkv, T, n_splits=splits).cpu().numpy()
+        want = oracle.kv_attend_gqa(mk.centroids, mk.code_lens, mv.centroids, mv.code_lens, q.view(np.uint16),
+                                    np_blocks(kb), np_meta(km), np_blocks(vb), np_meta(vm), seq, B, Hkv * grp, Hkv, T)
+        for h in range(Hkv * grp):
+            assert rel_l2(out[0, h], want[0, h]) <= REL_L2, (seq_len, splits, h)
+
+
 # ---------------------------------------------------------------------------------------------------
 # full-size workloads, checked on samples the oracle computes one by one
 def _full_weight_case(dev, oracle, name, which, rows_limit=None, n_sample=1536, batches=(1,)):
