@@ -63,6 +63,11 @@ int ecco_pb_fit(const uint16_t* data, size_t n_values, int S, uint64_t seed, ecc
  * texp in -15..7.  Errors: EINVAL, EFORMAT (a table fails validation), ENOMEM. */
 int ecco_pb_model_create(const uint16_t* centroids, const uint8_t* code_lens, const uint8_t* kp_lens, int S, int texp,
                          ecco_pb_model** out);
+/* CPU.  The model as a blob ({ 'ECP0', version 1, S, texp }, centroids, code lengths, pattern-id lengths; 2.1 KB + header for
+ * S = 64).  save: *written receives the size needed; buf == NULL only queries it; EINVAL if cap is too small.  load validates
+ * like ecco_pb_model_create (EFORMAT on a bad header, size or table). */
+int ecco_pb_model_save(const ecco_pb_model* m, void* buf, size_t cap, size_t* written);
+int ecco_pb_model_load(const void* buf, size_t len, ecco_pb_model** out);
 int ecco_pb_model_S(const ecco_pb_model* m);
 int ecco_pb_model_texp(const ecco_pb_model* m);
 const uint16_t* ecco_pb_model_centroids(const ecco_pb_model* m); /* [S][15], valid while the model lives */

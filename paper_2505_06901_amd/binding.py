@@ -23,7 +23,7 @@ EXPORTS = [
     "ecco_kv_attend_gqa", "ecco_kv_attend_gqa_workspace",
     "ecco_pb_fit", "ecco_pb_model_create", "ecco_pb_model_S", "ecco_pb_model_texp", "ecco_pb_model_centroids",
     "ecco_pb_model_code_lens", "ecco_pb_model_kp_lens", "ecco_pb_model_to_device", "ecco_pb_model_free",
-    "ecco_pb_encode", "ecco_pb_decode", "ecco_pb_decode_gemv",
+    "ecco_pb_encode", "ecco_pb_decode", "ecco_pb_decode_gemv", "ecco_pb_model_save", "ecco_pb_model_load",
 ]
 
 
@@ -74,6 +74,8 @@ def lib():
         L.ecco_pb_model_kp_lens.restype = C.POINTER(C.c_uint8)
         L.ecco_pb_model_free.restype = None
         L.ecco_pb_model_to_device.argtypes = [vp, i32]
+        L.ecco_pb_model_save.argtypes = [vp, vp, sz, C.POINTER(sz)]
+        L.ecco_pb_model_load.argtypes = [vp, sz, C.POINTER(vp)]
         L.ecco_pb_encode.argtypes = [vp, vp, sz, vp, vp]
         L.ecco_pb_decode.argtypes = [vp, vp, sz, vp, vp]
         L.ecco_pb_decode_gemv.argtypes = [vp, vp, i32, i32, vp, vp, vp]
@@ -343,6 +345,20 @@ def ecco_pb_model_create(centroids, code_lens, kp_lens, texp: int) -> PbModel:
     out = C.c_void_p(0)
     _check(lib().ecco_pb_model_create(c.ctypes.data_as(C.c_void_p), l.ctypes.data_as(C.c_void_p), k.ctypes.data_as(C.c_void_p),
                                       c.size // 15, int(texp), C.byref(out)), "ecco_pb_model_create")
+    return PbModel(out.value)
+
+
+def ecco_pb_model_save(m: PbModel) -> bytes:
+    n = C.c_size_t(0)
+    _check(lib().ecco_pb_model_save(m.handle, None, 0, C.byref(n)), "ecco_pb_model_save")
+    buf = C.create_string_buffer(n.value)
+    _check(lib().ecco_pb_model_save(m.handle, buf, n.value, C.byref(n)), "ecco_pb_model_save")
+    return buf.raw[: n.value]
+
+
+def ecco_pb_model_load(blob: bytes) -> PbModel:
+    out = C.c_void_p(0)
+    _check(lib().ecco_pb_model_load(blob, len(blob), C.byref(out)), "ecco_pb_model_load")
     return PbModel(out.value)
 
 

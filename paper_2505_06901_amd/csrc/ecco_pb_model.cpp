@@ -339,6 +339,45 @@ int ecco_pb_model_create(const uint16_t* centroids, const uint8_t* code_lens, co
     return ECCO_OK;
 }
 
+// serialised form: { 'ECP0', version 1, S, texp } then centroids [S][15] FP16, code lengths [S][4][16], pattern-id lengths [S]
+namespace {
+constexpr uint32_t kPbMagic = 0x30504345u;  // "ECP0"
+struct PbHeader { uint32_t magic, version; int32_t S, texp; };
+size_t pb_blob_bytes(int S) { return sizeof(PbHeader) + (size_t)S * (kCent * 2 + kBooks * kSym + 1); }
+}  // namespace
+
+int ecco_pb_model_save(const ecco_pb_model* m, void* buf, size_t cap, size_t* written) {
+    if (!m || !written) return ECCO_EINVAL;
+    const size_t need = pb_blob_bytes(m->S);
+    *written = need;
+    if (!buf) return ECCO_OK;
+    if (cap < need) return ECCO_EINVAL;
+    const PbHeader h{kPbMagic, 1u, m->S, m->texp};
+    unsigned char* p = static_cast<unsigned char*>(buf);
+    std::memcpy(p, &h, sizeof h);
+    p += sizeof h;
+    std::memcpy(p, m->cent, (size_t)m->S * kCent * 2);
+    p += (size_t)m->S * kCent * 2;
+    std::memcpy(p, m->lens, (size_t)m->S * kBooks * kSym);
+    p += (size_t)m->S * kBooks * kSym;
+    std::memcpy(p, m->kp_lens, (size_t)m->S);
+    return ECCO_OK;
+}
+
+int ecco_pb_model_load(const void* buf, size_t len, ecco_pb_model** out) {
+    if (!buf || !out) return ECCO_EINVAL;
+    if (len < sizeof(PbHeader)) return ECCO_EFORMAT;
+    PbHeader h;
+    std::memcpy(&h, buf, sizeof h);
+    if (h.magic != kPbMagic || h.version != 1u || h.S < 1 || h.S > kMaxS) return ECCO_EFORMAT;
+    if (len != pb_blob_bytes(h.S)) return ECCO_EFORMAT;
+    const unsigned char* p = static_cast<const unsigned char*>(buf) + sizeof h;
+    std::vector<uint16_t> cent((size_t)h.S * kCent);
+    std::memcpy(cent.data(), p, cent.size() * 2);
+    const uint8_t* lens = p + cent.size() * 2;
+    return ecco_pb_model_create(cent.data(), lens, lens + (size_t)h.S * kBooks * kSym, h.S, h.texp, out);
+}
+
 int ecco_pb_model_S(const ecco_pb_model* m) { return m ? m->S : 0; }
 int ecco_pb_model_texp(const ecco_pb_model* m) { return m ? m->texp : 0; }
 const uint16_t* ecco_pb_model_centroids(const ecco_pb_model* m) { return m ? m->cent : nullptr; }

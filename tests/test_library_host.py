@@ -141,6 +141,14 @@ def test_paper_block_fit_invariants():
     # the tables survive a trip through ecco_pb_model_create; bad tables are refused
     m3 = E.ecco_pb_model_create(m.centroids, lens, m.kp_lens, m.texp)
     assert np.array_equal(m3.centroids, m.centroids)
+    blob = E.ecco_pb_model_save(m)
+    assert len(blob) == 16 + 16 * (30 + 64 + 1) and blob[:4] == b"ECP0"
+    m4 = E.ecco_pb_model_load(blob)
+    assert (m4.S, m4.texp) == (m.S, m.texp) and np.array_equal(m4.code_lens, lens) and np.array_equal(m4.kp_lens, m.kp_lens)
+    for broken in (blob[:-1], b"XXXX" + blob[4:], blob[:496] + b"\x00" + blob[497:]):  # short, bad magic, a code length of 0
+        with pytest.raises(E.EccoError) as e:
+            E.ecco_pb_model_load(broken)
+        assert e.value.status == -5
     bad = lens.copy(); bad[0, 0, 0] = 1
     with pytest.raises(E.EccoError) as e:
         E.ecco_pb_model_create(m.centroids, bad, m.kp_lens, m.texp)
