@@ -316,6 +316,29 @@ def main():
             ms[row] = timed_replays(g, replays) / (replays * n)
             del g
 
+    # ---- what merely reading the same bytes costs: a read-only streaming kernel over the blocks of every rotating copy ----
+    stream_ms = None
+    if want("gemv1"):
+        sink = torch.zeros((256,), dtype=torch.int32, device=dev)
+        def read_round():
+            for c in range(n_copies):
+                E.ecco_read_stream(wb[c], sink)   # the 64-byte payloads: one launch per copy, like the decoder
+        if args.eager:
+            read_round()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            read_round()
+            e1.record()
+            torch.cuda.synchronize()
+            stream_ms = e0.elapsed_time(e1) / n_copies
+        else:
+            g = capture(read_round)
+            g.replay()
+            torch.cuda.synchronize()
+            stream_ms = timed_replays(g, 2) / (2 * n_copies)
+            del g
+
     # ---- cache-warm figure for the metric row (same copy every launch), labelled as such --------------
     warm_ms = None
     if want("gemv1"):
@@ -427,7 +450,9 @@ def main():
                                f"fused ecco_decode_gemv batch 1; other rows of the step: {','.join(row_names)}",
                    "n_groups": n_groups, "compressed_bytes": comp_bytes, "payload_only_GBps": achieved * 64 / 68,
                    "pct_hbm_peak": 100.0 * achieved / HBM_PEAK_GBS, "raw_block_fraction": raw_frac,
-                   "rotating_copies": n_copies, "timing": "eager launches" if args.eager else "HIP graph replay", "cache_warm_gemv1_GBps": (comp_bytes / (warm_ms * 1e-3) / 1e9) if warm_ms else None},
+                   "rotating_copies": n_copies, "timing": "eager launches" if args.eager else "HIP graph replay", "cache_warm_gemv1_GBps": (comp_bytes / (warm_ms * 1e-3) / 1e9) if warm_ms else None,
+                   "read_only_stream_GBps": (n_groups * 64 / (stream_ms * 1e-3) / 1e9) if stream_ms else None,
+                   "frac_of_read_only_stream": (achieved / (n_groups * 64 / (stream_ms * 1e-3) / 1e9)) if stream_ms and metric_row == "gemv1" else None},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
                      "kernel": "fused decode-GEMV, batch 1", "bytes_per_launch": comp_bytes,

@@ -20,7 +20,7 @@ EXPORTS = [
     "ecco_model_S", "ecco_model_centroids", "ecco_model_code_lens", "ecco_model_to_device", "ecco_model_free",
     "ecco_encode", "ecco_decode", "ecco_decode_indices", "ecco_decode_gemv", "ecco_kv_append", "ecco_kv_attend",
     "ecco_encode_minmax", "ecco_kv_append_minmax", "ecco_act_encode", "ecco_act_decode",
-    "ecco_kv_attend_gqa", "ecco_kv_attend_gqa_workspace",
+    "ecco_kv_attend_gqa", "ecco_kv_attend_gqa_workspace", "ecco_read_stream",
     "ecco_pb_fit", "ecco_pb_model_create", "ecco_pb_model_S", "ecco_pb_model_texp", "ecco_pb_model_centroids",
     "ecco_pb_model_code_lens", "ecco_pb_model_kp_lens", "ecco_pb_model_to_device", "ecco_pb_model_free",
     "ecco_pb_encode", "ecco_pb_decode", "ecco_pb_decode_gemv", "ecco_pb_model_save", "ecco_pb_model_load",
@@ -61,6 +61,7 @@ def lib():
         L.ecco_kv_append_minmax.argtypes = [vp] * 9 + [i32, i32, i32, vp]
         L.ecco_kv_attend.argtypes = [vp] * 8 + [i32, i32, i32, vp, vp]
         L.ecco_act_encode.argtypes = [vp, sz, vp, vp]
+        L.ecco_read_stream.argtypes = [vp, sz, vp, vp]
         L.ecco_kv_attend_gqa.argtypes = [vp] * 8 + [i32, i32, i32, i32, i32, vp, vp, vp]
         L.ecco_kv_attend_gqa_workspace.argtypes = [i32, i32, i32]
         L.ecco_kv_attend_gqa_workspace.restype = sz
@@ -262,6 +263,11 @@ def ecco_kv_attend_gqa(mk: Model, mv: Model, q, k_blocks, k_meta, v_blocks, v_me
                                     _dp(seq_len), B, Hq, Hkv, T_max, n_splits, _dp(workspace), _dp(out), _stream()),
            "ecco_kv_attend_gqa")
     return out
+
+
+def ecco_read_stream(src, out):
+    """Reads every byte of the CUDA tensor src once (measurement aid); out: CUDA int32 tensor with at least 256 elements."""
+    _check(lib().ecco_read_stream(_dp(src), src.numel() * src.element_size(), _dp(out), _stream()), "ecco_read_stream")
 
 
 ACT_GROUP = 64

@@ -148,6 +148,27 @@ __global__ __launch_bounds__(kActThreads) void act_encode_kernel(const uint4* __
     }
 }
 
+// A read-only streaming kernel: every lane reads 16-byte pieces on consecutive addresses and folds them into one word
+// per workgroup.  It does nothing useful; timed over the same bytes as a decoder it gives the rate at which this
+// machine can merely read them with one launch (the practical ceiling beside the 8 TB/s of the data sheet).
+__global__ __launch_bounds__(1024) void read_stream_kernel(const uint4* __restrict__ src, size_t n16, uint32_t* __restrict__ out) {
+    uint32_t acc = 0;
+    const size_t step = (size_t)gridDim.x * 1024;
+    size_t i = (size_t)blockIdx.x * 1024 + threadIdx.x;
+    for (; i + 3 * step < n16; i += 4 * step) {  // four loads in flight per lane
+        const uint4 a = src[i], b = src[i + step], c = src[i + 2 * step], d = src[i + 3 * step];
+        acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+    }
+    uint4 t[3] = {make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0)};
+#pragma unroll
+    for (int k = 0; k < 3; ++k)
+        if (i + k * step < n16) t[k] = src[i + k * step];
+#pragma unroll
+    for (int k = 0; k < 3; ++k) acc ^= t[k].x ^ t[k].y ^ t[k].z ^ t[k].w;
+    for (int m = 1; m < 64; m <<= 1) acc ^= (uint32_t)__shfl_xor((int)acc, m);
+    if ((threadIdx.x & 63) == 0) atomicXor(&out[blockIdx.x], acc);
+}
+
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
 inline int act_grid(size_t n_pieces) {
@@ -167,6 +188,17 @@ int ecco_act_encode(const uint16_t* src, size_t n_groups, void* blocks, void* st
     const size_t n_pieces = n_groups * kPiecesPerBlock;
     hipLaunchKernelGGL(act_encode_kernel, dim3(act_grid(n_pieces)), dim3(kActThreads), 0, static_cast<hipStream_t>(stream),
                        reinterpret_cast<const uint4*>(src), n_pieces, static_cast<uint2*>(blocks));
+    ECCO_HIP_CHECK(hipGetLastError());
+    return ECCO_OK;
+}
+
+int ecco_read_stream(const void* src, size_t bytes, uint32_t* out, void* stream) {
+    if (!src || !out) return ECCO_EINVAL;
+    if (bytes % 16 != 0) return ECCO_ESHAPE;
+    if (!aligned(src, 16) || !aligned(out, 4)) return ECCO_EALIGN;
+    if (bytes == 0) return ECCO_OK;
+    hipLaunchKernelGGL(read_stream_kernel, dim3(256), dim3(1024), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const uint4*>(src), bytes / 16, out);
     ECCO_HIP_CHECK(hipGetLastError());
     return ECCO_OK;
 }
