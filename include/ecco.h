@@ -192,7 +192,7 @@ int ecco_kv_attend(const ecco_model* mk, const ecco_model* mv, const uint16_t* q
                    const int32_t* seq_len, int B, int H, int T_max, float* out, void* stream);
 
 /* Measurement aid, not part of the codec: reads `bytes` bytes (a multiple of 16; src device, 16-byte aligned) with one launch
- * of 256 workgroups and XORs a checksum word per workgroup into out[0..255] (device).  Timed over the same compressed bytes as
+ * of 256 workgroups and writes a checksum word per workgroup to out[0..255] (device).  Timed over the same compressed bytes as
  * a decoder, it gives the rate at which the machine can merely read them: the practical ceiling that the benchmark prints
  * beside the data-sheet bandwidth.  Errors: EINVAL, ESHAPE (bytes % 16), EALIGN, EHIP. */
 int ecco_read_stream(const void* src, size_t bytes, uint32_t* out, void* stream);

@@ -166,7 +166,14 @@ __global__ __launch_bounds__(1024) void read_stream_kernel(const uint4* __restri
 #pragma unroll
     for (int k = 0; k < 3; ++k) acc ^= t[k].x ^ t[k].y ^ t[k].z ^ t[k].w;
     for (int m = 1; m < 64; m <<= 1) acc ^= (uint32_t)__shfl_xor((int)acc, m);
-    if ((threadIdx.x & 63) == 0) atomicXor(&out[blockIdx.x], acc);
+    __shared__ uint32_t part[16];
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t all = 0;
+        for (int w = 0; w < 16; ++w) all ^= part[w];
+        out[blockIdx.x] = all;  // one plain store per workgroup
+    }
 }
 
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
