@@ -9,8 +9,8 @@
  * attention (the consumers of Section 2.1), and the per-group encoder (Section 4.3 "Compressor
  * Design") for bulk tensors and for appended KV tokens.  The pattern / codebook fit runs on the CPU.
  *
- * BLOCK FORMAT (the simplified format this build measures; differences from the paper's
- * self-contained block are listed in the design doc):
+ * BLOCK FORMAT (the simplified format this build measures; the paper's self-contained block, which
+ * keeps the scale, the pattern id and padded outliers inside the 64 bytes, is in ecco_paper_block.h):
  *   - group  = 128 consecutive FP16 values.  Matrices: row-major, group g = (row, col/128).
  *   - block  = 64 bytes of payload per group at byte offset 64*g: 16 little-endian 32-bit words
  *              holding a bit stream; stream bit j (0..511) is bit 31 - (j & 31) of word j >> 5

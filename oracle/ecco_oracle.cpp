@@ -762,7 +762,7 @@ void oracle_kv_attend_gqa(const uint16_t* ck, const uint8_t* lk, int Sk, const u
 }
 
 // ------------------------------------------------------------------------------------------
-// The fit (Section 3.2).  Readings of what the paper leaves open are listed in the design doc.
+// The fit (Section 3.2).  Where the paper leaves a step open, the comment at that step says which reading is taken.
 int oracle_fit(const uint16_t* data, size_t n_values, int S, int max_len, uint64_t seed,
                uint16_t* centroids, uint8_t* lens, uint64_t* hist_out, size_t* n_fit_groups) {
     if (!data || n_values == 0 || n_values % G != 0 || S < 1 || S > ORACLE_MAX_S || max_len < 4 || max_len > ORACLE_MAX_LEN)

@@ -50,7 +50,7 @@ int oracle_verify_model(const uint16_t* centroids, const uint8_t* lens, int S);
  * update and after the last one.  cent_out is sorted ascending. */
 int oracle_kmeans_1d(const float* v, int n, int K, int max_iter, double* cent_out, double* objective);
 
-/* the whole fit of Section 3.2 steps 1-7 in this build's reading:
+/* the whole fit of Section 3.2 steps 1-7 in this build's reading (each step is commented in the function body):
  * centroids[S*16] fp16 bits, lens[S*16], hist[S*16] (may be NULL), n_fit_groups (may be NULL) */
 int oracle_fit(const uint16_t* data, size_t n_values, int S, int max_len, uint64_t seed,
                uint16_t* centroids, uint8_t* lens, uint64_t* hist, size_t* n_fit_groups);
