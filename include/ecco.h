@@ -36,7 +36,9 @@
  *   - "host" / "device" in a parameter comment says where the pointer must point.  The library
  *     never allocates, frees or keeps caller buffers; device work is enqueued on `stream`
  *     (a hipStream_t passed as void*, NULL = the default stream) and the call returns without
- *     synchronising.  Argument errors are detected on the host before anything is launched.
+ *     synchronising.  Argument errors are detected on the host before anything is launched, in
+ *     this order: null pointers (EINVAL), sizes (ESHAPE), alignment (EALIGN), and last whether the
+ *     model is on a device (EINVAL) -- so the first three can be checked on a machine without a GPU.
  *   - FP16 travels as uint16_t bit patterns.
  */
 #ifndef ECCO_H

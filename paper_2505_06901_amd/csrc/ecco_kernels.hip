@@ -1323,10 +1323,11 @@ int cu_count(int device) {
 extern "C" {
 
 static int encode_common(bool minmax, const ecco_model* m, const uint16_t* src, size_t n_groups, void* blocks, uint32_t* meta, void* stream) {
-    if (model_ready(m) != ECCO_OK) return ECCO_EINVAL;
-    if (n_groups == 0) return ECCO_OK;  // nothing to do; pointers may be null
+    if (!m) return ECCO_EINVAL;
+    if (n_groups == 0) return model_ready(m);  // nothing to do; pointers may be null
     if (!src || !blocks || !meta) return ECCO_EINVAL;
     if (!aligned(blocks, 64) || !aligned(src, 4) || !aligned(meta, 4)) return ECCO_EALIGN;
+    if (model_ready(m) != ECCO_OK) return ECCO_EINVAL;
     const size_t wgs = (n_groups + kEncWaves - 1) / kEncWaves;
     const int grid = (int)std::min<size_t>(wgs, (size_t)cu_count(m->device) * 16);
     hipLaunchKernelGGL(minmax ? encode_kernel<true> : encode_kernel<false>, dim3(grid), dim3(kEncThreads), enc_lds_bytes(m->S), static_cast<hipStream_t>(stream), m->dev,
@@ -1345,11 +1346,12 @@ int ecco_encode_minmax(const ecco_model* m, const uint16_t* src, size_t n_groups
 
 static int decode_common(const ecco_model* m, const void* blocks, const uint32_t* meta, size_t n_groups, void* dst,
                          void* stream, bool indices) {
-    if (model_ready(m) != ECCO_OK) return ECCO_EINVAL;
-    if (n_groups == 0) return ECCO_OK;  // nothing to do; pointers may be null
+    if (!m) return ECCO_EINVAL;
+    if (n_groups == 0) return model_ready(m);  // nothing to do; pointers may be null
     if (!blocks || !meta || !dst) return ECCO_EINVAL;
     if (n_groups > (size_t)0x7FFFFFFF - kUnitBlocks) return ECCO_ESHAPE;
     if (!aligned(blocks, 64) || !aligned(dst, 16) || !aligned(meta, 4)) return ECCO_EALIGN;
+    if (model_ready(m) != ECCO_OK) return ECCO_EINVAL;
     const int units = (int)((n_groups + kUnitBlocks - 1) / kUnitBlocks);
     const int cus = cu_count(m->device);
     const int units_per_wg = std::max(kDecWaves, (units + cus - 1) / cus);
@@ -1378,10 +1380,10 @@ int ecco_decode_indices(const ecco_model* m, const void* blocks, const uint32_t*
 
 int ecco_decode_gemv(const ecco_model* m, const void* blocks, const uint32_t* meta, int rows, int cols,
                      const uint16_t* x, int batch, float* y, void* stream) {
-    if (!blocks || !meta || !x || !y) return ECCO_EINVAL;
-    if (model_ready(m) != ECCO_OK) return ECCO_EINVAL;
+    if (!m || !blocks || !meta || !x || !y) return ECCO_EINVAL;
     if (rows <= 0 || cols <= 0 || cols % kGroup != 0 || cols > 65536 || batch < 1 || batch > 16) return ECCO_ESHAPE;
     if (!aligned(blocks, 64) || !aligned(x, 16) || !aligned(y, 4) || !aligned(meta, 4)) return ECCO_EALIGN;
+    if (model_ready(m) != ECCO_OK) return ECCO_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int gpr = cols / kGroup;
     const int cus = cu_count(m->device);
@@ -1422,10 +1424,10 @@ int ecco_decode_gemv(const ecco_model* m, const void* blocks, const uint32_t* me
 static int kv_append_common(bool minmax, const ecco_model* mk, const ecco_model* mv, const uint16_t* k_new, const uint16_t* v_new,
                             void* k_blocks, uint32_t* k_meta, void* v_blocks, uint32_t* v_meta,
                             const int32_t* seq_len, int B, int H, int T_max, void* stream) {
-    if (!k_new || !v_new || !k_blocks || !k_meta || !v_blocks || !v_meta || !seq_len) return ECCO_EINVAL;
-    if (model_ready(mk) != ECCO_OK || model_ready(mv) != ECCO_OK || mk->device != mv->device) return ECCO_EINVAL;
+    if (!mk || !mv || !k_new || !v_new || !k_blocks || !k_meta || !v_blocks || !v_meta || !seq_len) return ECCO_EINVAL;
     if (B <= 0 || H <= 0 || T_max <= 0) return ECCO_ESHAPE;
     if (!aligned(k_blocks, 64) || !aligned(v_blocks, 64) || !aligned(k_new, 4) || !aligned(v_new, 4)) return ECCO_EALIGN;
+    if (model_ready(mk) != ECCO_OK || model_ready(mv) != ECCO_OK || mk->device != mv->device) return ECCO_EINVAL;
     const dim3 grid(minmax ? (B * H + kEncWaves - 1) / kEncWaves : B * H, 2);
     hipLaunchKernelGGL(minmax ? kv_append_minmax_kernel : kv_append_kernel, grid, dim3(kEncThreads),
                        enc_lds_bytes(std::max(mk->S, mv->S)),
@@ -1457,12 +1459,12 @@ int ecco_kv_attend_gqa(const ecco_model* mk, const ecco_model* mv, const uint16_
                        const void* k_blocks, const uint32_t* k_meta, const void* v_blocks, const uint32_t* v_meta,
                        const int32_t* seq_len, int B, int Hq, int Hkv, int T_max, int n_splits, void* workspace,
                        float* out, void* stream) {
-    if (!q || !k_blocks || !k_meta || !v_blocks || !v_meta || !seq_len || !out) return ECCO_EINVAL;
-    if (model_ready(mk) != ECCO_OK || model_ready(mv) != ECCO_OK || mk->device != mv->device) return ECCO_EINVAL;
+    if (!mk || !mv || !q || !k_blocks || !k_meta || !v_blocks || !v_meta || !seq_len || !out) return ECCO_EINVAL;
     if (B <= 0 || Hq <= 0 || Hkv <= 0 || T_max <= 0 || Hq % Hkv != 0 || Hq / Hkv > kGqaMaxGroup) return ECCO_ESHAPE;
     if (n_splits < 1 || n_splits > 256 || (long long)B * Hkv > 0x7FFFFFFF) return ECCO_ESHAPE;
     if (n_splits > 1 && !workspace) return ECCO_EINVAL;
     if (!aligned(k_blocks, 64) || !aligned(v_blocks, 64) || !aligned(q, 16) || !aligned(out, 4) || !aligned(workspace, 16)) return ECCO_EALIGN;
+    if (model_ready(mk) != ECCO_OK || model_ready(mv) != ECCO_OK || mk->device != mv->device) return ECCO_EINVAL;
     const size_t lds = gqa_lds_bytes(mk->S, mv->S, Hq / Hkv);
     const bool lk = mk->max_len > kPeekBits, lv = mv->max_len > kPeekBits;
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -1486,10 +1488,10 @@ int ecco_kv_attend_gqa(const ecco_model* mk, const ecco_model* mv, const uint16_
 int ecco_kv_attend(const ecco_model* mk, const ecco_model* mv, const uint16_t* q,
                    const void* k_blocks, const uint32_t* k_meta, const void* v_blocks, const uint32_t* v_meta,
                    const int32_t* seq_len, int B, int H, int T_max, float* out, void* stream) {
-    if (!q || !k_blocks || !k_meta || !v_blocks || !v_meta || !seq_len || !out) return ECCO_EINVAL;
-    if (model_ready(mk) != ECCO_OK || model_ready(mv) != ECCO_OK || mk->device != mv->device) return ECCO_EINVAL;
+    if (!mk || !mv || !q || !k_blocks || !k_meta || !v_blocks || !v_meta || !seq_len || !out) return ECCO_EINVAL;
     if (B <= 0 || H <= 0 || T_max <= 0) return ECCO_ESHAPE;
     if (!aligned(k_blocks, 64) || !aligned(v_blocks, 64) || !aligned(q, 16) || !aligned(out, 4)) return ECCO_EALIGN;
+    if (model_ready(mk) != ECCO_OK || model_ready(mv) != ECCO_OK || mk->device != mv->device) return ECCO_EINVAL;
     const size_t lds = attn_lds_bytes(mk->S, mv->S);
     const bool lk = mk->max_len > kPeekBits, lv = mv->max_len > kPeekBits;
     auto launch = [&](auto kernel) -> int {

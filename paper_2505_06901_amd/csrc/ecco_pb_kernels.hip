@@ -520,10 +520,11 @@ int allow_lds(K kernel, size_t bytes) {
 extern "C" {
 
 int ecco_pb_encode(const ecco_pb_model* m, const uint16_t* src, size_t n_groups, void* blocks, void* stream) {
-    if (model_ready(m) != ECCO_OK) return ECCO_EINVAL;
-    if (n_groups == 0) return ECCO_OK;
+    if (!m) return ECCO_EINVAL;
+    if (n_groups == 0) return model_ready(m);
     if (!src || !blocks) return ECCO_EINVAL;
     if (!aligned(src, 4) || !aligned(blocks, 64)) return ECCO_EALIGN;
+    if (model_ready(m) != ECCO_OK) return ECCO_EINVAL;
     const size_t wgs = (n_groups + kEncWaves - 1) / kEncWaves;
     const int grid = (int)std::min<size_t>(wgs, 256 * 16);
     float inv_tscale = 1.0f;  // 2^-texp, exact
@@ -535,9 +536,10 @@ int ecco_pb_encode(const ecco_pb_model* m, const uint16_t* src, size_t n_groups,
 }
 
 int ecco_pb_decode_gemv(const ecco_pb_model* m, const void* blocks, int rows, int cols, const uint16_t* x, float* y, void* stream) {
-    if (model_ready(m) != ECCO_OK || !blocks || !x || !y) return ECCO_EINVAL;
+    if (!m || !blocks || !x || !y) return ECCO_EINVAL;
     if (rows <= 0 || cols <= 0 || cols % kGroup != 0 || cols > 65536) return ECCO_ESHAPE;
     if (!aligned(blocks, 64) || !aligned(x, 16) || !aligned(y, 4)) return ECCO_EALIGN;
+    if (model_ready(m) != ECCO_OK) return ECCO_EINVAL;
     const int gpr = cols / kGroup;
     // a band of rows per workgroup: about one band per compute unit, at most kGvPartFloats blocks
     int band = std::max(1, (rows + 255) / 256);
@@ -557,11 +559,12 @@ int ecco_pb_decode_gemv(const ecco_pb_model* m, const void* blocks, int rows, in
 }
 
 int ecco_pb_decode(const ecco_pb_model* m, const void* blocks, size_t n_groups, uint16_t* dst, void* stream) {
-    if (model_ready(m) != ECCO_OK) return ECCO_EINVAL;
-    if (n_groups == 0) return ECCO_OK;
+    if (!m) return ECCO_EINVAL;
+    if (n_groups == 0) return model_ready(m);
     if (!blocks || !dst) return ECCO_EINVAL;
     if (n_groups >= ((size_t)1 << 31)) return ECCO_ESHAPE;
     if (!aligned(blocks, 64) || !aligned(dst, 16)) return ECCO_EALIGN;
+    if (model_ready(m) != ECCO_OK) return ECCO_EINVAL;
     const size_t lds = dec_lds_bytes(m->S);
     const int rc = allow_lds(pb_decode_kernel, lds);
     if (rc != ECCO_OK) return rc;

@@ -122,6 +122,62 @@ def test_argument_errors_without_gpu(tiny_model):
     assert L.ecco_decode(h, null, fake, 1, fake, null) == -1
     assert L.ecco_model_to_device(null, 0) == -1
     assert L.ecco_model_to_device(h, -1) == -1
+    # sizes (ESHAPE) and alignment (EALIGN) are judged before the model's device, so they show without a GPU
+    odd = C.c_void_p(0x1004)
+    assert L.ecco_decode_gemv(h, fake, fake, 1, 100, fake, 1, fake, null) == -2      # cols % 128
+    assert L.ecco_decode_gemv(h, fake, fake, 1, 128, fake, 17, fake, null) == -2     # batch
+    assert L.ecco_decode_gemv(h, fake, fake, 0, 128, fake, 1, fake, null) == -2      # rows
+    assert L.ecco_decode_gemv(h, fake, fake, 1, 65536 + 128, fake, 1, fake, null) == -2
+    assert L.ecco_decode_gemv(h, odd, fake, 1, 128, fake, 1, fake, null) == -3       # blocks not 64-byte aligned
+    assert L.ecco_decode_gemv(h, fake, fake, 1, 128, odd, 1, fake, null) == -3       # x not 16-byte aligned
+    assert L.ecco_decode(h, odd, fake, 1, fake, null) == -3
+    assert L.ecco_decode(h, fake, fake, 1, odd, null) == -3
+    assert L.ecco_decode(h, fake, fake, 1 << 31, fake, null) == -2
+    assert L.ecco_decode(h, null, null, 0, null, null) == -1                         # nothing to do, but no device either
+    assert L.ecco_encode(h, fake, 1, odd, fake, null) == -3
+    assert L.ecco_encode_minmax(h, fake, 1, odd, fake, null) == -3
+    assert L.ecco_kv_append(h, h, fake, fake, fake, fake, fake, fake, fake, 0, 1, 1, null) == -2
+    assert L.ecco_kv_append(h, h, fake, fake, odd, fake, fake, fake, fake, 1, 1, 1, null) == -3
+    assert L.ecco_kv_append_minmax(h, h, fake, fake, fake, fake, fake, fake, fake, 1, 0, 1, null) == -2
+    assert L.ecco_kv_attend(h, h, fake, fake, fake, fake, fake, fake, 1, 1, 0, fake, null) == -2
+    assert L.ecco_kv_attend(h, h, odd, fake, fake, fake, fake, fake, 1, 1, 1, fake, null) == -3
+    assert L.ecco_kv_attend(h, null, fake, fake, fake, fake, fake, fake, 1, 1, 1, fake, null) == -1
+    gqa = lambda Hq, Hkv, splits, ws, q=fake: L.ecco_kv_attend_gqa(h, h, q, fake, fake, fake, fake, fake, 1, Hq, Hkv, 8, splits, ws, fake, null)
+    assert gqa(6, 4, 1, null) == -2          # Hq % Hkv
+    assert gqa(34, 2, 1, null) == -2         # more than 16 query heads per key/value head
+    assert gqa(8, 2, 0, null) == -2 and gqa(8, 2, 257, fake) == -2
+    assert gqa(8, 2, 2, null) == -1          # splits need a workspace
+    assert gqa(8, 2, 2, odd) == -3
+    assert gqa(8, 2, 1, null) == -1          # all fine up to the model, which is on no device
+    assert L.ecco_kv_attend_gqa_workspace(2, 8, 3) == 2 * 8 * 3 * 130 * 4
+    # the activation codec and the streaming reference take no model: everything but the launch is host logic
+    assert L.ecco_act_encode(null, 1, fake, null) == -1 and L.ecco_act_decode(fake, 1, null, null) == -1
+    assert L.ecco_act_encode(fake, (1 << 40) + 1, fake, null) == -2
+    assert L.ecco_act_encode(odd, 1, fake, null) == -3 and L.ecco_act_decode(odd, 1, fake, null) == -3
+    assert L.ecco_act_encode(null, 0, null, null) == 0 and L.ecco_act_decode(null, 0, null, null) == 0
+    assert L.ecco_read_stream(fake, 24, fake, null) == -2 and L.ecco_read_stream(odd, 32, fake, null) == -3
+    assert L.ecco_read_stream(fake, 0, fake, null) == 0
+
+
+def test_paper_block_argument_errors_without_gpu():
+    w = W.config_weight("tiny")
+    m = E.ecco_pb_fit(w, 4, 0)
+    L = binding.lib()
+    h = m.handle
+    null, fake, odd = C.c_void_p(0), C.c_void_p(0x1000), C.c_void_p(0x1004)
+    assert L.ecco_pb_decode(null, fake, 1, fake, null) == -1
+    assert L.ecco_pb_decode(h, fake, 1, fake, null) == -1            # model on no device
+    assert L.ecco_pb_decode(h, null, 1, fake, null) == -1
+    assert L.ecco_pb_decode(h, fake, 1 << 31, fake, null) == -2
+    assert L.ecco_pb_decode(h, odd, 1, fake, null) == -3 and L.ecco_pb_decode(h, fake, 1, odd, null) == -3
+    assert L.ecco_pb_encode(h, fake, 1, odd, null) == -3
+    assert L.ecco_pb_encode(h, fake, 1, fake, null) == -1
+    assert L.ecco_pb_decode_gemv(h, fake, 1, 100, fake, fake, null) == -2
+    assert L.ecco_pb_decode_gemv(h, fake, 0, 128, fake, fake, null) == -2
+    assert L.ecco_pb_decode_gemv(h, fake, 1, 65536 + 128, fake, fake, null) == -2
+    assert L.ecco_pb_decode_gemv(h, fake, 1, 128, odd, fake, null) == -3
+    assert L.ecco_pb_decode_gemv(h, fake, 1, 128, fake, fake, null) == -1
+    assert L.ecco_pb_model_to_device(null, 0) == -1
 
 
 def test_paper_block_fit_invariants():
