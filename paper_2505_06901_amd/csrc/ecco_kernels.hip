@@ -406,14 +406,15 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_kernel(const uint32_t* __re
 // 4096 x 4096 matrix).  So the FP16 values pass through a per-wavefront LDS image, 32 values per
 // chain at a time, and are read back so that adjacent lanes hold adjacent 16-byte pieces: four lanes
 // write the 64 contiguous bytes a segment gets per pass.  The image is swizzled (piece c of segment
-// s sits at 4 s + (c ^ (s / 4) % 4)) so that the transposed reads are conflict-free.  Twelve
-// wavefronts with a 4 KB image each fit 160 KB of LDS next to the S = 64 tables (sixteen with 2 KB
-// images and 32-byte pieces measured slower, also on small inputs).
-constexpr int kDecWaves = 12;
+// s sits at 4 s + (c ^ (s / 4) % 4)) so that the transposed reads are conflict-free.  The 4 KB image
+// lies over the wavefront's 2.2 KB payload buffer, which is dead once both chains are decoded (the
+// values wait in registers meanwhile), so sixteen wavefronts fit 160 KB of LDS next to the S = 64
+// tables; the zero words that bound each block's stream are rewritten with every unit.
+constexpr int kDecWaves = 16;
 struct DecCfg {
     static constexpr int kLinePieces = kHalf / 8;                  // 16-byte pieces of a chain's 128 output bytes
     static constexpr int kImageWords = 32 * kLinePieces * 4;       // 32 lines at a time
-    static constexpr int kWaveWords = kUnitWords + kImageWords;    // private LDS of a wavefront
+    static constexpr int kWaveWords = kImageWords > kUnitWords ? kImageWords : kUnitWords;  // private LDS of a wavefront: payload, then image
 };
 inline size_t decode_lds_bytes(int S) { return (table_words(S) + (size_t)kDecWaves * DecCfg::kWaveWords) * 4; }
 
@@ -427,9 +428,7 @@ __global__ __launch_bounds__(kDecWaves * 64) void decode_kernel(const uint32_t* 
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const Tables T = stage_tables(smem, dev, S);
     uint32_t* wbuf = smem + table_words(S) + wave * Cfg::kWaveWords;
-    uint4* image = reinterpret_cast<uint4*>(wbuf + kUnitWords);
-    if (lane < kUnitBlocks) wbuf[lane * kStride + kBlockWords] = 0u;
-    if (lane == 0) wbuf[kUnitBlocks * kStride] = 0u;
+    uint4* image = reinterpret_cast<uint4*>(wbuf);
     __syncthreads();
 
     const int total_units = (n_groups + kUnitBlocks - 1) / kUnitBlocks;
@@ -439,7 +438,10 @@ __global__ __launch_bounds__(kDecWaves * 64) void decode_kernel(const uint32_t* 
     if (u < u_end) pre = load_unit(blocks, meta, 0, n_groups, u, lane);
     const int blk = lane & (kUnitBlocks - 1), half = lane >> 5;  // block of the unit and chain of this lane
     for (; u < u_end; u += kDecWaves) {
+        wave_lds_fence();  // the previous unit's image has been read
         store_unit(wbuf, pre, lane);
+        if (lane < kUnitBlocks) wbuf[lane * kStride + kBlockWords] = 0u;  // zero pads of the payload buffer
+        if (lane == 0) wbuf[kUnitBlocks * kStride] = 0u;
         const uint32_t mw = pre.meta;
         if (u + kDecWaves < u_end) pre = load_unit(blocks, meta, 0, n_groups, u + kDecWaves, lane);
         const Lane L = lane_setup(T, mw, S);
@@ -1354,7 +1356,7 @@ static int decode_common(const ecco_model* m, const void* blocks, const uint32_t
     if (model_ready(m) != ECCO_OK) return ECCO_EINVAL;
     const int units = (int)((n_groups + kUnitBlocks - 1) / kUnitBlocks);
     const int cus = cu_count(m->device);
-    const int units_per_wg = std::max(kDecWaves, (units + cus - 1) / cus);
+    const int units_per_wg = std::max(1, (units + cus - 1) / cus);  // small inputs: few units on many compute units (a wavefront's chain is the floor)
     const int grid = (units + units_per_wg - 1) / units_per_wg;
     const size_t lds = decode_lds_bytes(m->S);
     const bool lng = m->max_len > kPeekBits;
