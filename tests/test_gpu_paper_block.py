@@ -122,7 +122,7 @@ def test_fused_gemv_matches_oracle(pb, dev):
     om = _model(pb, S=6, texp=-9, seed=21, skew=2.6)
     m = _both(pb, om)
     rng = np.random.default_rng(22)
-    for rows, gpr in [(1, 1), (5, 3), (17, 32), (40, 33), (300, 2), (64, 64), (9, 70), (700, 5)]:
+    for rows, gpr in [(1, 1), (5, 3), (17, 32), (40, 33), (300, 2), (64, 64), (9, 70), (700, 5), (11, 512)]:  # 512: the widest matrix allowed
         cols = gpr * 128
         w = _groups(rows * 7 + gpr, rows * gpr, scale=2.0 ** -9 * 30).reshape(rows, cols)
         blocks = pb.encode(om, w.view(np.uint16))

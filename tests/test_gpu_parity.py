@@ -260,6 +260,25 @@ def test_ragged_matrix_shapes(dev, oracle, tiny):
             assert y.shape == (batch, rows) and rel_l2(y, want) <= REL_L2, (rows, gpr, batch)
 
 
+def test_widest_matrix(dev, oracle, tiny):
+    """cols = 65536, the documented maximum: 512 column groups per row, 16 column tiles per band in the batch-1 kernel,
+    256 units per 16-row block in the batched one; and one column group more is refused."""
+    m = tiny["m"]
+    rows, cols = 37, 65536
+    w = W.weight_matrix(rows, cols, 0.02, 0.001, 10.0, 31)
+    ob, om = oracle.encode(m.centroids, m.code_lens, w.reshape(-1, 128).view(np.uint16))
+    blocks, meta = E.ecco_encode(m, t16(w, dev))
+    assert np.array_equal(np_blocks(blocks), ob) and np.array_equal(np_meta(meta), om)
+    for batch in (1, 4, 16):
+        x = W.activation(batch, cols, 131 + batch)
+        y = E.ecco_decode_gemv(m, blocks, meta, rows, cols, t16(x, dev)).cpu().numpy()
+        want = oracle.gemv(m.centroids, m.code_lens, ob, om, rows, cols, x.view(np.uint16))
+        assert y.shape == (batch, rows) and rel_l2(y, want) <= REL_L2, batch
+    with pytest.raises(E.EccoError) as e:
+        E.ecco_decode_gemv(m, blocks, meta, 1, cols + 128, t16(np.zeros((1, cols + 128), np.float16), dev))
+    assert e.value.status == -2
+
+
 # ---------------------------------------------------------------------------------------------------
 def _kv_setup(dev, oracle, B, H, T, S):
     k, v = W.kv_cache(B, H, T, 128, seed=3)
