@@ -444,7 +444,7 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f16 weights, f32 accumulate",
+        "dtype": "f32",  # the multiply-adds: FP16 operands (decoded weights, activations), FP32 products and sums
         "data": "synthetic",
         "config": {"workload": f"{args.workload}: {rows}x{cols} FP16 projection, group 128, S={cfg['S']}, 64-byte blocks; "
                                f"fused ecco_decode_gemv batch 1; other rows of the step: {','.join(row_names)}",
