@@ -35,7 +35,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 BYTES_PER_GROUP = 68   # 64-byte payload + 4-byte meta word
 # HBM bytes per launch of the fused batch-1 kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs, scaled by
 # what the same counters read for an 8 MiB plain copy); the summary of those runs is under profiles/
-MEASURED_TRAFFIC_BYTES = {"proj7b": int((4466.7 * 1.994 + 16.0) * 1024)}
+MEASURED_TRAFFIC_BYTES = {"proj7b": int((4465.2 * 1.994 + 16.0) * 1024)}
 
 
 def cpu_baseline(m, blocks_np, meta_np, rows, cols, x_np, budget_s=12.0):

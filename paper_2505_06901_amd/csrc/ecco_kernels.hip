@@ -122,12 +122,28 @@ __device__ __forceinline__ Tables table_pointers(uint32_t* base, int S) {
     tb.cent = reinterpret_cast<const __half*>(base + S * (kPeekEntries + 2 * kK));
     return tb;
 }
-// the whole job with all threads of the workgroup; the caller synchronises afterwards
-__device__ inline Tables stage_tables(uint32_t* base, const uint32_t* __restrict__ dev, int S) {
-    const DevLayout D{S};
-    for (int t = threadIdx.x; t < S * kK; t += blockDim.x) build_table_item(base, S, t, load_table_item(dev, S, t));
-    stage_vec(base + S * (kPeekEntries + kK), dev + D.longtab(), S * kK);
-    stage_vec(base + S * (kPeekEntries + 2 * kK), dev + D.cent(), S * kK / 2);
+// The whole job for a workgroup of at least S * 16 / 2 threads, with a payload prefetch in its shadow: every
+// thread first requests its (up to) two table items, then calls `prefetch` (the loads of its first unit), then
+// builds the tables.  Loads return in issue order and a wait names how many may still be outstanding, so with
+// the items requested first -- the same loads on one straight path in every thread, indices clamped, threads
+// beyond the items repeating the last one -- the build does not wait for the payload.  The lists of the long
+// codes and the centroids are copied only for a model that needs them (behind the payload, then).  The caller
+// synchronises afterwards.
+template <bool kLong, class Prefetch>
+__device__ __forceinline__ Tables stage_tables_around(uint32_t* base, const uint32_t* __restrict__ dev, int S, Prefetch&& prefetch) {
+    const int n = S * kK;
+    const int t0 = min((int)threadIdx.x, n - 1), t1 = min((int)(threadIdx.x + blockDim.x), n - 1);
+    const TableItem i0 = load_table_item(dev, S, t0), i1 = load_table_item(dev, S, t1);
+    __builtin_amdgcn_sched_barrier(0);
+    prefetch();
+    __builtin_amdgcn_sched_barrier(0);
+    build_table_item(base, S, t0, i0);
+    build_table_item(base, S, t1, i1);
+    if (kLong) {
+        const DevLayout D{S};
+        stage_vec(base + S * (kPeekEntries + kK), dev + D.longtab(), S * kK);
+        stage_vec(base + S * (kPeekEntries + 2 * kK), dev + D.cent(), S * kK / 2);
+    }
     return table_pointers(base, S);
 }
 
@@ -312,19 +328,23 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_kernel(const uint32_t* __re
     uint32_t* xt = reinterpret_cast<uint32_t*>(part + kMaxBandRows * kMaxColTiles);
     const uint4* x4 = reinterpret_cast<const uint4*>(x);
 
-    // loads in the order they are needed: table item, x, then the first unit's payload (from HBM)
-    TableItem item{0u, 0u};
-    if (tid < S * kK) item = load_table_item(dev, S, tid);
+    // Loads in the order they are needed: table item, x, then the first unit's payload (from HBM).  Loads
+    // return in issue order and a wait names how many may still be outstanding, so every thread issues the
+    // same loads on one straight path (indices clamped instead of branches around them): only then can the
+    // wait for the table item leave the payload in flight while the tables are built.
+    // (The scheduling barriers keep the compiler from issuing them in another order.)
+    const int ti = min(tid, S * kK - 1);  // threads beyond the items repeat the last one: same values to the same words
+    const TableItem item = load_table_item(dev, S, ti);
+    __builtin_amdgcn_sched_barrier(0);
     static_assert(kXLdsGroups * 16 == 2 * kGemvThreads, "two x pieces per thread");
-    uint4 xp0 = make_uint4(0, 0, 0, 0), xp1 = xp0;
-    if (x_in_lds) {
-        xp0 = x4[min(tid, gpr * 16 - 1)];
-        xp1 = x4[min(tid + kGemvThreads, gpr * 16 - 1)];
-    }
+    const uint4 xp0 = x4[min(tid, gpr * 16 - 1)];
+    const uint4 xp1 = x4[min(tid + kGemvThreads, gpr * 16 - 1)];
+    __builtin_amdgcn_sched_barrier(0);
     int u = wave;
-    UnitLoad pre;
-    if (u < units) pre = load_unit(blocks, meta, row0 + u % band_rows, gpr, u / band_rows, lane);
-    if (tid < S * kK) build_table_item(smem, S, tid, item);
+    const int u_first = min(u, units - 1);  // a wavefront without work loads the band's last unit and drops it
+    UnitLoad pre = load_unit(blocks, meta, row0 + u_first % band_rows, gpr, u_first / band_rows, lane);
+    __builtin_amdgcn_sched_barrier(0);
+    build_table_item(smem, S, ti, item);
     if (kLong) {
         const DevLayout D{S};
         for (int i = tid; i < S * kK; i += kGemvThreads) smem[S * (kPeekEntries + kK) + i] = dev[D.longtab() + i];
@@ -426,16 +446,28 @@ __global__ __launch_bounds__(kDecWaves * 64) void decode_kernel(const uint32_t* 
     extern __shared__ __align__(16) uint32_t smem[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const Tables T = stage_tables(smem, dev, S);
     uint32_t* wbuf = smem + table_words(S) + wave * Cfg::kWaveWords;
     uint4* image = reinterpret_cast<uint4*>(wbuf);
-    __syncthreads();
-
     const int total_units = (n_groups + kUnitBlocks - 1) / kUnitBlocks;
     const int u_end = min(total_units, (int)(blockIdx.x + 1) * units_per_wg);
     int u = blockIdx.x * units_per_wg + wave;
-    UnitLoad pre;
-    if (u < u_end) pre = load_unit(blocks, meta, 0, n_groups, u, lane);
+    // table item first, then the first unit's payload, the same loads in every thread, and the tables are built
+    // while the payload is on its way (see gemv_kernel)
+    static_assert(ECCO_MAX_S * kK <= kDecWaves * 64, "one table item per thread");
+    const int ti = min(tid, S * kK - 1);
+    const TableItem item = load_table_item(dev, S, ti);
+    __builtin_amdgcn_sched_barrier(0);
+    UnitLoad pre = load_unit(blocks, meta, 0, n_groups, min(u, u_end - 1), lane);
+    __builtin_amdgcn_sched_barrier(0);
+    build_table_item(smem, S, ti, item);
+    if (kLong) {
+        const DevLayout D{S};
+        for (int i = tid; i < S * kK; i += kDecWaves * 64) smem[S * (kPeekEntries + kK) + i] = dev[D.longtab() + i];
+        for (int i = tid; i < S * kK / 2; i += kDecWaves * 64) smem[S * (kPeekEntries + 2 * kK) + i] = dev[D.cent() + i];
+    }
+    const Tables T = table_pointers(smem, S);
+    __syncthreads();
+
     const int blk = lane & (kUnitBlocks - 1), half = lane >> 5;  // block of the unit and chain of this lane
     for (; u < u_end; u += kDecWaves) {
         wave_lds_fence();  // the previous unit's image has been read
@@ -918,7 +950,9 @@ __global__ __launch_bounds__(kLongV ? 512 : kAttnThreads) void kv_attend_kernel(
         const int units = (span + kUnitBlocks - 1) / kUnitBlocks, unit0 = s0 / kUnitBlocks;
         // ---- scores of the span
         __syncthreads();
-        const Tables TK = stage_tables(smem, dev_k, Sk);
+        int u = wave;
+        UnitLoad pre;
+        const Tables TK = stage_tables_around<kLongK>(smem, dev_k, Sk, [&] { pre = load_unit(k_blocks, k_meta, bh, T_max, unit0 + min(u, units - 1), lane); });
         __syncthreads();
         float my_max = -INFINITY;
         {
@@ -930,9 +964,6 @@ __global__ __launch_bounds__(kLongV ? 512 : kAttnThreads) void kv_attend_kernel(
                 const uint4 v = qsrc[j];
                 qx[4 * j] = v.x; qx[4 * j + 1] = v.y; qx[4 * j + 2] = v.z; qx[4 * j + 3] = v.w;
             }
-            int u = wave;
-            UnitLoad pre;
-            if (u < units) pre = load_unit(k_blocks, k_meta, bh, T_max, unit0 + u, lane);
             for (; u < units; u += waves) {
                 store_unit(wbuf, pre, lane);
                 const uint32_t mw = pre.meta;
@@ -977,15 +1008,13 @@ __global__ __launch_bounds__(kLongV ? 512 : kAttnThreads) void kv_attend_kernel(
         run_max = new_max;
         // ---- weighted sum of V over the span
         __syncthreads();
-        const Tables TV = stage_tables(smem, dev_v, Sv);
+        u = wave;
+        const Tables TV = stage_tables_around<kLongV>(smem, dev_v, Sv, [&] { pre = load_unit(v_blocks, v_meta, bh, T_max, unit0 + min(u, units - 1), lane); });
         __syncthreads();
         {
             float o[kHalf];
 #pragma unroll
             for (int i = 0; i < kHalf; ++i) o[i] = 0.0f;
-            int u = wave;
-            UnitLoad pre;
-            if (u < units) pre = load_unit(v_blocks, v_meta, bh, T_max, unit0 + u, lane);
             for (; u < units; u += waves) {
                 store_unit(wbuf, pre, lane);
                 // a slot past the sequence end may hold anything (the cache behind seq_len need not be initialised):
@@ -1129,7 +1158,9 @@ __global__ __launch_bounds__(kGqaThreads) void kv_attend_gqa_kernel(const uint32
         const int units = (span + kUnitBlocks - 1) / kUnitBlocks, unit0 = s0 / kUnitBlocks;  // s0 is a multiple of 32
         // ---- scores of the span, all query heads of the group
         __syncthreads();
-        const Tables TK = stage_tables(smem, dev_k, Sk);
+        int u = wave;
+        UnitLoad pre;
+        const Tables TK = stage_tables_around<kLongK>(smem, dev_k, Sk, [&] { pre = load_unit(k_blocks, k_meta, bkv, T_max, unit0 + min(u, units - 1), lane); });
         __syncthreads();
         {
             uint4 bq[kHalf / 8];  // B operands: the query of head blk, dimensions 64 * half + 8j .. + 7
@@ -1137,9 +1168,6 @@ __global__ __launch_bounds__(kGqaThreads) void kv_attend_gqa_kernel(const uint32
             asm volatile("" : "+v"(qsrc));  // reloaded per span rather than kept alive across the V phase
 #pragma unroll
             for (int j = 0; j < kHalf / 8; ++j) bq[j] = head_ok ? qsrc[j] : make_uint4(0u, 0u, 0u, 0u);
-            int u = wave;
-            UnitLoad pre;
-            if (u < units) pre = load_unit(k_blocks, k_meta, bkv, T_max, unit0 + u, lane);
             for (; u < units; u += kGqaWaves) {
                 store_unit(wbuf, pre, lane);
                 const uint32_t mw = pre.meta;
@@ -1195,7 +1223,8 @@ __global__ __launch_bounds__(kGqaThreads) void kv_attend_gqa_kernel(const uint32
         }
         // ---- weighted sum of V over the span
         __syncthreads();
-        const Tables TV = stage_tables(smem, dev_v, Sv);
+        u = wave;
+        const Tables TV = stage_tables_around<kLongV>(smem, dev_v, Sv, [&] { pre = load_unit(v_blocks, v_meta, bkv, T_max, unit0 + min(u, units - 1), lane); });
         __syncthreads();
         {
             const float alpha = head_ok ? st_alpha[blk] : 1.0f;  // every accumulator of a lane belongs to head l % 32
@@ -1203,9 +1232,6 @@ __global__ __launch_bounds__(kGqaThreads) void kv_attend_gqa_kernel(const uint32
             for (int j = 0; j < 4; ++j)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) o[j][i] *= alpha;
-            int u = wave;
-            UnitLoad pre;
-            if (u < units) pre = load_unit(v_blocks, v_meta, bkv, T_max, unit0 + u, lane);
             for (; u < units; u += kGqaWaves) {
                 store_unit(wbuf, pre, lane);
                 // a slot past the range may hold anything: scale 0, so that its values are zeros (NaN * 0 would poison the sum)
