@@ -336,6 +336,7 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_kernel(const uint32_t* __re
     const int ti = min(tid, S * kK - 1);  // threads beyond the items repeat the last one: same values to the same words
     const TableItem item = load_table_item(dev, S, ti);
     __builtin_amdgcn_sched_barrier(0);
+    static_assert(ECCO_MAX_S * kK <= kGemvThreads, "one table item per thread");
     static_assert(kXLdsGroups * 16 == 2 * kGemvThreads, "two x pieces per thread");
     const uint4 xp0 = x4[min(tid, gpr * 16 - 1)];
     const uint4 xp1 = x4[min(tid + kGemvThreads, gpr * 16 - 1)];
@@ -902,6 +903,7 @@ __global__ __launch_bounds__(kEncThreads) void kv_append_minmax_kernel(const uin
 constexpr int kAttnThreads = 768;      // workgroup size; 512 for a V model with long codes
 constexpr int kAttnWaves = kAttnThreads / 64;
 constexpr int kSpan = 8192;
+static_assert(2 * 512 >= ECCO_MAX_S * kK, "stage_tables_around: two table items per thread cover every model (the smallest attention workgroup has 512 threads)");
 inline size_t attn_lds_bytes(int Sk, int Sv) {
     return (table_words(std::max(Sk, Sv)) + (size_t)kAttnWaves * kUnitWords + kSpan + kAttnWaves * kGroup + 64) * 4;
 }
