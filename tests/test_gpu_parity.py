@@ -260,6 +260,40 @@ def test_ragged_matrix_shapes(dev, oracle, tiny):
             assert y.shape == (batch, rows) and rel_l2(y, want) <= REL_L2, (rows, gpr, batch)
 
 
+@pytest.mark.parametrize("S", [1, 3])
+def test_smallest_models(dev, oracle, S):
+    """One pattern (nothing to choose) and three (fewer table items than any workgroup has threads, not a power of
+    two): every entry point of the two-chain format against the oracle."""
+    w = W.weight_matrix(48, 640, 0.02, 0.001, 10.0, 41)
+    m = E.ecco_model_to_device(E.ecco_fit_patterns(w, S, 12, 7), 0)
+    assert m.S == S
+    ob, om = oracle.encode(m.centroids, m.code_lens, w.reshape(-1, 128).view(np.uint16))
+    blocks, meta = E.ecco_encode(m, t16(w, dev))
+    assert np.array_equal(np_blocks(blocks), ob) and np.array_equal(np_meta(meta), om)
+    assert ((om >> 16) & 0x3F).max() < S
+    assert np.array_equal(E.ecco_decode(m, blocks, meta).cpu().numpy().view(np.uint16), oracle.decode(m.centroids, m.code_lens, ob, om))
+    sb, sm = E.ecco_encode_minmax(m, t16(w, dev))
+    wb, wm = oracle.encode_minmax(m.centroids, m.code_lens, w.reshape(-1, 128).view(np.uint16))
+    assert np.array_equal(np_blocks(sb), wb) and np.array_equal(np_meta(sm), wm)
+    for batch in (1, 8):
+        x = W.activation(batch, 640, 141 + batch)
+        y = E.ecco_decode_gemv(m, blocks, meta, 48, 640, t16(x, dev)).cpu().numpy()
+        assert rel_l2(y, oracle.gemv(m.centroids, m.code_lens, ob, om, 48, 640, x.view(np.uint16))) <= REL_L2
+    # the same model for K and V: append two tokens to an empty cache, then attend (plain and grouped, two splits)
+    B, H, T = 2, 2, 40
+    k, v = W.kv_cache(B, H, T, 128, seed=43)
+    kb, km = E.ecco_encode(m, t16(k, dev)); vb, vm = E.ecco_encode(m, t16(v, dev))
+    q = W.activation(B * H * 2, 128, 143).reshape(B, 2 * H, 128)
+    seq = np.array([T, 17], np.int32)
+    args = (np_blocks(kb), np_meta(km), np_blocks(vb), np_meta(vm), seq)
+    want = oracle.kv_attend(m.centroids, m.code_lens, m.centroids, m.code_lens, np.ascontiguousarray(q[:, :H]).view(np.uint16), *args, B, H, T)
+    out = E.ecco_kv_attend(m, m, t16(q[:, :H], dev), kb, km, vb, vm, ti32(seq, dev), B, H, T).cpu().numpy()
+    assert rel_l2(out, want) <= REL_L2
+    want = oracle.kv_attend_gqa(m.centroids, m.code_lens, m.centroids, m.code_lens, q.view(np.uint16), *args, B, 2 * H, H, T)
+    out = E.ecco_kv_attend_gqa(m, m, t16(q, dev), kb, km, vb, vm, ti32(seq, dev), B, 2 * H, H, T, n_splits=2).cpu().numpy()
+    assert rel_l2(out, want) <= REL_L2
+
+
 def test_widest_matrix(dev, oracle, tiny):
     """cols = 65536, the documented maximum: 512 column groups per row, 16 column tiles per band in the batch-1 kernel,
     256 units per 16-row block in the batched one; and one column group more is refused."""
