@@ -171,7 +171,7 @@ def main():
             # the same H query heads over H / group key/value heads: the caches of the first H / group heads of every sequence
             grp = args.gqa_group
             Hkv = H // grp
-            gqa_splits = args.gqa_splits or max(1, 256 // (B * Hkv))
+            gqa_splits = args.gqa_splits or E.ecco_kv_attend_gqa_splits(0, B, Hkv, T)
             take = lambda a: [x[:, :Hkv].contiguous() for x in a]
             gkb, gkm, gvb, gvm = take(kbs), take(kms), take(vbs), take(vms)
             n_ws = (B * H * gqa_splits * 130 * 4) if gqa_splits > 1 else 16

@@ -213,6 +213,11 @@ int ecco_read_stream(const void* src, size_t bytes, uint32_t* out, void* stream)
  * may be uninitialised.  Calls that share a workspace must not overlap.
  * Errors: EINVAL, ESHAPE (sizes, Hq % Hkv, group > 16, n_splits), EALIGN, EHIP. */
 size_t ecco_kv_attend_gqa_workspace(int B, int Hq, int n_splits);
+/* A split count for ecco_kv_attend_gqa: enough token ranges to give every compute unit of `device` a workgroup
+ * (B * Hkv * n_splits >= compute units where the sequences allow it), at least 256 tokens each, at most 256 splits.
+ * `tokens` is the longest sequence to be read.  Returns >= 1, or ESHAPE for a size <= 0.  An unknown device counts
+ * as 256 compute units. */
+int ecco_kv_attend_gqa_splits(int device, int B, int Hkv, int tokens);
 int ecco_kv_attend_gqa(const ecco_model* mk, const ecco_model* mv, const uint16_t* q,
                        const void* k_blocks, const uint32_t* k_meta, const void* v_blocks, const uint32_t* v_meta,
                        const int32_t* seq_len, int B, int Hq, int Hkv, int T_max, int n_splits, void* workspace,

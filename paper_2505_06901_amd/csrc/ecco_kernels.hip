@@ -1480,6 +1480,14 @@ int ecco_kv_append_minmax(const ecco_model* mk, const ecco_model* mv, const uint
     return kv_append_common(true, mk, mv, k_new, v_new, k_blocks, k_meta, v_blocks, v_meta, seq_len, B, H, T_max, stream);
 }
 
+int ecco_kv_attend_gqa_splits(int device, int B, int Hkv, int tokens) {
+    if (B <= 0 || Hkv <= 0 || tokens <= 0) return ECCO_ESHAPE;
+    const long long heads = (long long)B * Hkv;
+    const long long by_units = std::max<long long>(1, cu_count(device) / heads);  // a workgroup for every compute unit
+    const long long by_tokens = ((long long)tokens + 255) / 256;                  // but at least 256 tokens per split
+    return (int)std::min<long long>(std::min(by_units, by_tokens), 256);
+}
+
 size_t ecco_kv_attend_gqa_workspace(int B, int Hq, int n_splits) {
     if (B <= 0 || Hq <= 0 || n_splits <= 1) return 0;
     return (size_t)B * Hq * n_splits * (kGroup + 2) * sizeof(float);

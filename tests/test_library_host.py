@@ -150,6 +150,13 @@ def test_argument_errors_without_gpu(tiny_model):
     assert gqa(8, 2, 2, odd) == -3
     assert gqa(8, 2, 1, null) == -1          # all fine up to the model, which is on no device
     assert L.ecco_kv_attend_gqa_workspace(2, 8, 3) == 2 * 8 * 3 * 130 * 4
+    # split count: a workgroup per compute unit (an unknown device counts as 256), 256 tokens per split at least
+    assert L.ecco_kv_attend_gqa_splits(-1, 8, 8, 4096) == 4
+    assert L.ecco_kv_attend_gqa_splits(-1, 1, 32, 32768) == 8
+    assert L.ecco_kv_attend_gqa_splits(-1, 64, 8, 4096) == 1
+    assert L.ecco_kv_attend_gqa_splits(-1, 1, 4, 300) == 2
+    assert L.ecco_kv_attend_gqa_splits(-1, 1, 1, 1 << 20) == 256
+    assert L.ecco_kv_attend_gqa_splits(-1, 0, 4, 300) == -2
     # the activation codec and the streaming reference take no model: everything but the launch is host logic
     assert L.ecco_act_encode(null, 1, fake, null) == -1 and L.ecco_act_decode(fake, 1, null, null) == -1
     assert L.ecco_act_encode(fake, (1 << 40) + 1, fake, null) == -2
