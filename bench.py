@@ -273,6 +273,7 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    spread = {}  # row -> (median, least, replays, launches per replay) of the per-replay means, graph timing only
 
     if args.eager:
         # every call bracketed by its own pair of events; the host-side launch path (about 10 us per call from
@@ -312,7 +313,20 @@ def main():
             g = capture(one_round)
             g.replay()
             torch.cuda.synchronize()
-            replays = 2 if row.startswith("encode") else 5 if row.startswith("act_") or row == "copy_reference" else max(1, int(np.ceil(max(args.steps, 100) / n)))
+            replays = 2 if row.startswith("encode") else 5 if row.startswith("act_") or row == "copy_reference" else max(5, int(np.ceil(max(args.steps, 100) / n)))
+            # every replay (one launch per rotating copy) between its own pair of events: the median and the least
+            # replay say how steady the row is (replays of few launches include the host's gap between replays)
+            pairs = []
+            for _ in range(replays):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                g.replay()
+                e1.record()
+                pairs.append((e0, e1))
+            torch.cuda.synchronize()
+            per = [a.elapsed_time(b) / n for a, b in pairs]
+            spread[row] = (float(np.median(per)), float(np.min(per)), replays, n)
+            # the row's figure: all replays between one pair of events (no host gaps between short replays)
             ms[row] = timed_replays(g, replays) / (replays * n)
             del g
 
@@ -394,6 +408,8 @@ def main():
     rows_out = {}
     for r in row_names:
         d = {"ms": ms[r]}
+        if r in spread:
+            d["median_ms"], d["min_ms"], d["replays"], d["launches_per_replay"] = spread[r]
         if r.startswith("gemv"):
             b = int(r[4:])
             d["GBps_compressed"] = comp_bytes / (ms[r] * 1e-3) / 1e9
