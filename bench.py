@@ -59,10 +59,28 @@ def cpu_baseline(m, blocks_np, meta_np, rows, cols, x_np, budget_s=12.0):
         passes += 1
     groups = nrows * gpr
     per_pass = spent / passes
+    # one thread, on a slice: about two seconds
+    O.set_threads(1)
+    rows1 = max(1, min(rows, nrows // max(threads, 1)))
+    t1, n1 = 0.0, 0
+    while t1 < 2.0 and n1 < 50:
+        t1 += run(rows1)
+        n1 += 1
+    O.set_threads(threads)
+    cpu = "unknown"
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    cpu = line.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
     return {"value": groups * BYTES_PER_GROUP / per_pass / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
             "sample": f"oracle_gemv batch 1 on the first {nrows} of {rows} rows of the same matrix ({groups} groups), "
                       f"{passes} passes, {spent:.1f} s in all",
-            "gemv_per_s_equiv": 1.0 / (per_pass * rows / nrows)}
+            "gemv_per_s_equiv": 1.0 / (per_pass * rows / nrows),
+            "single_thread_GBps": rows1 * gpr * BYTES_PER_GROUP / (t1 / n1) / 1e9, "cpu": cpu, "host_cpus": os.cpu_count()}
 
 
 def main():
@@ -489,6 +507,13 @@ def main():
     }
     if sweep is not None:
         out["decode_sweep"] = sweep
+    props = torch.cuda.get_device_properties(dev)
+    out["device"] = {"name": props.name, "compute_units": props.multi_processor_count, "memory_bytes": props.total_memory}
+    _, clk, width = E.ecco_device_info(0)
+    if clk and width:
+        # as the runtime reports them (kHz, bits).  The data-sheet 8 TB/s the roofline uses is four transfers per
+        # reported clock on this bus (2 GHz x 8192 bit x 4 / 8)
+        out["device"].update({"memory_clock_kHz": clk, "memory_bus_bits": width, "GBps_at_4_transfers_per_clock": 4.0 * clk * 1e3 * width / 8 / 1e9})
     if kv_needed and selector_quality is not None:
         out["selector_quality"] = selector_quality
     if not args.no_cpu_baseline and want("gemv1"):

@@ -198,6 +198,9 @@ int ecco_kv_attend(const ecco_model* mk, const ecco_model* mv, const uint16_t* q
  * a decoder, it gives the rate at which the machine can merely read them: the practical ceiling that the benchmark prints
  * beside the data-sheet bandwidth.  Errors: EINVAL, ESHAPE (bytes % 16), EALIGN, EHIP. */
 int ecco_read_stream(const void* src, size_t bytes, uint32_t* out, void* stream);
+/* Measurement aid: what the runtime reports for `device` -- compute units, memory clock (kHz) and memory bus width
+ * (bits), printed by the benchmark beside the data-sheet bandwidth its roofline uses.  All three outputs are host pointers.  Errors: EINVAL (null, device < 0), EHIP. */
+int ecco_device_info(int device, int* compute_units, int* memory_clock_khz, int* memory_bus_bits);
 
 /* Grouped-query form of ecco_kv_attend, split over the tokens (Section 5.3: with grouped-query attention several
  * query heads share one key/value head and the matrix-vector products become small matrix products).

@@ -20,7 +20,7 @@ EXPORTS = [
     "ecco_model_S", "ecco_model_centroids", "ecco_model_code_lens", "ecco_model_to_device", "ecco_model_free",
     "ecco_encode", "ecco_decode", "ecco_decode_indices", "ecco_decode_gemv", "ecco_kv_append", "ecco_kv_attend",
     "ecco_encode_minmax", "ecco_kv_append_minmax", "ecco_act_encode", "ecco_act_decode",
-    "ecco_kv_attend_gqa", "ecco_kv_attend_gqa_workspace", "ecco_kv_attend_gqa_splits", "ecco_read_stream",
+    "ecco_kv_attend_gqa", "ecco_kv_attend_gqa_workspace", "ecco_kv_attend_gqa_splits", "ecco_read_stream", "ecco_device_info",
     "ecco_pb_fit", "ecco_pb_model_create", "ecco_pb_model_S", "ecco_pb_model_texp", "ecco_pb_model_centroids",
     "ecco_pb_model_code_lens", "ecco_pb_model_kp_lens", "ecco_pb_model_to_device", "ecco_pb_model_free",
     "ecco_pb_encode", "ecco_pb_decode", "ecco_pb_decode_gemv", "ecco_pb_model_save", "ecco_pb_model_load",
@@ -67,6 +67,8 @@ def lib():
         L.ecco_kv_attend_gqa_workspace.restype = sz
         L.ecco_kv_attend_gqa_splits.argtypes = [i32, i32, i32, i32]
         L.ecco_kv_attend_gqa_splits.restype = i32
+        L.ecco_device_info.argtypes = [i32, C.POINTER(C.c_int), C.POINTER(C.c_int), C.POINTER(C.c_int)]
+        L.ecco_device_info.restype = i32
         L.ecco_pb_fit.argtypes = [vp, sz, i32, u64, C.POINTER(vp)]
         L.ecco_pb_model_create.argtypes = [vp, vp, vp, i32, i32, C.POINTER(vp)]
         for name in ("ecco_pb_model_S", "ecco_pb_model_texp", "ecco_pb_model_centroids", "ecco_pb_model_code_lens",
@@ -251,6 +253,13 @@ def ecco_kv_attend(mk: Model, mv: Model, q, k_blocks, k_meta, v_blocks, v_meta, 
     _check(lib().ecco_kv_attend(mk.handle, mv.handle, _dp(q), _dp(k_blocks), _dp(k_meta), _dp(v_blocks), _dp(v_meta),
                                 _dp(seq_len), B, H, T_max, _dp(out), _stream()), "ecco_kv_attend")
     return out
+
+
+def ecco_device_info(device: int = 0):
+    """(compute units, memory clock in kHz, memory bus width in bits) as the runtime reports them."""
+    cu, clk, bits = C.c_int(0), C.c_int(0), C.c_int(0)
+    _check(lib().ecco_device_info(device, C.byref(cu), C.byref(clk), C.byref(bits)), "ecco_device_info")
+    return cu.value, clk.value, bits.value
 
 
 def ecco_kv_attend_gqa_splits(device: int, B: int, Hkv: int, tokens: int) -> int:

@@ -199,6 +199,14 @@ int ecco_act_encode(const uint16_t* src, size_t n_groups, void* blocks, void* st
     return ECCO_OK;
 }
 
+int ecco_device_info(int device, int* compute_units, int* memory_clock_khz, int* memory_bus_bits) {
+    if (!compute_units || !memory_clock_khz || !memory_bus_bits || device < 0) return ECCO_EINVAL;
+    ECCO_HIP_CHECK(hipDeviceGetAttribute(compute_units, hipDeviceAttributeMultiprocessorCount, device));
+    ECCO_HIP_CHECK(hipDeviceGetAttribute(memory_clock_khz, hipDeviceAttributeMemoryClockRate, device));
+    ECCO_HIP_CHECK(hipDeviceGetAttribute(memory_bus_bits, hipDeviceAttributeMemoryBusWidth, device));
+    return ECCO_OK;
+}
+
 int ecco_read_stream(const void* src, size_t bytes, uint32_t* out, void* stream) {
     if (!src || !out) return ECCO_EINVAL;
     if (bytes % 16 != 0) return ECCO_ESHAPE;

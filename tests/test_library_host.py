@@ -164,6 +164,8 @@ def test_argument_errors_without_gpu(tiny_model):
     assert L.ecco_act_encode(null, 0, null, null) == 0 and L.ecco_act_decode(null, 0, null, null) == 0
     assert L.ecco_read_stream(fake, 24, fake, null) == -2 and L.ecco_read_stream(odd, 32, fake, null) == -3
     assert L.ecco_read_stream(fake, 0, fake, null) == 0
+    one = C.c_int(0)
+    assert L.ecco_device_info(0, None, C.byref(one), C.byref(one)) == -1 and L.ecco_device_info(-1, C.byref(one), C.byref(one), C.byref(one)) == -1
 
 
 def test_paper_block_argument_errors_without_gpu():
