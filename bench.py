@@ -503,7 +503,8 @@ def main():
                      "kernel": "fused decode-GEMV, batch 1", "bytes_per_launch": comp_bytes,
                      "avg_launch_ms": ms.get(metric_row)},
         "rows": rows_out,
-        "footprint": {"fp16_bytes": n_groups * 256, "compressed_bytes": comp_bytes, "ratio": 256.0 / BYTES_PER_GROUP},
+        "footprint": {"fp16_bytes": n_groups * 256, "compressed_bytes": comp_bytes, "ratio": 256.0 / BYTES_PER_GROUP,
+                      "payload_bytes": n_groups * 64, "meta_bytes": n_groups * 4, "model_blob_bytes": len(E.ecco_model_save(m))},
     }
     if sweep is not None:
         out["decode_sweep"] = sweep
