@@ -517,6 +517,15 @@ def test_gqa_long_context(dev, oracle):
                                     np_blocks(kb), np_meta(km), np_blocks(vb), np_meta(vm), seq, B, Hkv * grp, Hkv, T)
         for h in range(Hkv * grp):
             assert rel_l2(out[0, h], want[0, h]) <= REL_L2, (seq_len, splits, h)
+    # the plain kernel on the same cache: 20 000 tokens are three spans of its running softmax
+    q1 = np.ascontiguousarray(q[:, :Hkv])
+    for seq_len in (T, 8192, 8193):
+        seq = np.array([seq_len], np.int32)
+        out = E.ecco_kv_attend(mk, mv, t16(q1, dev), kb, km, vb, vm, ti32(seq, dev), B, Hkv, T).cpu().numpy()
+        want = oracle.kv_attend(mk.centroids, mk.code_lens, mv.centroids, mv.code_lens, q1.view(np.uint16),
+                                np_blocks(kb), np_meta(km), np_blocks(vb), np_meta(vm), seq, B, Hkv, T)
+        for h in range(Hkv):
+            assert rel_l2(out[0, h], want[0, h]) <= REL_L2, (seq_len, h)
 
 
 # ---------------------------------------------------------------------------------------------------
