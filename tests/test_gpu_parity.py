@@ -665,3 +665,73 @@ def test_repeated_launches_are_identical(dev, oracle):
         for _ in range(40):
             again = E.ecco_decode_gemv(m, blocks, meta, rows, cols, x)
             assert torch.equal(first, again), batch
+
+
+def test_graph_replay_matches_eager(dev, oracle, tiny):
+    """Every entry point of the two-chain format recorded into one HIP graph and replayed three times on inputs that
+    change between the replays (with eager work and synchronisation in between): every replay must give the bits the
+    eager calls give on the same inputs."""
+    m = tiny["m"]
+    rows, cols = 64, 1024
+    B, H, T = 2, 4, 96
+    k, v, mk, mv = _kv_setup(dev, oracle, B, H, T, 8)
+
+    def inputs(seed):
+        w = W.weight_matrix(rows, cols, 0.02, 0.001, 10.0, seed)
+        x = W.activation(8, cols, seed + 1)
+        q = W.activation(B * H, 128, seed + 2).reshape(B, H, 128)
+        kn = W.activation(B * H, 128, seed + 3).reshape(B, H, 128)
+        vn = W.activation(B * H, 128, seed + 4).reshape(B, H, 128)
+        return [t16(a, dev) for a in (w, x, q, kn, vn)]
+
+    w_in, x_in, q_in, kn_in, vn_in = inputs(50)
+    kb, km = E.ecco_encode(mk, t16(k, dev)); vb, vm = E.ecco_encode(mv, t16(v, dev))
+    kb0, km0, vb0, vm0 = kb.clone(), km.clone(), vb.clone(), vm.clone()
+    seq = ti32(np.array([T - 1, 40], np.int32), dev)
+    blocks = torch.empty((rows * cols // 128, 64), dtype=torch.uint8, device=dev)
+    meta = torch.empty((rows * cols // 128,), dtype=torch.int32, device=dev)
+    dec = torch.empty((rows, cols), dtype=torch.float16, device=dev)
+    y1 = torch.empty((1, rows), dtype=torch.float32, device=dev)
+    y8 = torch.empty((8, rows), dtype=torch.float32, device=dev)
+    att = torch.empty((B, H, 128), dtype=torch.float32, device=dev)
+    gqa = torch.empty((B, H, 128), dtype=torch.float32, device=dev)
+    ws = torch.empty((B * H * 2 * 130 * 4,), dtype=torch.uint8, device=dev)  # ecco_kv_attend_gqa_workspace(B, Hq, 2) bytes
+    ab = torch.empty((rows * cols // 64, 64), dtype=torch.uint8, device=dev)
+    adec = torch.empty((rows, cols), dtype=torch.float16, device=dev)
+
+    outs = lambda: [t.clone() for t in (blocks, meta, dec, y1, y8, att, gqa, ab, adec, kb, km, vb, vm)]
+    seq1 = seq + 1  # built outside the capture: the graph holds kernels of the library only
+    def run_all():  # what is recorded: calls of the library only
+        E.ecco_encode(m, w_in, blocks, meta)
+        E.ecco_decode(m, blocks, meta, dec)
+        E.ecco_decode_gemv(m, blocks, meta, rows, cols, x_in[:1], y1)
+        E.ecco_decode_gemv(m, blocks, meta, rows, cols, x_in, y8)
+        E.ecco_kv_append(mk, mv, kn_in, vn_in, kb, km, vb, vm, seq, B, H, T)
+        E.ecco_kv_attend(mk, mv, q_in, kb, km, vb, vm, seq1, B, H, T, att)
+        E.ecco_kv_attend_gqa(mk, mv, q_in, kb, km, vb, vm, seq1, B, H, H // 2, T, 2, ws, gqa)
+        E.ecco_act_encode(w_in, ab)
+        E.ecco_act_decode(ab, adec)
+
+    run_all()  # warm-up outside the capture (kernel attributes are set on first use)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        run_all()
+    for rep, seed in enumerate((60, 70, 80)):
+        new = inputs(seed)
+        for dst, src in zip((w_in, x_in, q_in, kn_in, vn_in), new):
+            dst.copy_(src)
+        for dst, src in zip((kb, km, vb, vm), (kb0, km0, vb0, vm0)):
+            dst.copy_(src)
+        run_all()
+        torch.cuda.synchronize()
+        want = outs()
+        for t in (blocks, meta, dec, y1, y8, att, gqa, ab, adec):
+            t.zero_()
+        for dst, src in zip((kb, km, vb, vm), (kb0, km0, vb0, vm0)):
+            dst.copy_(src)
+        _ = (dec.float() @ dec.float().T).sum().item()  # eager work of the program's own between the replays
+        g.replay()
+        torch.cuda.synchronize()
+        for i, (a, b) in enumerate(zip(outs(), want)):
+            assert torch.equal(a.view(torch.uint8), b.view(torch.uint8)), (rep, i)
