@@ -673,33 +673,57 @@ struct EncChoice {
 // reconstructed values fp16(centroid * s) of those patterns into E.recon, nearest value per element
 // (strict <: the lowest index wins a tie), squared errors summed by the balanced tree, least sum
 // wins (strict <: the lowest pattern wins a tie).  p0 < p1.
+// Choosing the pattern needs the least distance of every element, not the index that attains it: the squared
+// error of an element is that distance squared, whichever of several equally near values is taken.  So the
+// patterns are rated with a subtraction per candidate and a three-way minimum per two candidates, and the
+// index scan (a subtraction, a compare and a select per candidate) runs once, for the winner.
 __device__ inline EncChoice search_patterns(const EncLds& E, int p0, int p1, float s, float x0, float x1) {
     const int lane = threadIdx.x & 63;
     for (int i = p0 * kK + lane; i < p1 * kK; i += 64) E.recon[i] = half_bits_f(dequant_bits(__half_as_ushort(E.cent[i]), s));
     wave_lds_fence();
     EncChoice best{0.0f, p0, 0u};
-    for (int p = p0; p < p1; ++p) {
-        const float* r = E.recon + p * kK;
-        // The reconstructed values ascend with k, and FP32 rounding is monotone, so |x - r[k]| falls (weakly) up to its
-        // least value and rises (weakly) after it: the first index of the least distance -- what a scan with a strict <
-        // finds -- is the last k at which the distance strictly drops.  One compare and one select per candidate.
-        float d0 = fabsf(__fsub_rn(x0, r[0])), d1 = fabsf(__fsub_rn(x1, r[0]));
-        uint32_t k0 = 0, k1 = 0;
+    if (p1 - p0 > 1) {
+        for (int p = p0; p < p1; ++p) {
+            const float* r = E.recon + p * kK;
+            float d0 = fabsf(__fsub_rn(x0, r[0])), d1 = fabsf(__fsub_rn(x1, r[0]));
+            static_assert(kK % 2 == 0, "candidates 1 .. kK - 2 in pairs, the last one alone");
 #pragma unroll
-        for (int k = 1; k < kK; ++k) {
-            const float rk = r[k];
-            const float a = fabsf(__fsub_rn(x0, rk)), b = fabsf(__fsub_rn(x1, rk));
-            k0 = a < d0 ? (uint32_t)k : k0;
-            k1 = b < d1 ? (uint32_t)k : k1;
-            d0 = a;
-            d1 = b;
+            for (int k = 1; k + 1 < kK; k += 2) {
+                const float ra = r[k], rb = r[k + 1];
+                d0 = fminf(fminf(d0, fabsf(__fsub_rn(x0, ra))), fabsf(__fsub_rn(x0, rb)));
+                d1 = fminf(fminf(d1, fabsf(__fsub_rn(x1, ra))), fabsf(__fsub_rn(x1, rb)));
+            }
+            d0 = fminf(d0, fabsf(__fsub_rn(x0, r[kK - 1])));
+            d1 = fminf(d1, fabsf(__fsub_rn(x1, r[kK - 1])));
+            // tree level 0: values 2l and 2l+1; levels 1..6 over the lanes: aligned blocks of 2, 4, 8, 16 lanes by
+            // cross-lane moves (every lane of a block holds the block's sum, so a mirror pairs the same two
+            // blocks as the xor butterfly), then (row 0 + row 1) + (row 2 + row 3)
+            const float v = wave_sum(__fadd_rn(__fmul_rn(d0, d0), __fmul_rn(d1, d1)));
+            if (p == p0 || v < best.sse) {
+                best.sse = v;
+                best.pattern = p;
+            }
         }
+    }
+    // The indices of the chosen pattern.  The reconstructed values ascend with k, and FP32 rounding is monotone, so
+    // |x - r[k]| falls (weakly) up to its least value and rises (weakly) after it: the first index of the least
+    // distance -- what a scan with a strict < finds -- is the last k at which the distance strictly drops.
+    const float* r = E.recon + best.pattern * kK;
+    float d0 = fabsf(__fsub_rn(x0, r[0])), d1 = fabsf(__fsub_rn(x1, r[0]));
+    uint32_t k0 = 0, k1 = 0;
+#pragma unroll
+    for (int k = 1; k < kK; ++k) {
+        const float rk = r[k];
+        const float a = fabsf(__fsub_rn(x0, rk)), b = fabsf(__fsub_rn(x1, rk));
+        k0 = a < d0 ? (uint32_t)k : k0;
+        k1 = b < d1 ? (uint32_t)k : k1;
+        d0 = a;
+        d1 = b;
+    }
+    best.idx = k0 | (k1 << 4);
+    if (p1 - p0 == 1) {
         const float e0 = __fsub_rn(x0, r[k0]), e1 = __fsub_rn(x1, r[k1]);
-        // tree level 0: values 2l and 2l+1; levels 1..6 over the lanes: aligned blocks of 2, 4, 8, 16 lanes by
-        // cross-lane moves (every lane of a block holds the block's sum, so a mirror pairs the same two
-        // blocks as the xor butterfly), then (row 0 + row 1) + (row 2 + row 3)
-        const float v = wave_sum(__fadd_rn(__fmul_rn(e0, e0), __fmul_rn(e1, e1)));
-        if (p == p0 || v < best.sse) best = EncChoice{v, p, k0 | (k1 << 4)};
+        best.sse = wave_sum(__fadd_rn(__fmul_rn(e0, e0), __fmul_rn(e1, e1)));
     }
     return best;
 }

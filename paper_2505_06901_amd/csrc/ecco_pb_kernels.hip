@@ -428,14 +428,34 @@ __global__ __launch_bounds__(kEncThreads) void pb_encode_kernel(const uint32_t* 
         if (lane < kBitWords) bits[lane] = 0u;
         wave_lds_fence();
         // pattern of least squared error over the other 127 elements
+        // Rating a pattern needs every element's least distance, not the index that attains it (the squared error is
+        // that distance squared): a subtraction per candidate and a three-way minimum per two candidates.  The index
+        // scan runs once, for the winner.
         float best_sse = 0.0f;
         int best_p = 0;
-        uint32_t best_idx = 0;
         for (int p = 0; p < S; ++p) {
             const float* r = recon + p * 16;
+            float d0 = fabsf(__fsub_rn(x0, r[0])), d1 = fabsf(__fsub_rn(x1, r[0]));
+            static_assert(kCent % 2 == 1, "candidates 1 .. kCent - 1 in pairs");
+#pragma unroll
+            for (int k = 1; k < kCent; k += 2) {
+                const float ra = r[k], rb = r[k + 1];
+                d0 = fminf(fminf(d0, fabsf(__fsub_rn(x0, ra))), fabsf(__fsub_rn(x0, rb)));
+                d1 = fminf(fminf(d1, fabsf(__fsub_rn(x1, ra))), fabsf(__fsub_rn(x1, rb)));
+            }
+            const float q0 = is0 ? 0.0f : __fmul_rn(d0, d0), q1 = is1 ? 0.0f : __fmul_rn(d1, d1);
+            const float sse = wave_tree_sum(__fadd_rn(q0, q1));
+            if (p == 0 || sse < best_sse) {
+                best_sse = sse;
+                best_p = p;
+            }
+        }
+        uint32_t best_idx;
+        {
             // the reconstructed values ascend with k and FP32 rounding is monotone, so the distance falls (weakly) to its
             // least value and rises (weakly) after it: the first index of the least distance -- what a scan with a strict <
             // finds -- is the last k at which the distance strictly drops
+            const float* r = recon + best_p * 16;
             float d0 = fabsf(__fsub_rn(x0, r[0])), d1 = fabsf(__fsub_rn(x1, r[0]));
             uint32_t k0 = 0, k1 = 0;
 #pragma unroll
@@ -447,14 +467,7 @@ __global__ __launch_bounds__(kEncThreads) void pb_encode_kernel(const uint32_t* 
                 d0 = u;
                 d1 = v;
             }
-            const float e0 = __fsub_rn(x0, r[k0]), e1 = __fsub_rn(x1, r[k1]);
-            const float q0 = is0 ? 0.0f : __fmul_rn(e0, e0), q1 = is1 ? 0.0f : __fmul_rn(e1, e1);
-            const float sse = wave_tree_sum(__fadd_rn(q0, q1));
-            if (p == 0 || sse < best_sse) {
-                best_sse = sse;
-                best_p = p;
-                best_idx = k0 | (k1 << 4);
-            }
+            best_idx = k0 | (k1 << 4);
         }
         const uint32_t i0 = is0 ? 15u : (best_idx & 15u), i1 = is1 ? 15u : (best_idx >> 4);
         // the codebook of least total length
