@@ -663,6 +663,25 @@ __device__ inline uint32_t group_scale_bits(uint32_t hx0, uint32_t hx1) {
     return wave_all(max(hx0 & 0x7FFFu, hx1 & 0x7FFFu), [](uint32_t a, uint32_t b) { return max(a, b); });
 }
 
+// Sixteen sums over the 64 lanes at once, each in the balanced tree (lanes l and l ^ 1, then ^ 2, ^ 4, ... ^ 32):
+// at every one of the first four levels a lane keeps the half of its entries that matches its own lane bit and
+// sends the other half to its partner, so the work halves per level instead of being done sixteen times over.
+// Lane l returns the total of entry l & 15.  (Addition is commutative, so own + received is the tree's sum.)
+__device__ __forceinline__ float wave_sum16(const float (&q)[16], int lane) {
+    const bool b0 = lane & 1, b1 = lane & 2, b2 = lane & 4, b3 = lane & 8;
+    float a[8], b[4], c[2];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) a[i] = (b0 ? q[2 * i + 1] : q[2 * i]) + dpp_mov<0xB1>(b0 ? q[2 * i] : q[2 * i + 1]);    // entry 2i + b0
+#pragma unroll
+    for (int i = 0; i < 4; ++i) b[i] = (b1 ? a[2 * i + 1] : a[2 * i]) + dpp_mov<0x4E>(b1 ? a[2 * i] : a[2 * i + 1]);    // entry 4i + (l & 3)
+#pragma unroll
+    for (int i = 0; i < 2; ++i) c[i] = (b2 ? b[2 * i + 1] : b[2 * i]) + __shfl_xor(b2 ? b[2 * i] : b[2 * i + 1], 4);    // entry 8i + (l & 7)
+    float t = (b3 ? c[1] : c[0]) + __shfl_xor(b3 ? c[0] : c[1], 8);                                                    // entry l & 15
+    t += __shfl_xor(t, 16);
+    t += __shfl_xor(t, 32);
+    return t;
+}
+
 struct EncChoice {
     float sse;         // squared error of the best pattern so far (uniform over the wavefront)
     int pattern;
@@ -683,27 +702,44 @@ __device__ inline EncChoice search_patterns(const EncLds& E, int p0, int p1, flo
     wave_lds_fence();
     EncChoice best{0.0f, p0, 0u};
     if (p1 - p0 > 1) {
-        for (int p = p0; p < p1; ++p) {
-            const float* r = E.recon + p * kK;
-            float d0 = fabsf(__fsub_rn(x0, r[0])), d1 = fabsf(__fsub_rn(x1, r[0]));
-            static_assert(kK % 2 == 0, "candidates 1 .. kK - 2 in pairs, the last one alone");
+        // Sixteen patterns at a time: q[e] is this lane's part (two elements) of the squared error of pattern pb + e.
+        // The sixteen sums over the wavefront are formed together (wave_sum16): lane l ends up with the total of
+        // pattern pb + (l & 15), keeps the least it has seen over the batches, and the lanes are compared at the end.
+        float mine = __builtin_inff();
+        int mine_p = p0;
+        for (int pb = p0; pb < p1; pb += 16) {
+            float q[16];
 #pragma unroll
-            for (int k = 1; k + 1 < kK; k += 2) {
-                const float ra = r[k], rb = r[k + 1];
-                d0 = fminf(fminf(d0, fabsf(__fsub_rn(x0, ra))), fabsf(__fsub_rn(x0, rb)));
-                d1 = fminf(fminf(d1, fabsf(__fsub_rn(x1, ra))), fabsf(__fsub_rn(x1, rb)));
+            for (int e = 0; e < 16; ++e) {
+                q[e] = __builtin_inff();
+                if (pb + e < p1) {  // uniform
+                    const float* r = E.recon + (pb + e) * kK;
+                    float d0 = fabsf(__fsub_rn(x0, r[0])), d1 = fabsf(__fsub_rn(x1, r[0]));
+                    static_assert(kK % 2 == 0, "candidates 1 .. kK - 2 in pairs, the last one alone");
+#pragma unroll
+                    for (int k = 1; k + 1 < kK; k += 2) {
+                        const float ra = r[k], rb = r[k + 1];
+                        d0 = fminf(fminf(d0, fabsf(__fsub_rn(x0, ra))), fabsf(__fsub_rn(x0, rb)));
+                        d1 = fminf(fminf(d1, fabsf(__fsub_rn(x1, ra))), fabsf(__fsub_rn(x1, rb)));
+                    }
+                    d0 = fminf(d0, fabsf(__fsub_rn(x0, r[kK - 1])));
+                    d1 = fminf(d1, fabsf(__fsub_rn(x1, r[kK - 1])));
+                    q[e] = __fadd_rn(__fmul_rn(d0, d0), __fmul_rn(d1, d1));  // tree level 0: values 2l and 2l+1
+                }
             }
-            d0 = fminf(d0, fabsf(__fsub_rn(x0, r[kK - 1])));
-            d1 = fminf(d1, fabsf(__fsub_rn(x1, r[kK - 1])));
-            // tree level 0: values 2l and 2l+1; levels 1..6 over the lanes: aligned blocks of 2, 4, 8, 16 lanes by
-            // cross-lane moves (every lane of a block holds the block's sum, so a mirror pairs the same two
-            // blocks as the xor butterfly), then (row 0 + row 1) + (row 2 + row 3)
-            const float v = wave_sum(__fadd_rn(__fmul_rn(d0, d0), __fmul_rn(d1, d1)));
-            if (p == p0 || v < best.sse) {
-                best.sse = v;
-                best.pattern = p;
+            const float t = wave_sum16(q, lane);
+            const int tp = pb + (lane & 15);
+            if (t < mine) {  // strict <: an earlier batch keeps a tie
+                mine = t;
+                mine_p = tp;
             }
         }
+        // least sum over the lanes, and the lowest pattern among the lanes that hold it (a pattern past p1 holds +inf;
+        // if every sum is +inf or the input held a NaN, against the contract, p0 stays)
+        best.sse = wave_all(mine, [](float a, float b) { return fminf(a, b); });
+        const int cand = (mine == best.sse && mine_p < p1) ? mine_p : 0x7FFFFFFF;
+        const int win = wave_all(cand, [](int a, int b) { return min(a, b); });
+        best.pattern = win < p1 ? win : p0;
     }
     // The indices of the chosen pattern.  The reconstructed values ascend with k, and FP32 rounding is monotone, so
     // |x - r[k]| falls (weakly) up to its least value and rises (weakly) after it: the first index of the least

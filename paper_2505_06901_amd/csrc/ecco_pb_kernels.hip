@@ -205,6 +205,25 @@ __device__ __forceinline__ float wave_tree_sum(float t) {
     return __fadd_rn(__fadd_rn(g(lane_u32(f(t), 0)), g(lane_u32(f(t), 16))), __fadd_rn(g(lane_u32(f(t), 32)), g(lane_u32(f(t), 48))));
 }
 
+// Sixteen such sums at once: at each of the first four levels a lane keeps the half of its entries that matches its
+// own lane bit and sends the other half to its partner (lanes l and l ^ 1, ^ 2, ^ 4, ^ 8), then the two remaining
+// levels (^ 16, ^ 32) on the one entry left: lane l returns the total of entry l & 15, summed in the same tree.
+__device__ __forceinline__ float wave_tree_sum16(const float (&q)[16], int lane) {
+    const auto x1 = [](float v) { return __uint_as_float(dpp_u32<0xB1>(__float_as_uint(v))); };
+    const auto x2 = [](float v) { return __uint_as_float(dpp_u32<0x4E>(__float_as_uint(v))); };
+    const bool b0 = lane & 1, b1 = lane & 2, b2 = lane & 4, b3 = lane & 8;
+    float a[8], b[4], c[2];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) a[i] = __fadd_rn(b0 ? q[2 * i + 1] : q[2 * i], x1(b0 ? q[2 * i] : q[2 * i + 1]));
+#pragma unroll
+    for (int i = 0; i < 4; ++i) b[i] = __fadd_rn(b1 ? a[2 * i + 1] : a[2 * i], x2(b1 ? a[2 * i] : a[2 * i + 1]));
+#pragma unroll
+    for (int i = 0; i < 2; ++i) c[i] = __fadd_rn(b2 ? b[2 * i + 1] : b[2 * i], __shfl_xor(b2 ? b[2 * i] : b[2 * i + 1], 4));
+    float t = __fadd_rn(b3 ? c[1] : c[0], __shfl_xor(b3 ? c[0] : c[1], 8));
+    t = __fadd_rn(t, __shfl_xor(t, 16));
+    return __fadd_rn(t, __shfl_xor(t, 32));
+}
+
 // ---- decode fused into the matrix-vector product --------------------------------------------------------------------
 // y = W x without writing W: a workgroup owns a band of rows (its blocks are consecutive in memory); a wavefront
 // takes 64 consecutive blocks of the band at a time, one per lane, exactly as the decoder does.  The lane keeps the
@@ -431,25 +450,41 @@ __global__ __launch_bounds__(kEncThreads) void pb_encode_kernel(const uint32_t* 
         // Rating a pattern needs every element's least distance, not the index that attains it (the squared error is
         // that distance squared): a subtraction per candidate and a three-way minimum per two candidates.  The index
         // scan runs once, for the winner.
-        float best_sse = 0.0f;
-        int best_p = 0;
-        for (int p = 0; p < S; ++p) {
-            const float* r = recon + p * 16;
-            float d0 = fabsf(__fsub_rn(x0, r[0])), d1 = fabsf(__fsub_rn(x1, r[0]));
-            static_assert(kCent % 2 == 1, "candidates 1 .. kCent - 1 in pairs");
+        // Sixteen patterns at a time: q[e] is this lane's part of the squared error of pattern pb + e; the sixteen sums
+        // over the wavefront are formed together (wave_tree_sum16: lane l ends up with the total of pattern
+        // pb + (l & 15)), every lane keeps the least it has seen, and the lanes are compared at the end.
+        float mine = __builtin_inff();
+        int mine_p = 0;
+        for (int pb = 0; pb < S; pb += 16) {
+            float q[16];
 #pragma unroll
-            for (int k = 1; k < kCent; k += 2) {
-                const float ra = r[k], rb = r[k + 1];
-                d0 = fminf(fminf(d0, fabsf(__fsub_rn(x0, ra))), fabsf(__fsub_rn(x0, rb)));
-                d1 = fminf(fminf(d1, fabsf(__fsub_rn(x1, ra))), fabsf(__fsub_rn(x1, rb)));
+            for (int e = 0; e < 16; ++e) {
+                q[e] = __builtin_inff();
+                if (pb + e < S) {  // uniform
+                    const float* r = recon + (pb + e) * 16;
+                    float d0 = fabsf(__fsub_rn(x0, r[0])), d1 = fabsf(__fsub_rn(x1, r[0]));
+                    static_assert(kCent % 2 == 1, "candidates 1 .. kCent - 1 in pairs");
+#pragma unroll
+                    for (int k = 1; k < kCent; k += 2) {
+                        const float ra = r[k], rb = r[k + 1];
+                        d0 = fminf(fminf(d0, fabsf(__fsub_rn(x0, ra))), fabsf(__fsub_rn(x0, rb)));
+                        d1 = fminf(fminf(d1, fabsf(__fsub_rn(x1, ra))), fabsf(__fsub_rn(x1, rb)));
+                    }
+                    const float q0 = is0 ? 0.0f : __fmul_rn(d0, d0), q1 = is1 ? 0.0f : __fmul_rn(d1, d1);
+                    q[e] = __fadd_rn(q0, q1);
+                }
             }
-            const float q0 = is0 ? 0.0f : __fmul_rn(d0, d0), q1 = is1 ? 0.0f : __fmul_rn(d1, d1);
-            const float sse = wave_tree_sum(__fadd_rn(q0, q1));
-            if (p == 0 || sse < best_sse) {
-                best_sse = sse;
-                best_p = p;
+            const float t = wave_tree_sum16(q, lane);
+            if (t < mine) {  // strict <: an earlier batch keeps a tie
+                mine = t;
+                mine_p = pb + (lane & 15);
             }
         }
+        // least sum over the lanes, and the lowest pattern among the lanes that hold it
+        const float least = __uint_as_float(wave_all_u32(__float_as_uint(mine), [](uint32_t a, uint32_t b) { return __float_as_uint(fminf(__uint_as_float(a), __uint_as_float(b))); }));
+        const uint32_t cand = (mine == least && mine_p < S) ? (uint32_t)mine_p : 0x7FFFFFFFu;
+        const uint32_t win = wave_all_u32(cand, [](uint32_t a, uint32_t b) { return min(a, b); });
+        const int best_p = win < (uint32_t)S ? (int)win : 0;
         uint32_t best_idx;
         {
             // the reconstructed values ascend with k and FP32 rounding is monotone, so the distance falls (weakly) to its
