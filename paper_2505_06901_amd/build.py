@@ -19,6 +19,12 @@ def _hipcc() -> str:
     return "hipcc"
 
 
+# Kernels that may park a few scalar registers in vector-register lanes.  Only the grouped-query attention kernel
+# for two models with long codes does (4 registers); the batched matrix-vector kernel gave wrong sums, not
+# reproducibly, in a variant whose long-code instantiation parked 8, so every other kernel has to stay clear.
+_SGPR_SPILL_TOLERATED = ("kv_attend_gqa_kernelILb1ELb1E",)
+
+
 def _check_kernel_resources(remarks: str, verbose: bool) -> None:
     """Every kernel must keep its working set in registers: a kernel that spills to scratch memory is
     far off its design point (the decode loops are sized for 1024-thread workgroups, 128 VGPRs), so
@@ -36,6 +42,13 @@ def _check_kernel_resources(remarks: str, verbose: bool) -> None:
                 print("  %s: scratch %s bytes/lane" % (name, m.group(1)))
             if int(m.group(1)) != 0 and not os.environ.get("ECCO_ALLOW_SCRATCH"):
                 raise RuntimeError("kernel %s spills %s bytes/lane to scratch memory" % (name, m.group(1)))
+        m = re.search(r"remark:\s+(SGPRs|VGPRs) Spill: (\d+)", line)
+        if m and name:
+            if verbose and int(m.group(2)):
+                print("  %s: %s spilled: %s" % (name, m.group(1), m.group(2)))
+            tolerated = m.group(1) == "SGPRs" and any(k in name for k in _SGPR_SPILL_TOLERATED)
+            if int(m.group(2)) != 0 and not tolerated and not os.environ.get("ECCO_ALLOW_SCRATCH"):
+                raise RuntimeError("kernel %s spills %s %s" % (name, m.group(2), m.group(1)))
     if found == 0:
         raise RuntimeError("no kernel resource remarks found: cannot verify register use")
 

@@ -546,7 +546,9 @@ __global__ __launch_bounds__(kDecWaves * 64) void decode_kernel(const uint32_t* 
 constexpr int kMmaRows = 16;
 constexpr int kMaxBatch = 16;
 typedef float float4_t __attribute__((ext_vector_type(4)));
-inline size_t gemm_lds_bytes(int S) { return (table_words(S) + (size_t)kWaves * kUnitWords + (size_t)kWaves * kMmaRows * kMaxBatch) * 4; }
+constexpr int kRbChunk = 3;  // row blocks whose per-wavefront sums wait in LDS for one common reduction
+static_assert((table_words(ECCO_MAX_S) + (size_t)(kGemvThreads / 64) * (32 * kStride + 4) + (size_t)kRbChunk * (kGemvThreads / 64) * 16 * 16) * 4 <= 160 * 1024, "the batched kernel's LDS fits a compute unit");
+inline size_t gemm_lds_bytes(int S) { return (table_words(S) + (size_t)kWaves * kUnitWords + (size_t)kRbChunk * kWaves * kMmaRows * kMaxBatch) * 4; }
 
 // this lane's payload pieces and meta word of unit (rb, u): block (r, c) of the unit -- row 16 rb + r,
 // column group 2 u + c -- goes to slot 2 r + c.  Indices are clamped into the matrix (see load_unit).
@@ -572,7 +574,7 @@ __global__ __launch_bounds__(kGemvThreads) void gemm_kernel(const uint32_t* __re
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     uint32_t* wbuf = smem + table_words(S) + wave * kUnitWords;
-    float* part = reinterpret_cast<float*>(smem + table_words(S) + kWaves * kUnitWords);  // [wavefront][row 16][batch 16]
+    float* part = reinterpret_cast<float*>(smem + table_words(S) + kWaves * kUnitWords);  // [row block of the chunk][wavefront][batch 16][row 16]
     const int total_rb = (rows + kMmaRows - 1) / kMmaRows;
     const int rb0 = blockIdx.x * rb_per_wg, rb1 = min(total_rb, rb0 + rb_per_wg);
     const int upr = (gpr + 1) / 2;  // units per row block
@@ -595,51 +597,84 @@ __global__ __launch_bounds__(kGemvThreads) void gemm_kernel(const uint32_t* __re
 
     const int r = lane & 15, c = lane >> 5, half = (lane >> 4) & 1;  // this lane's chain: row r, column group 2 u + c, chain `half`
     const int n = lane & 15;                                          // its batch row in B and its column in the accumulator
-    for (int rb = rb0; rb < rb1; ++rb) {
-        float4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
+    uint4 bx[kHalf / 8];  // B: 64 activations of batch row n at this chain's columns
+    for (int c0 = rb0; c0 < rb1; c0 += kRbChunk) {
+        const int nrb = min(kRbChunk, rb1 - c0);
         for (int u = wave; u < upr; u += kWaves) {
-            store_unit(wbuf, pre, lane);
-            const uint32_t mw = pre.meta;
             const int cg = 2 * u + c;
-            uint4 bx[kHalf / 8];  // B: 64 activations of batch row n at this chain's columns
+            for (int k = 0; k < nrb; ++k) {
+                store_unit(wbuf, pre, lane);
+                uint32_t mw = pre.meta;
+                // the meta word is taken here, ahead of the activation loads: a wait for it placed behind them
+                // would have to wait for them as well (they sit under a condition, so their number is not known)
+                asm volatile("" : "+v"(mw));
+                if (k == 0) {
 #pragma unroll
-            for (int j = 0; j < kHalf / 8; ++j) bx[j] = make_uint4(0, 0, 0, 0);
-            if (n < batch && cg < gpr) {
-                const uint4* src = reinterpret_cast<const uint4*>(x + (size_t)n * cols + (size_t)cg * kGroup + half * kHalf);
+                    for (int j = 0; j < kHalf / 8; ++j) bx[j] = make_uint4(0, 0, 0, 0);
+                    if (n < batch && cg < gpr) {
+                        const uint4* src = reinterpret_cast<const uint4*>(x + (size_t)n * cols + (size_t)cg * kGroup + half * kHalf);
 #pragma unroll
-                for (int j = 0; j < kHalf / 8; ++j) bx[j] = src[j];
-            }
-            // the next unit's payload is requested after the activations (loads return in issue order)
-            int un = u + kWaves, rbn = rb;
-            if (un >= upr) {
-                un = wave;
-                ++rbn;
-            }
-            if (rbn < rb1) pre = load_unit16(blocks, meta, rows, gpr, rbn, un, lane);
-            const Lane L = lane_setup(T, mw, S);
-            const _Float16 sh = __builtin_bit_cast(_Float16, (unsigned short)(mw & 0xFFFFu));
-            const half2_t s2 = {sh, sh};
-            uint32_t pk[4] = {0, 0, 0, 0};
-            decode_chain<kLong, kHalf>(wbuf + (2 * r + c) * kStride, half ? L.second_start : 0u, L, [&](int i, uint32_t e) {
-                if ((i & 1) == 0) {
-                    pk[(i >> 1) & 3] = e >> 16;
-                    return;
+                        for (int j = 0; j < kHalf / 8; ++j) bx[j] = src[j];
+                    }
                 }
-                pk[(i >> 1) & 3] = __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2_t, pk[(i >> 1) & 3] | (e & 0xFFFF0000u)) * s2);
-                if ((i & 7) != 7) return;
-                const uint4 av = make_uint4(pk[0], pk[1], pk[2], pk[3]);
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, av), __builtin_bit_cast(half8_t, bx[i >> 3]), acc, 0, 0, 0);
-            });
+                // the next unit's payload is requested after the activations (loads return in issue order):
+                // the next row block of the chunk at the same columns, else the wavefront's next columns,
+                // else the first unit of the next chunk
+                int un = u, rbn = c0 + k + 1;
+                if (k + 1 == nrb) {
+                    un = u + kWaves;
+                    rbn = c0;
+                    if (un >= upr) {
+                        un = wave;
+                        rbn = c0 + kRbChunk;
+                    }
+                }
+                if (rbn >= rb1) {  // nothing follows: the unit in hand is requested again (from cache) and dropped, so that
+                    rbn = c0 + k;  // the same loads are in flight on every path and the waits for the activations
+                    un = u;        // below can leave them outstanding
+                }
+                pre = load_unit16(blocks, meta, rows, gpr, rbn, un, lane);
+                const Lane L = lane_setup(T, mw, S);
+                const _Float16 sh = __builtin_bit_cast(_Float16, (unsigned short)(mw & 0xFFFFu));
+                const half2_t s2 = {sh, sh};
+                uint32_t pk[4] = {0, 0, 0, 0};
+                float4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
+                decode_chain<kLong, kHalf>(wbuf + (2 * r + c) * kStride, half ? L.second_start : 0u, L, [&](int i, uint32_t e) {
+                    if ((i & 1) == 0) {
+                        pk[(i >> 1) & 3] = e >> 16;
+                        return;
+                    }
+                    pk[(i >> 1) & 3] = __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2_t, pk[(i >> 1) & 3] | (e & 0xFFFF0000u)) * s2);
+                    if ((i & 7) != 7) return;
+                    const uint4 av = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, av), __builtin_bit_cast(half8_t, bx[i >> 3]), acc, 0, 0, 0);
+                });
+                // accumulator layout of the 16 x 16 tile: register j of lane l is row 4 * (l / 16) + j, column l % 16.
+                // The wavefront's sums of a row block live in its own slice of LDS: the first unit stores, later ones add.
+                float4_t* slot = reinterpret_cast<float4_t*>(part + (k * kWaves + wave) * (kMmaRows * kMaxBatch) + n * kMmaRows + 4 * (lane >> 4));
+                if (u != wave) acc += *slot;
+                *slot = acc;
+            }
         }
-        // accumulator layout of the 16 x 16 tile: register j of lane l is row 4 * (l / 16) + j, column l % 16
-#pragma unroll
-        for (int j = 0; j < 4; ++j) part[wave * (kMmaRows * kMaxBatch) + n * kMmaRows + 4 * (lane >> 4) + j] = acc[j];
+        if (wave >= upr) {  // a wavefront without units contributes zeros
+            const float4_t zero = {0.0f, 0.0f, 0.0f, 0.0f};
+            for (int k = 0; k < nrb; ++k) reinterpret_cast<float4_t*>(part + (k * kWaves + wave) * (kMmaRows * kMaxBatch))[lane] = zero;
+        }
         __syncthreads();
         if (tid < kMmaRows * kMaxBatch) {
-            float sum = 0.0f;
-            for (int w = 0; w < kWaves; ++w) sum += part[w * (kMmaRows * kMaxBatch) + tid];
-            const int b = tid >> 4, row = rb * kMmaRows + (tid & 15);
-            if (b < batch && row < rows) y[(size_t)b * rows + row] = sum;
+            // the thread index is taken afresh: addresses derived from it are then formed here and not kept in
+            // registers across the decode loop above, which has none to spare
+            int t = tid;
+            asm volatile("" : "+v"(t));
+            const int b = t >> 4;
+            for (int k = 0; k < nrb; ++k) {
+                // a fixed number of reads, all in flight at once (a loop with a run-time bound waits for one after the other)
+                float sum = 0.0f;
+#pragma unroll
+                for (int w = 0; w < kWaves; ++w) sum += part[(k * kWaves + w) * (kMmaRows * kMaxBatch) + t];
+                const int row = (c0 + k) * kMmaRows + (t & 15);
+                if (b < batch && row < rows) y[(size_t)b * rows + row] = sum;
+            }
         }
         __syncthreads();
     }
