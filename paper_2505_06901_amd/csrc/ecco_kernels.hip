@@ -239,8 +239,9 @@ constexpr int kGemvThreads = 1024;
 // buffer, adds the 64 lane sums with a wavefront reduction and goes on, without any further
 // workgroup barrier, so a wavefront starts decoding as soon as its own bytes have arrived and the
 // loads of one unit overlap the decode of the one before.  Units of a wavefront stay in one column
-// tile as long as possible, and the lane keeps the 64 activations of its chain in registers across
-// those units, so a value costs one mixed-precision FMA.  Rows are never split over workgroups:
+// tile as long as possible (a contiguous run of units when the row has several column tiles), and the
+// lane keeps the 64 activations of its chain in registers across those units, so a value costs one
+// mixed-precision FMA.  Rows are never split over workgroups:
 // partial sums of a row's column tiles meet in LDS and are added in a fixed order.
 constexpr int kUnitBlocks = 32;
 constexpr int kWaves = kGemvThreads / 64;
@@ -341,7 +342,14 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_kernel(const uint32_t* __re
     const uint4 xp0 = x4[min(tid, gpr * 16 - 1)];
     const uint4 xp1 = x4[min(tid + kGemvThreads, gpr * 16 - 1)];
     __builtin_amdgcn_sched_barrier(0);
-    int u = wave;
+    // With several column tiles a wavefront takes a contiguous run of units (column tile by column tile, row by
+    // row; runs differ by one unit at most), so it changes its column tile -- and fetches 64 activations per
+    // lane -- as rarely as possible.  With one column tile there is nothing to keep, and the wavefronts stride
+    // through the rows together, so that the workgroup reads one contiguous stretch of memory at a time.
+    const bool runs = col_tiles > 1;
+    const int u_step = runs ? 1 : kWaves;
+    int u = runs ? wave * units / kWaves : wave;
+    const int u_end = runs ? (wave + 1) * units / kWaves : units;
     const int u_first = min(u, units - 1);  // a wavefront without work loads the band's last unit and drops it
     UnitLoad pre = load_unit(blocks, meta, row0 + u_first % band_rows, gpr, u_first / band_rows, lane);
     __builtin_amdgcn_sched_barrier(0);
@@ -364,7 +372,7 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_kernel(const uint32_t* __re
     const int blk = lane & (kUnitBlocks - 1), half = lane >> 5;
     uint32_t xs[kHalf / 2];
     int cur_ct = -1;
-    for (; u < units; u += kWaves) {
+    for (; u < u_end; u += u_step) {
         const int ct = u / band_rows, r = u - ct * band_rows;
         store_unit(wbuf, pre, lane);
         const uint32_t mw = pre.meta;
@@ -390,8 +398,8 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_kernel(const uint32_t* __re
         }
         // the next unit's payload is requested after the activations: loads return in issue order, and the
         // activations (from cache) must not queue behind a fetch from HBM
-        const int un = u + kWaves;
-        if (un < units) pre = load_unit(blocks, meta, row0 + un % band_rows, gpr, un / band_rows, lane);
+        const int un = u + u_step;
+        if (un < u_end) pre = load_unit(blocks, meta, row0 + un % band_rows, gpr, un / band_rows, lane);
         const Lane L = lane_setup(T, mw, S);
         float acc = 0.0f;
         decode_chain<kLong, kHalf>(wbuf + blk * kStride, half ? L.second_start : 0u, L, [&](int i, uint32_t e) {
