@@ -225,3 +225,29 @@ def test_paper_block_fit_invariants():
     blocks = P.encode(om, w.view(np.uint16))
     dec, n_coded, n_out = P.decode(om, blocks)
     assert n_coded.mean() > 120 and (n_out > 0).mean() > 0.05
+
+
+def test_build_rejects_register_spills(monkeypatch):
+    """The build reads the compiler's resource remarks: scratch memory or spilled registers in any kernel stop it
+    (scalar spills are tolerated in the one kernel that is known to have them)."""
+    from paper_2505_06901_amd import build as B
+
+    monkeypatch.delenv("ECCO_ALLOW_SCRATCH", raising=False)
+
+    def remarks(name, scratch=0, sgpr=0, vgpr=0):
+        pre = "x.hip:1:1: remark: "
+        return "\n".join([pre + "Function Name: %s [-Rpass-analysis=kernel-resource-usage]" % name,
+                          pre + "    TotalSGPRs: 60 [-Rpass-analysis=kernel-resource-usage]",
+                          pre + "    ScratchSize [bytes/lane]: %d [-Rpass-analysis=kernel-resource-usage]" % scratch,
+                          pre + "    SGPRs Spill: %d [-Rpass-analysis=kernel-resource-usage]" % sgpr,
+                          pre + "    VGPRs Spill: %d [-Rpass-analysis=kernel-resource-usage]" % vgpr])
+
+    B._check_kernel_resources(remarks("_Z11gemm_kernelILb0EEvv"), False)
+    for bad in (dict(scratch=52), dict(sgpr=8), dict(vgpr=3)):
+        with pytest.raises(RuntimeError, match="spills"):
+            B._check_kernel_resources(remarks("_Z11gemm_kernelILb1EEvv", **bad), False)
+    B._check_kernel_resources(remarks("_ZN12_GLOBAL__N_120kv_attend_gqa_kernelILb1ELb1EEEvv", sgpr=4), False)
+    with pytest.raises(RuntimeError, match="spills"):
+        B._check_kernel_resources(remarks("_ZN12_GLOBAL__N_120kv_attend_gqa_kernelILb1ELb1EEEvv", vgpr=1), False)
+    with pytest.raises(RuntimeError, match="no kernel resource remarks"):
+        B._check_kernel_resources("nothing here", False)
