@@ -419,8 +419,15 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_kernel(const uint32_t* __re
     if (col_tiles > 1) {
         __syncthreads();
         if (tid < band_rows) {
+            // four reads in flight at a time (indices clamped, the surplus not added): same order of additions
             float sum = 0.0f;
-            for (int ct = 0; ct < col_tiles; ++ct) sum += part[tid * col_tiles + ct];
+            for (int ct0 = 0; ct0 < col_tiles; ct0 += 4) {
+                float v[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) v[j] = part[tid * col_tiles + min(ct0 + j, col_tiles - 1)];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) sum += ct0 + j < col_tiles ? v[j] : 0.0f;
+            }
             y[row0 + tid] = sum;
         }
     }
