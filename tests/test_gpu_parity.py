@@ -667,6 +667,28 @@ def test_repeated_launches_are_identical(dev, oracle):
             assert torch.equal(first, again), batch
 
 
+@pytest.mark.parametrize("rows,cols", [(37, 8192), (8200, 1024), (48, 4096)])
+def test_batched_gemv_repeatable_with_long_codes(dev, oracle, rows, cols):
+    """The batched kernel's long-code variant on shapes with several units per wavefront (37 x 8192), with three row
+    blocks per workgroup and a ragged last one (8200 x 1024), and with one unit per wavefront: right against the
+    batch-1 kernel's rows, and the same bits on every launch."""
+    S = 7
+    cent, lens, probs = _skewed_model(oracle, S, 1)
+    assert lens.max() == 12
+    m = E.ecco_model_to_device(E.ecco_model_create(cent, lens), 0)
+    n = rows * cols // 128
+    x = _skewed_data(cent, probs, 4096, 5)
+    x = np.tile(x, (-(-n // 4096), 1))[:n]
+    blocks, meta = E.ecco_encode(m, t16(x, dev))
+    for batch in (4, 16):
+        xb = t16(W.activation(batch, cols, 40 + batch), dev)
+        ref = torch.stack([E.ecco_decode_gemv(m, blocks, meta, rows, cols, xb[b:b + 1].contiguous())[0] for b in range(batch)])
+        first = E.ecco_decode_gemv(m, blocks, meta, rows, cols, xb)
+        assert float((first - ref).norm() / ref.norm()) <= REL_L2, batch
+        for _ in range(10):
+            assert torch.equal(first, E.ecco_decode_gemv(m, blocks, meta, rows, cols, xb)), batch
+
+
 def test_graph_replay_matches_eager(dev, oracle, tiny):
     """Every entry point of the two-chain format recorded into one HIP graph and replayed three times on inputs that
     change between the replays (with eager work and synchronisation in between): every replay must give the bits the
