@@ -176,6 +176,33 @@ def test_long_codes_in_attention(dev, oracle):
         assert rel_l2(out, want) <= REL_L2
 
 
+def test_long_code_attention_repeatable(dev, oracle):
+    """Both attention kernels with long codes in K and in V, over many units per wavefront: right against the oracle
+    and the same bits on every launch."""
+    B, H, T = 2, 2, 1500
+    cent, lens, probs = _skewed_model(oracle, 5, 3)
+    m = E.ecco_model_to_device(E.ecco_model_create(cent, lens), 0)
+    kl = _skewed_data(cent, probs, B * H * T, 6).reshape(B, H, T, 128)
+    vl = _skewed_data(cent, probs, B * H * T, 7).reshape(B, H, T, 128)
+    q = W.activation(B * H * 2, 128, 109).reshape(B, 2 * H, 128)
+    seq = np.array([T, 1111], np.int32)
+    kb, km = E.ecco_encode(m, t16(kl, dev)); vb, vm = E.ecco_encode(m, t16(vl, dev))
+    args = (np_blocks(kb), np_meta(km), np_blocks(vb), np_meta(vm), seq)
+    want = oracle.kv_attend(m.centroids, m.code_lens, m.centroids, m.code_lens, np.ascontiguousarray(q[:, :H]).view(np.uint16), *args, B, H, T)
+    qd, sd = t16(q[:, :H], dev), ti32(seq, dev)
+    first = E.ecco_kv_attend(m, m, qd, kb, km, vb, vm, sd, B, H, T)
+    assert rel_l2(first.cpu().numpy(), want) <= REL_L2
+    for _ in range(15):
+        assert torch.equal(first, E.ecco_kv_attend(m, m, qd, kb, km, vb, vm, sd, B, H, T))
+    want = oracle.kv_attend_gqa(m.centroids, m.code_lens, m.centroids, m.code_lens, q.view(np.uint16), *args, B, 2 * H, H, T)
+    qd = t16(q, dev)
+    for n_splits in (1, 3):
+        first = E.ecco_kv_attend_gqa(m, m, qd, kb, km, vb, vm, sd, B, 2 * H, H, T, n_splits=n_splits)
+        assert rel_l2(first.cpu().numpy(), want) <= REL_L2, n_splits
+        for _ in range(15):
+            assert torch.equal(first, E.ecco_kv_attend_gqa(m, m, qd, kb, km, vb, vm, sd, B, 2 * H, H, T, n_splits=n_splits)), n_splits
+
+
 def test_corrupt_blocks_decode_like_oracle(dev, oracle):
     S = 5
     cent, lens, _ = _skewed_model(oracle, S, 3)
