@@ -694,11 +694,12 @@ def test_repeated_launches_are_identical(dev, oracle):
             assert torch.equal(first, again), batch
 
 
-@pytest.mark.parametrize("rows,cols", [(37, 8192), (8200, 1024), (48, 4096)])
+@pytest.mark.parametrize("rows,cols", [(37, 8192), (8200, 1024), (48, 4096), (16400, 256)])
 def test_batched_gemv_repeatable_with_long_codes(dev, oracle, rows, cols):
     """The batched kernel's long-code variant on shapes with several units per wavefront (37 x 8192), with three row
     blocks per workgroup and a ragged last one (8200 x 1024), and with one unit per wavefront: right against the
-    batch-1 kernel's rows, and the same bits on every launch."""
+    batch-1 kernel's rows, and the same bits on every launch.  16400 x 256: five row blocks per workgroup (two rounds
+    of the workgroup's reduction) and one unit per row block, so fifteen of the sixteen wavefronts have none."""
     S = 7
     cent, lens, probs = _skewed_model(oracle, S, 1)
     assert lens.max() == 12
