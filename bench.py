@@ -38,7 +38,7 @@ BYTES_PER_GROUP = 68   # 64-byte payload + 4-byte meta word
 MEASURED_TRAFFIC_BYTES = {"proj7b": int((4465.2 * 1.994 + 16.0) * 1024)}
 
 
-def cpu_baseline(m, blocks_np, meta_np, rows, cols, x_np, budget_s=12.0):
+def cpu_baseline(m, blocks_np, meta_np, rows, cols, x_np, w_np=None, budget_s=12.0):
     """The oracle's decode + GEMV (double accumulation) on the same matrix, repeated for about budget_s seconds."""
     from oracle import oracle as O
     threads = O.set_threads(os.cpu_count() or 1)
@@ -67,6 +67,27 @@ def cpu_baseline(m, blocks_np, meta_np, rows, cols, x_np, budget_s=12.0):
         t1 += run(rows1)
         n1 += 1
     O.set_threads(threads)
+    # the oracle's standalone decoder and encoder on all threads, about three seconds each, on the first groups
+    # of the same matrix (rates on the same byte accounting as the GPU rows)
+    extra = {}
+
+    def timed(fn, n0, total, budget=3.0):
+        n = min(total, n0)
+        t0 = time.perf_counter()
+        fn(n)
+        t = time.perf_counter() - t0
+        n = int(min(total, max(n, n * budget / max(t, 1e-6))))
+        t0 = time.perf_counter()
+        fn(n)
+        return n, time.perf_counter() - t0
+
+    total_groups = rows * gpr
+    n, t = timed(lambda n: O.decode(cent, lens, blocks_np[:n], meta_np[:n]), 64 * threads, total_groups)
+    extra["decode"] = {"groups": n, "seconds": t, "GBps_total_traffic": n * (BYTES_PER_GROUP + 256) / t / 1e9}
+    if w_np is not None:
+        wg = w_np.reshape(-1, 128).view(np.uint16)
+        n, t = timed(lambda n: O.encode(cent, lens, wg[:n]), 16 * threads, total_groups)
+        extra["encode"] = {"groups": n, "seconds": t, "groups_per_s": n / t}
     cpu = "unknown"
     try:
         with open("/proc/cpuinfo") as f:
@@ -80,7 +101,8 @@ def cpu_baseline(m, blocks_np, meta_np, rows, cols, x_np, budget_s=12.0):
             "sample": f"oracle_gemv batch 1 on the first {nrows} of {rows} rows of the same matrix ({groups} groups), "
                       f"{passes} passes, {spent:.1f} s in all",
             "gemv_per_s_equiv": 1.0 / (per_pass * rows / nrows),
-            "single_thread_GBps": rows1 * gpr * BYTES_PER_GROUP / (t1 / n1) / 1e9, "cpu": cpu, "host_cpus": os.cpu_count()}
+            "single_thread_GBps": rows1 * gpr * BYTES_PER_GROUP / (t1 / n1) / 1e9, "cpu": cpu, "host_cpus": os.cpu_count(),
+            "other_oracle_legs": extra}
 
 
 def main():
@@ -538,7 +560,7 @@ def main():
         out["selector_quality"] = selector_quality
     if not args.no_cpu_baseline and want("gemv1"):
         out["cpu_baseline"] = cpu_baseline(m, blocks0.cpu().numpy(), meta0.cpu().numpy().view(np.uint32), rows, cols,
-                                           xs[1].cpu().numpy())
+                                           xs[1].cpu().numpy(), w_np=w)
     print(json.dumps(out))
 
 
