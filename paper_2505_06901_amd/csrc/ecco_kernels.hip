@@ -1015,7 +1015,7 @@ constexpr int kAttnWaves = kAttnThreads / 64;
 constexpr int kSpan = 8192;
 static_assert(2 * 512 >= ECCO_MAX_S * kK, "stage_tables_around: two table items per thread cover every model (the smallest attention workgroup has 512 threads)");
 inline size_t attn_lds_bytes(int Sk, int Sv) {
-    return (table_words(std::max(Sk, Sv)) + (size_t)kAttnWaves * kUnitWords + kSpan + kAttnWaves * kGroup + 64) * 4;
+    return (table_words(std::max(Sk, Sv)) + (size_t)kAttnWaves * kUnitWords + kSpan + kAttnWaves * 2 * kGroup + 64) * 4;
 }
 
 __device__ inline float wg_reduce(float v, float* scratch, bool is_max, int waves) {
@@ -1046,8 +1046,8 @@ __global__ __launch_bounds__(kLongV ? 512 : kAttnThreads) void kv_attend_kernel(
     const int waves = kLongV ? 8 : kAttnWaves, threads = waves * 64;
     uint32_t* wbuf = smem + table_words(Smax) + wave * kUnitWords;
     float* scores = reinterpret_cast<float*>(smem + table_words(Smax) + kAttnWaves * kUnitWords);
-    float* wred = scores + kSpan;               // [wavefront][128] at the end
-    float* scratch = wred + kAttnWaves * kGroup;
+    float* wred = scores + kSpan;               // [wavefront][row of 16 lanes][64] at the end
+    float* scratch = wred + kAttnWaves * 2 * kGroup;
     if (lane < kUnitBlocks) wbuf[lane * kStride + kBlockWords] = 0u;
     if (lane == 0) wbuf[kUnitBlocks * kStride] = 0u;
 
@@ -1150,24 +1150,27 @@ __global__ __launch_bounds__(kLongV ? 512 : kAttnThreads) void kv_attend_kernel(
             }
             // the span's sums: over the lanes of a wavefront on the VALU (lanes 0..31 hold values 0..63, lanes
             // 32..63 values 64..127), then over the wavefronts through LDS into the running output
+            int ln = lane;  // taken afresh: what is derived from it is then formed here, not kept across the loop above
+            asm volatile("" : "+v"(ln));
+            const bool row_first = (ln & 15) == 0;
+            float* wrow = wred + (wave * 4 + (ln >> 4)) * kHalf;
 #pragma unroll
             for (int i = 0; i < kHalf; ++i) {
                 float t = o[i];
                 t += dpp_mov<0xB1>(t);   // quad_perm [1,0,3,2]
                 t += dpp_mov<0x4E>(t);   // quad_perm [2,3,0,1]
                 t += dpp_mov<0x141>(t);  // row_half_mirror
-                t += dpp_mov<0x140>(t);  // row_mirror
-                const float lo = read_lane(t, 0) + read_lane(t, 16), hi = read_lane(t, 32) + read_lane(t, 48);
-                if (lane == 0) {
-                    wred[wave * kGroup + i] = lo;
-                    wred[wave * kGroup + kHalf + i] = hi;
-                }
+                t += dpp_mov<0x140>(t);  // row_mirror: every lane of a row of 16 now holds the row's sum
+                // the first lane of each row stores it: rows 0 and 1 belong to values 0..63, rows 2 and 3 to 64..127
+                if (row_first) wrow[i] = t;
             }
         }
         __syncthreads();
         if (tid < kGroup) {
             float v = 0.0f;
-            for (int w = 0; w < waves; ++w) v += wred[w * kGroup + tid];
+            const int hrow = (tid >> 6) * 2, i = tid & (kHalf - 1);
+#pragma unroll 4
+            for (int w = 0; w < waves; ++w) v += wred[(w * 4 + hrow) * kHalf + i] + wred[(w * 4 + hrow + 1) * kHalf + i];
             my_out = my_out * rescale + v;
         }
     }
