@@ -122,6 +122,7 @@ def main():
     ap.add_argument("--gqa-splits", type=int, default=0, help="token splits of the kv_attend_gqa row (0: enough to give every compute unit a workgroup)")
     ap.add_argument("--selector-quality", action="store_true",
                     help="add the reconstruction error of the min/max pattern selector against the least-squared-error search on the K and V caches")
+    ap.add_argument("--kv-patterns", type=int, default=0, help="shared patterns of the K and V models (default: the KV workload's 64; the paper's online compressor uses 16)")
     ap.add_argument("--workload", default="proj7b", choices=["proj7b", "mlp_up", "mlp_down", "proj70b"])
     ap.add_argument("--sweep", action="store_true", help="add an ecco_decode sweep over block counts 2^14..2^22 (as far as the workload has blocks)")
     args = ap.parse_args()
@@ -171,8 +172,9 @@ def main():
     if kv_needed:
         k, v = W.kv_cache(B, H, T, 128, kc["seeds"][0])
         cal = kc["calib_tokens"]
-        mk = E.ecco_model_to_device(E.ecco_fit_patterns(k[:, :, :cal], kc["S"], 12, kc["seeds"][0]), 0)
-        mv = E.ecco_model_to_device(E.ecco_fit_patterns(v[:, :, :cal], kc["S"], 12, kc["seeds"][0] + 1), 0)
+        kv_S = args.kv_patterns or kc["S"]
+        mk = E.ecco_model_to_device(E.ecco_fit_patterns(k[:, :, :cal], kv_S, 12, kc["seeds"][0]), 0)
+        mv = E.ecco_model_to_device(E.ecco_fit_patterns(v[:, :, :cal], kv_S, 12, kc["seeds"][0] + 1), 0)
         k_dev = torch.from_numpy(k).to(dev)
         kb0, km0 = E.ecco_encode(mk, k_dev)
         vb0, vm0 = E.ecco_encode(mv, torch.from_numpy(v).to(dev))
@@ -556,6 +558,8 @@ def main():
         # as the runtime reports them (kHz, bits).  The data-sheet 8 TB/s the roofline uses is four transfers per
         # reported clock on this bus (2 GHz x 8192 bit x 4 / 8)
         out["device"].update({"memory_clock_kHz": clk, "memory_bus_bits": width, "GBps_at_4_transfers_per_clock": 4.0 * clk * 1e3 * width / 8 / 1e9})
+    if kv_needed:
+        out["config"]["kv_patterns"] = kv_S
     if kv_needed and selector_quality is not None:
         out["selector_quality"] = selector_quality
     if not args.no_cpu_baseline and want("gemv1"):
