@@ -1423,17 +1423,41 @@ __global__ __launch_bounds__(kGroup) void kv_attend_combine_kernel(const float* 
     const size_t bh = blockIdx.x;
     const float* ml = ws + (size_t)n_heads * n_splits * kGroup + bh * n_splits * 2;
     const float* part = ws + bh * n_splits * kGroup + threadIdx.x;
+    // the largest of the splits' maxima: a few splits per lane and a wavefront maximum (exact whatever the order),
+    // instead of a chain of n_splits dependent loads
     float mx = -INFINITY;
-    for (int s = 0; s < n_splits; ++s) mx = fmaxf(mx, ml[2 * s]);
-    // no branch in the loop, so that the loads of all splits are in flight together; an empty split
-    // (maximum -inf, zeros) gets weight 0, also when every split is empty (mx = -inf)
+    for (int s = threadIdx.x & 63; s < n_splits; s += 64) mx = fmaxf(mx, ml[2 * s]);
+    mx = wave_all(mx, [](float a, float b) { return fmaxf(a, b); });
+    // Sixteen splits at a time with all their loads in flight together (indices clamped, the surplus given weight 0
+    // by a select, no branch); the additions run in split order.  An empty split (maximum -inf, zeros) gets weight
+    // 0, also when every split is empty (mx = -inf).
     float num = 0.0f, den = 0.0f;
+    if (n_splits <= 8) {  // few splits: four at a time cost fewer surplus loads
 #pragma unroll 4
-    for (int s = 0; s < n_splits; ++s) {
-        const float m = ml[2 * s], d = ml[2 * s + 1], v = part[(size_t)s * kGroup];
-        const float w = m == -INFINITY ? 0.0f : __expf(m - mx);
-        num += w * v;
-        den += w * d;
+        for (int s = 0; s < n_splits; ++s) {
+            const float m = ml[2 * s], d = ml[2 * s + 1], v = part[(size_t)s * kGroup];
+            const float w = m == -INFINITY ? 0.0f : __expf(m - mx);
+            num += w * v;
+            den += w * d;
+        }
+    } else
+    for (int s0 = 0; s0 < n_splits; s0 += 16) {
+        float m[16], d[16], v[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const int sj = min(s0 + j, n_splits - 1);
+            m[j] = ml[2 * sj];
+            d[j] = ml[2 * sj + 1];
+            v[j] = part[(size_t)sj * kGroup];
+        }
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            if (s0 + j < n_splits) {  // uniform
+                const float w = m[j] == -INFINITY ? 0.0f : __expf(m[j] - mx);
+                num += w * v[j];
+                den += w * d[j];
+            }
+        }
     }
     out[bh * kGroup + threadIdx.x] = den > 0.0f ? num / den : 0.0f;
 }
