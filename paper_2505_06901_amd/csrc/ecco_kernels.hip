@@ -1318,15 +1318,32 @@ __global__ __launch_bounds__(kGqaThreads) void kv_attend_gqa_kernel(const uint32
         // ---- running softmax, one wavefront per query head
         for (int g = wave; g < grp; g += kGqaWaves) {
             const int n = units * kUnitBlocks;
+            // both passes take four scores per lane at a time, so that their LDS reads are in flight together (a loop
+            // over single reads waits for each); indices past the end are clamped for the read (a repeated score does
+            // not change a maximum) and left out of the second pass; the additions keep their order
             float mx = -INFINITY;
-            for (int t = lane; t < n; t += 64) mx = fmaxf(mx, scores[g * sstride + t]);
+            for (int t0 = lane; t0 < n; t0 += 4 * 64) {
+                float a[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) a[j] = scores[g * sstride + min(t0 + 64 * j, n - 1)];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) mx = fmaxf(mx, a[j]);
+            }
             mx = wave_all(mx, [](float a, float c) { return fmaxf(a, c); });
             const float old_max = st_max[g], new_max = fmaxf(old_max, mx);
             float den = 0.0f;
-            for (int t = lane; t < n; t += 64) {
-                const _Float16 ph = (_Float16)__expf(scores[g * sstride + t] - new_max);  // 0 for the tokens past the span
-                probs[g * pstride + t] = ph;
-                den += (float)ph;
+            for (int t0 = lane; t0 < n; t0 += 4 * 64) {
+                float a[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) a[j] = scores[g * sstride + min(t0 + 64 * j, n - 1)];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    if (t0 + 64 * j < n) {
+                        const _Float16 ph = (_Float16)__expf(a[j] - new_max);  // 0 for the tokens past the span
+                        probs[g * pstride + t0 + 64 * j] = ph;
+                        den += (float)ph;
+                    }
+                }
             }
             den = wave_sum(den);
             if (lane == 0) {
