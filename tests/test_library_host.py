@@ -251,3 +251,13 @@ def test_build_rejects_register_spills(monkeypatch):
         B._check_kernel_resources(remarks("_ZN12_GLOBAL__N_120kv_attend_gqa_kernelILb1ELb1EEEvv", vgpr=1), False)
     with pytest.raises(RuntimeError, match="no kernel resource remarks"):
         B._check_kernel_resources("nothing here", False)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py is a one-GPU program: any other --gpus value ends with a message before anything touches a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    p = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert p.returncode != 0
+    assert "one GPU" in (p.stderr + p.stdout)
