@@ -170,6 +170,10 @@ __device__ __forceinline__ Lane lane_setup(const Tables& T, uint32_t meta, int S
     return L;
 }
 
+typedef __attribute__((address_space(3))) uint32_t lds_u32;  // a 32-bit word in LDS, addressed as such
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(1))) u32x4 global_u4;   // sixteen bytes in global memory
+
 // ---- the chain decoder ----------------------------------------------------------------------------------
 // Decodes kCount values starting at stream bit `start` of the staged block `w` (16 words, a zero
 // word, then two more readable words), calling sink(i, entry) with the table entry of each (length,
@@ -201,8 +205,12 @@ __device__ __forceinline__ void decode_chain(const uint32_t* w, uint32_t start, 
                 if ((e & 0xFFu) == 0u) {
                     // code longer than the peek: rank of the next 12 bits among the left-aligned canonical codes
                     const uint32_t v = (uint32_t)(win >> 32) >> (32 - kMaxLen);
-                    const uint32_t* lt = L.longtab;
-                    asm volatile("" : "+v"(lt));  // the list is read here, on the rare path, not held in 16 registers throughout
+                    // the list is read here, on the rare path, not held in 16 registers throughout: its LDS byte address
+                    // passes through an empty asm statement (a pointer passed through one would come back without its
+                    // address space, and the reads below would become flat loads instead of LDS reads)
+                    uint32_t lt_at = (uint32_t)(size_t)(const lds_u32*)L.longtab;
+                    asm volatile("" : "+v"(lt_at));
+                    const lds_u32* lt = (const lds_u32*)(size_t)lt_at;
                     int rank = 0;
                     for (int q = 1; q < kK; ++q) rank += ((lt[q] & 0xFFFu) <= v) ? 1 : 0;
                     const uint32_t t = lt[rank];
@@ -1069,11 +1077,14 @@ __global__ __launch_bounds__(kLongV ? 512 : kAttnThreads) void kv_attend_kernel(
         float my_max = -INFINITY;
         {
             uint32_t qx[kHalf / 2];  // the query elements of this lane's chain, FP16 pairs
-            const uint4* qsrc = reinterpret_cast<const uint4*>(q + (size_t)bh * kGroup + half * kHalf);
-            asm volatile("" : "+v"(qsrc));  // reloaded per span (from cache) rather than kept alive across the V phase
+            // reloaded per span (from cache) rather than kept alive across the V phase; the pointer that comes back from
+            // the empty asm statement is given its address space again, or its loads would be flat loads
+            const uint4* qgen = reinterpret_cast<const uint4*>(q + (size_t)bh * kGroup + half * kHalf);
+            asm volatile("" : "+v"(qgen));
+            const global_u4* qsrc = (const global_u4*)qgen;
 #pragma unroll
             for (int j = 0; j < kHalf / 8; ++j) {
-                const uint4 v = qsrc[j];
+                const u32x4 v = qsrc[j];
                 qx[4 * j] = v.x; qx[4 * j + 1] = v.y; qx[4 * j + 2] = v.z; qx[4 * j + 3] = v.w;
             }
             for (; u < units; u += waves) {
@@ -1279,10 +1290,15 @@ __global__ __launch_bounds__(kGqaThreads) void kv_attend_gqa_kernel(const uint32
         __syncthreads();
         {
             uint4 bq[kHalf / 8];  // B operands: the query of head blk, dimensions 64 * half + 8j .. + 7
-            const uint4* qsrc = reinterpret_cast<const uint4*>(q + q_row + half * kHalf);
-            asm volatile("" : "+v"(qsrc));  // reloaded per span rather than kept alive across the V phase
+            // reloaded per span rather than kept alive across the V phase (address space restored as above)
+            const uint4* qgen = reinterpret_cast<const uint4*>(q + q_row + half * kHalf);
+            asm volatile("" : "+v"(qgen));
+            const global_u4* qsrc = (const global_u4*)qgen;
 #pragma unroll
-            for (int j = 0; j < kHalf / 8; ++j) bq[j] = head_ok ? qsrc[j] : make_uint4(0u, 0u, 0u, 0u);
+            for (int j = 0; j < kHalf / 8; ++j) {
+                const u32x4 v = qsrc[j];
+                bq[j] = head_ok ? make_uint4(v.x, v.y, v.z, v.w) : make_uint4(0u, 0u, 0u, 0u);
+            }
             for (; u < units; u += kGqaWaves) {
                 store_unit(wbuf, pre, lane);
                 const uint32_t mw = pre.meta;
