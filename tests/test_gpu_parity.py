@@ -717,6 +717,35 @@ def test_batched_gemv_repeatable_with_long_codes(dev, oracle, rows, cols):
             assert torch.equal(first, E.ecco_decode_gemv(m, blocks, meta, rows, cols, xb)), batch
 
 
+def test_batched_gemv_random_shapes(dev, oracle):
+    """Thirty seeded shapes (1 to 20 000 rows, 1 to 86 column groups, batch 2 to 16) under three models (long codes,
+    16 and 64 fitted patterns): the batched kernel against the batch-1 kernel row by row, and three launches bit for bit.
+    (The batch-1 kernel is checked against the oracle elsewhere; this test is about the batched kernel's indexing.)"""
+    rng = np.random.default_rng(0)
+    cent, lens, probs = _skewed_model(oracle, 7, 1)
+    models = [(E.ecco_model_to_device(E.ecco_model_create(cent, lens), 0), (cent, probs))]
+    w = W.weight_matrix(512, 4096, 0.02, 1e-3, 10.0, 77)
+    models += [(E.ecco_model_to_device(E.ecco_fit_patterns(w, S, 12, 5), 0), None) for S in (16, 64)]
+    for case in range(30):
+        m, skew = models[case % 3]
+        rows = int(rng.choice([1, 3, 15, 16, 17, 47, 300, 1000, 4097, 8200, 12290, 20000]))
+        gpr = int(rng.choice([1, 2, 3, 7, 8, 31, 32, 33, 64, 86]))
+        if rows * gpr > 400000:
+            gpr = max(1, 400000 // rows)
+        cols, n = gpr * 128, rows * gpr
+        base = _skewed_data(skew[0], skew[1], 2048, case) if skew else \
+            W.weight_matrix(16, 128 * 128, 0.02, 1e-3, 10.0, 1000 + case).reshape(-1, 128)
+        x = np.ascontiguousarray(np.tile(base, (-(-n // base.shape[0]), 1))[:n])
+        blocks, meta = E.ecco_encode(m, t16(x, dev))
+        batch = int(rng.integers(2, 17))
+        xb = t16(W.activation(batch, cols, 500 + case), dev)
+        ref = torch.stack([E.ecco_decode_gemv(m, blocks, meta, rows, cols, xb[b:b + 1].contiguous())[0] for b in range(batch)])
+        first = E.ecco_decode_gemv(m, blocks, meta, rows, cols, xb)
+        assert float((first - ref).norm() / ref.norm()) <= REL_L2, (case, rows, gpr, batch)
+        for _ in range(2):
+            assert torch.equal(first, E.ecco_decode_gemv(m, blocks, meta, rows, cols, xb)), (case, rows, gpr, batch)
+
+
 def test_graph_replay_matches_eager(dev, oracle, tiny):
     """Every entry point of the two-chain format recorded into one HIP graph and replayed three times on inputs that
     change between the replays (with eager work and synchronisation in between): every replay must give the bits the
