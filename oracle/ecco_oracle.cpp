@@ -763,8 +763,14 @@ void oracle_kv_attend_gqa(const uint16_t* ck, const uint8_t* lk, int Sk, const u
 
 // ------------------------------------------------------------------------------------------
 // The fit (Section 3.2).  Where the paper leaves a step open, the comment at that step says which reading is taken.
-int oracle_fit(const uint16_t* data, size_t n_values, int S, int max_len, uint64_t seed,
-               uint16_t* centroids, uint8_t* lens, uint64_t* hist_out, size_t* n_fit_groups) {
+// oracle_fit_trace is the fit itself; beside the model it hands out what the steps produced on the way, so that
+// tests can check each step on its own: the groups picked in step 1, the per-group patterns of step 3, and the
+// objective of step 4 (sum over the groups of the squared distance to the nearest shared pattern) at every
+// assignment pass.  Any of the trace pointers may be NULL.
+int oracle_fit_trace(const uint16_t* data, size_t n_values, int S, int max_len, uint64_t seed,
+                     uint16_t* centroids, uint8_t* lens, uint64_t* hist_out, size_t* n_fit_groups,
+                     uint64_t* pick_out, double* group_patterns_out, double* objective_out, int* n_objective) {
+    if (n_objective) *n_objective = 0;
     if (!data || n_values == 0 || n_values % G != 0 || S < 1 || S > ORACLE_MAX_S || max_len < 4 || max_len > ORACLE_MAX_LEN)
         return -1;
     const size_t n_all = n_values / G;
@@ -788,6 +794,7 @@ int oracle_fit(const uint16_t* data, size_t n_values, int S, int max_len, uint64
     }
     const size_t n = pick.size();
     if (n_fit_groups) *n_fit_groups = n;
+    if (pick_out) for (size_t i = 0; i < n; ++i) pick_out[i] = (uint64_t)pick[i];
 
     // steps 2-3: normalise by the group's absolute maximum, then 16-cluster k-means per group
     std::vector<double> pat(n * K);
@@ -801,6 +808,8 @@ int oracle_fit(const uint16_t* data, size_t n_values, int S, int max_len, uint64
         for (int i = 0; i < G; ++i) v[i] = (s_bits == 0) ? 0.0f : oracle_h2f(x[i]) / s;
         oracle_kmeans_1d(v, G, K, 25, &pat[(size_t)gi * K], nullptr);
     }
+
+    if (group_patterns_out) std::memcpy(group_patterns_out, pat.data(), sizeof(double) * n * K);
 
     // step 4: k-means with S clusters over the 16-vectors.  k-means++ seeding (Arthur & Vassilvitskii 2007)
     std::vector<double> cen((size_t)S * K);
@@ -846,6 +855,12 @@ int oracle_fit(const uint16_t* data, size_t n_values, int S, int max_len, uint64
             if (best != assign[(size_t)gi]) { assign[(size_t)gi] = best; ++changed; }
             own[(size_t)gi] = bd;
         }
+        if (objective_out) {  // reporting only: the fit does not use this sum
+            double total = 0.0;
+            for (size_t g = 0; g < n; ++g) total += own[g];
+            objective_out[it] = total;
+        }
+        if (n_objective) *n_objective = it + 1;
         if (changed == 0) break;
         std::vector<double> sum((size_t)S * K, 0.0);
         std::vector<size_t> cnt((size_t)S, 0);
@@ -907,6 +922,12 @@ int oracle_fit(const uint16_t* data, size_t n_values, int S, int max_len, uint64
         if (rc != 0) return rc;
     }
     return 0;
+}
+
+int oracle_fit(const uint16_t* data, size_t n_values, int S, int max_len, uint64_t seed,
+               uint16_t* centroids, uint8_t* lens, uint64_t* hist_out, size_t* n_fit_groups) {
+    return oracle_fit_trace(data, n_values, S, max_len, seed, centroids, lens, hist_out, n_fit_groups,
+                            nullptr, nullptr, nullptr, nullptr);
 }
 
 }  // extern "C"

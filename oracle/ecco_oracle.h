@@ -54,6 +54,13 @@ int oracle_kmeans_1d(const float* v, int n, int K, int max_iter, double* cent_ou
  * centroids[S*16] fp16 bits, lens[S*16], hist[S*16] (may be NULL), n_fit_groups (may be NULL) */
 int oracle_fit(const uint16_t* data, size_t n_values, int S, int max_len, uint64_t seed,
                uint16_t* centroids, uint8_t* lens, uint64_t* hist, size_t* n_fit_groups);
+/* the same fit, also handing out what its steps produced (each pointer may be NULL): pick[n_fit_groups] the indices
+ * of the groups used (step 1; ascending), group_patterns[n_fit_groups*16] the sorted per-group centroids (step 3),
+ * objective[0..*n_objective-1] the sum of squared distances to the nearest shared pattern at every assignment pass of
+ * step 4 (at most 50 entries) */
+int oracle_fit_trace(const uint16_t* data, size_t n_values, int S, int max_len, uint64_t seed,
+                     uint16_t* centroids, uint8_t* lens, uint64_t* hist, size_t* n_fit_groups,
+                     uint64_t* pick, double* group_patterns, double* objective, int* n_objective);
 
 /* ---- encoder (Section 3.2 step 5 + Section 4.3) ---------------------------------------- */
 /* one group: scale bits, chosen pattern, 128 indices, SSE of every pattern (sse may be NULL) */

@@ -107,6 +107,27 @@ def fit(data_u16, S: int, max_len: int = MAX_LEN, seed: int = 0):
     return cent, lens, hist, int(nfit.value)
 
 
+def fit_trace(data_u16, S: int, max_len: int = MAX_LEN, seed: int = 0):
+    """oracle_fit_trace: the fit plus the picked group indices, the per-group patterns and the step-4 objective."""
+    data = _c(data_u16, np.uint16).reshape(-1)
+    n_all = data.size // GROUP
+    n_cap = min(n_all, 65536)
+    cent = np.zeros((S, K), np.uint16)
+    lens = np.zeros((S, K), np.uint8)
+    hist = np.zeros((S, K), np.uint64)
+    pick = np.zeros(n_cap, np.uint64)
+    pats = np.zeros((n_cap, K), np.float64)
+    obj = np.zeros(50, np.float64)
+    nfit, nobj = C.c_size_t(0), C.c_int(0)
+    rc = lib().oracle_fit_trace(_p(data), C.c_size_t(data.size), C.c_int(S), C.c_int(max_len), C.c_uint64(seed),
+                                _p(cent), _p(lens), _p(hist), C.byref(nfit), _p(pick), _p(pats), _p(obj), C.byref(nobj))
+    if rc != 0:
+        raise ValueError(f"oracle_fit_trace rc={rc}")
+    n = int(nfit.value)
+    return dict(cent=cent, lens=lens, hist=hist, n_fit=n, pick=pick[:n].astype(np.int64), patterns=pats[:n],
+                objective=obj[: int(nobj.value)].copy())
+
+
 def quantize_group(centroids, x_u16):
     centroids = _c(centroids, np.uint16)
     S = centroids.size // K
