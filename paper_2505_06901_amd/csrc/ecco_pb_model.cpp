@@ -466,7 +466,7 @@ int ecco_pb_fit(const uint16_t* data, size_t n_values, int S, uint64_t seed, ecc
         int t = 0;
         for (int i = 0; i < kGroup; ++i)
             if (i != a) v[t++] = s > 0.0f ? std::min(1.0f, std::max(-1.0f, half_bits_to_float(x[i]) / s)) : 0.0f;
-        std::sort(v, v + kGroup - 1);
+        std::sort(v, v + (kGroup - 1));
         kmeans_1d(v, kGroup - 1, kCent, &pats[j * kCent]);
     });
     // shared patterns
