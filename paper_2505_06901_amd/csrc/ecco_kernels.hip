@@ -17,6 +17,10 @@
 #include <hip/hip_fp16.h>
 
 #include <algorithm>
+#include <atomic>
+#include <mutex>
+#include <utility>
+#include <vector>
 
 #include "ecco_internal.h"
 
@@ -311,11 +315,17 @@ __device__ __forceinline__ UnitLoad load_unit(const uint4* __restrict__ blocks, 
     u.meta = meta[row_base + min(g, gpr - 1)];
     return u;
 }
+// Lane l writes pieces of blocks l / 4 and l / 4 + 16; the chains are then read by other lanes (lane b and b + 32
+// read block b).  The exchange goes through the wavefront's private buffer without a workgroup barrier, so it is
+// fenced on both sides at wavefront scope: the reads of the previous unit come before these writes, and these
+// writes before the reads that follow.
 __device__ __forceinline__ void store_unit(uint32_t* wbuf, const UnitLoad& u, int lane) {
+    wave_lds_fence();
     uint32_t* d = wbuf + (lane >> 2) * kStride + (lane & 3) * 4;
     d[0] = u.v0.x; d[1] = u.v0.y; d[2] = u.v0.z; d[3] = u.v0.w;
     d += 16 * kStride;
     d[0] = u.v1.x; d[1] = u.v1.y; d[2] = u.v1.z; d[3] = u.v1.w;
+    wave_lds_fence();
 }
 
 template <bool kLong>
@@ -494,10 +504,10 @@ __global__ __launch_bounds__(kDecWaves * 64) void decode_kernel(const uint32_t* 
 
     const int blk = lane & (kUnitBlocks - 1), half = lane >> 5;  // block of the unit and chain of this lane
     for (; u < u_end; u += kDecWaves) {
-        wave_lds_fence();  // the previous unit's image has been read
-        store_unit(wbuf, pre, lane);
-        if (lane < kUnitBlocks) wbuf[lane * kStride + kBlockWords] = 0u;  // zero pads of the payload buffer
+        store_unit(wbuf, pre, lane);  // fenced: the previous unit's image has been read
+        if (lane < kUnitBlocks) wbuf[lane * kStride + kBlockWords] = 0u;  // zero pads of the payload buffer (the image lay over them)
         if (lane == 0) wbuf[kUnitBlocks * kStride] = 0u;
+        wave_lds_fence();
         const uint32_t mw = pre.meta;
         if (u + kDecWaves < u_end) pre = load_unit(blocks, meta, 0, n_groups, u + kDecWaves, lane);
         const Lane L = lane_setup(T, mw, S);
@@ -1500,22 +1510,33 @@ inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_
 
 inline int model_ready(const ecco_model* m) { return (m && m->dev && m->device >= 0) ? ECCO_OK : ECCO_EINVAL; }
 
-template <class K>
-int allow_lds(K kernel, size_t bytes) {
-    if (bytes > 64 * 1024)
-        ECCO_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+// A kernel that needs more than 64 KB of LDS has to be told so; the attribute belongs to the kernel (on the
+// current device), not to a launch, so it is set the first time a kernel is launched on a device -- to the most
+// any launch can ask for -- and remembered (a short list under a mutex: host threads may enter together).
+int allow_lds_once(const void* kernel, int device, size_t bytes) {
+    if (bytes <= 64 * 1024) return ECCO_OK;
+    static std::mutex lock;
+    static std::vector<std::pair<const void*, int>> done;
+    std::lock_guard<std::mutex> hold(lock);
+    for (const auto& d : done)
+        if (d.first == kernel && d.second == device) return ECCO_OK;
+    ECCO_HIP_CHECK(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+    done.emplace_back(kernel, device);
     return ECCO_OK;
 }
+template <class K>
+int allow_lds(K kernel, int device, size_t bytes) { return allow_lds_once(reinterpret_cast<const void*>(kernel), device, bytes); }
 
+// compute units of a device, asked once per device (atomics: host threads may race to fill the cache, with the same value)
 int cu_count(int device) {
-    static int cached[16] = {0};
+    static std::atomic<int> cached[16];
     if (device < 0 || device >= 16) return 256;
-    if (!cached[device]) {
-        int n = 0;
+    int n = cached[device].load(std::memory_order_relaxed);
+    if (n == 0) {
         if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || n <= 0) n = 256;
-        cached[device] = n;
+        cached[device].store(n, std::memory_order_relaxed);
     }
-    return cached[device];
+    return n;
 }
 
 }  // namespace
@@ -1558,8 +1579,9 @@ static int decode_common(const ecco_model* m, const void* blocks, const uint32_t
     const int grid = (units + units_per_wg - 1) / units_per_wg;
     const size_t lds = decode_lds_bytes(m->S);
     const bool lng = m->max_len > kPeekBits;
+    const int dev_id = m->device;
     auto launch = [&](auto kernel) -> int {
-        int rc = allow_lds(kernel, lds);
+        int rc = allow_lds(kernel, dev_id, lds);
         if (rc != ECCO_OK) return rc;
         hipLaunchKernelGGL(kernel, dim3(grid), dim3(kDecWaves * 64), lds, static_cast<hipStream_t>(stream), m->dev, m->S,
                            static_cast<const uint4*>(blocks), meta, (int)n_groups, units_per_wg, dst);
@@ -1592,7 +1614,7 @@ int ecco_decode_gemv(const ecco_model* m, const void* blocks, const uint32_t* me
         // one band of rows per workgroup, one workgroup per compute unit where the matrix allows it
         const int band = std::min(kMaxBandRows, std::max(1, (rows + cus - 1) / cus));
         const size_t lds = gemv_lds_bytes(m->S, gpr);
-        int rc = lng ? allow_lds(gemv_kernel<true>, lds) : allow_lds(gemv_kernel<false>, lds);
+        int rc = lng ? allow_lds(gemv_kernel<true>, m->device, lds) : allow_lds(gemv_kernel<false>, m->device, lds);
         if (rc != ECCO_OK) return rc;
         const uint32_t* xb = reinterpret_cast<const uint32_t*>(x);
         const int grid = (rows + band - 1) / band;
@@ -1608,7 +1630,7 @@ int ecco_decode_gemv(const ecco_model* m, const void* blocks, const uint32_t* me
         const int rb_per_wg = std::max(1, (total_rb + cus - 1) / cus);
         const int grid = (total_rb + rb_per_wg - 1) / rb_per_wg;
         const size_t glds = gemm_lds_bytes(m->S);
-        int rc = lng ? allow_lds(gemm_kernel<true>, glds) : allow_lds(gemm_kernel<false>, glds);
+        int rc = lng ? allow_lds(gemm_kernel<true>, m->device, glds) : allow_lds(gemm_kernel<false>, m->device, glds);
         if (rc != ECCO_OK) return rc;
         if (lng)
             hipLaunchKernelGGL(gemm_kernel<true>, dim3(grid), dim3(kGemvThreads), glds, st, m->dev, m->S,
@@ -1625,7 +1647,7 @@ static int kv_append_common(bool minmax, const ecco_model* mk, const ecco_model*
                             void* k_blocks, uint32_t* k_meta, void* v_blocks, uint32_t* v_meta,
                             const int32_t* seq_len, int B, int H, int T_max, void* stream) {
     if (!mk || !mv || !k_new || !v_new || !k_blocks || !k_meta || !v_blocks || !v_meta || !seq_len) return ECCO_EINVAL;
-    if (B <= 0 || H <= 0 || T_max <= 0) return ECCO_ESHAPE;
+    if (B <= 0 || H <= 0 || T_max <= 0 || (long long)B * H > 0x7FFFFFFF) return ECCO_ESHAPE;
     if (!aligned(k_blocks, 64) || !aligned(v_blocks, 64) || !aligned(k_new, 4) || !aligned(v_new, 4)) return ECCO_EALIGN;
     if (model_ready(mk) != ECCO_OK || model_ready(mv) != ECCO_OK || mk->device != mv->device) return ECCO_EINVAL;
     const dim3 grid(minmax ? (B * H + kEncWaves - 1) / kEncWaves : B * H, 2);
@@ -1663,47 +1685,67 @@ size_t ecco_kv_attend_gqa_workspace(int B, int Hq, int n_splits) {
     return (size_t)B * Hq * n_splits * (kGroup + 2) * sizeof(float);
 }
 
-int ecco_kv_attend_gqa(const ecco_model* mk, const ecco_model* mv, const uint16_t* q,
-                       const void* k_blocks, const uint32_t* k_meta, const void* v_blocks, const uint32_t* v_meta,
-                       const int32_t* seq_len, int B, int Hq, int Hkv, int T_max, int n_splits, void* workspace,
-                       float* out, void* stream) {
+// argument checks shared by the two grouped-query entry points (everything but the workspace)
+static int gqa_check(const ecco_model* mk, const ecco_model* mv, const uint16_t* q,
+                     const void* k_blocks, const uint32_t* k_meta, const void* v_blocks, const uint32_t* v_meta,
+                     const int32_t* seq_len, int B, int Hq, int Hkv, int T_max, int n_splits, const float* out) {
     if (!mk || !mv || !q || !k_blocks || !k_meta || !v_blocks || !v_meta || !seq_len || !out) return ECCO_EINVAL;
     if (B <= 0 || Hq <= 0 || Hkv <= 0 || T_max <= 0 || Hq % Hkv != 0 || Hq / Hkv > kGqaMaxGroup) return ECCO_ESHAPE;
-    if (n_splits < 1 || n_splits > 256 || (long long)B * Hkv > 0x7FFFFFFF) return ECCO_ESHAPE;
-    if (n_splits > 1 && !workspace) return ECCO_EINVAL;
-    if (!aligned(k_blocks, 64) || !aligned(v_blocks, 64) || !aligned(q, 16) || !aligned(out, 4) || !aligned(workspace, 16)) return ECCO_EALIGN;
-    if (model_ready(mk) != ECCO_OK || model_ready(mv) != ECCO_OK || mk->device != mv->device) return ECCO_EINVAL;
+    if (n_splits < 1 || n_splits > 256 || (long long)B * Hkv > 0x7FFFFFFF || (long long)B * Hq > 0x7FFFFFFF) return ECCO_ESHAPE;
+    return ECCO_OK;
+}
+
+// the two launches: the attention kernel over (sequence, key/value head, split), then the merge of the splits
+static int gqa_launch(const ecco_model* mk, const ecco_model* mv, const uint16_t* q,
+                      const void* k_blocks, const uint32_t* k_meta, const void* v_blocks, const uint32_t* v_meta,
+                      const int32_t* seq_len, int B, int Hq, int Hkv, int T_max, int n_splits, float* workspace,
+                      float* out, void* stream) {
     const size_t lds = gqa_lds_bytes(mk->S, mv->S, Hq / Hkv);
     const bool lk = mk->max_len > kPeekBits, lv = mv->max_len > kPeekBits;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    const int dev_id = mk->device;
     auto launch = [&](auto kernel) -> int {
-        int rc = allow_lds(kernel, lds);
+        int rc = allow_lds(kernel, dev_id, lds);
         if (rc != ECCO_OK) return rc;
         hipLaunchKernelGGL(kernel, dim3(B * Hkv, n_splits), dim3(kGqaThreads), lds, st, mk->dev, mk->S, mv->dev, mv->S, q,
                            static_cast<const uint4*>(k_blocks), k_meta, static_cast<const uint4*>(v_blocks), v_meta, seq_len,
-                           Hq, Hkv, T_max, out, static_cast<float*>(workspace));
+                           Hq, Hkv, T_max, out, workspace);
         ECCO_HIP_CHECK(hipGetLastError());
         return ECCO_OK;
     };
     const int rc = lk ? (lv ? launch(kv_attend_gqa_kernel<true, true>) : launch(kv_attend_gqa_kernel<true, false>))
                       : (lv ? launch(kv_attend_gqa_kernel<false, true>) : launch(kv_attend_gqa_kernel<false, false>));
     if (rc != ECCO_OK || n_splits == 1) return rc;
-    hipLaunchKernelGGL(kv_attend_combine_kernel, dim3(B * Hq), dim3(kGroup), 0, st, static_cast<const float*>(workspace), B * Hq, n_splits, out);
+    hipLaunchKernelGGL(kv_attend_combine_kernel, dim3(B * Hq), dim3(kGroup), 0, st, workspace, B * Hq, n_splits, out);
     ECCO_HIP_CHECK(hipGetLastError());
     return ECCO_OK;
+}
+
+int ecco_kv_attend_gqa(const ecco_model* mk, const ecco_model* mv, const uint16_t* q,
+                       const void* k_blocks, const uint32_t* k_meta, const void* v_blocks, const uint32_t* v_meta,
+                       const int32_t* seq_len, int B, int Hq, int Hkv, int T_max, int n_splits, void* workspace,
+                       float* out, void* stream) {
+    const int rc = gqa_check(mk, mv, q, k_blocks, k_meta, v_blocks, v_meta, seq_len, B, Hq, Hkv, T_max, n_splits, out);
+    if (rc != ECCO_OK) return rc;
+    if (n_splits > 1 && !workspace) return ECCO_EINVAL;
+    if (!aligned(k_blocks, 64) || !aligned(v_blocks, 64) || !aligned(q, 16) || !aligned(out, 4) || !aligned(workspace, 16)) return ECCO_EALIGN;
+    if (model_ready(mk) != ECCO_OK || model_ready(mv) != ECCO_OK || mk->device != mv->device) return ECCO_EINVAL;
+    return gqa_launch(mk, mv, q, k_blocks, k_meta, v_blocks, v_meta, seq_len, B, Hq, Hkv, T_max, n_splits,
+                      static_cast<float*>(workspace), out, stream);
 }
 
 int ecco_kv_attend(const ecco_model* mk, const ecco_model* mv, const uint16_t* q,
                    const void* k_blocks, const uint32_t* k_meta, const void* v_blocks, const uint32_t* v_meta,
                    const int32_t* seq_len, int B, int H, int T_max, float* out, void* stream) {
     if (!mk || !mv || !q || !k_blocks || !k_meta || !v_blocks || !v_meta || !seq_len || !out) return ECCO_EINVAL;
-    if (B <= 0 || H <= 0 || T_max <= 0) return ECCO_ESHAPE;
+    if (B <= 0 || H <= 0 || T_max <= 0 || (long long)B * H > 0x7FFFFFFF) return ECCO_ESHAPE;
     if (!aligned(k_blocks, 64) || !aligned(v_blocks, 64) || !aligned(q, 16) || !aligned(out, 4)) return ECCO_EALIGN;
     if (model_ready(mk) != ECCO_OK || model_ready(mv) != ECCO_OK || mk->device != mv->device) return ECCO_EINVAL;
     const size_t lds = attn_lds_bytes(mk->S, mv->S);
     const bool lk = mk->max_len > kPeekBits, lv = mv->max_len > kPeekBits;
+    const int dev_id = mk->device;
     auto launch = [&](auto kernel) -> int {
-        int rc = allow_lds(kernel, lds);
+        int rc = allow_lds(kernel, dev_id, lds);
         if (rc != ECCO_OK) return rc;
         hipLaunchKernelGGL(kernel, dim3(B * H), dim3(lv ? 512 : kAttnThreads), lds, static_cast<hipStream_t>(stream), mk->dev, mk->S, mv->dev,
                            mv->S, q, static_cast<const uint4*>(k_blocks), k_meta, static_cast<const uint4*>(v_blocks), v_meta,
