@@ -3,10 +3,13 @@
 
 A step is one pass of the whole hot path over one batch of synthetic input:
   ecco_kv_append (1 new token x 8 sequences x 32 heads, K and V)           -- encoder
-  ecco_decode                on the 4096 x 4096 projection                  -- standalone decode
+  ecco_decode                on the 8192 x 28672 projection (70B class)     -- standalone decode
   ecco_decode_gemv batch 1   on the same projection                         -- THE METRIC
   ecco_decode_gemv batch 8, batch 16
   ecco_kv_attend             8 x 32 heads x 4096 cached tokens
+The headline workload is the largest single-GPU configuration (--workload proj70b, the default); the fused GEMV
+on the smaller matrices (4096 x 4096, 11008 x 4096, 4096 x 11008) is timed the same way after the step and
+reported as further rows of the same line (rows.proj7b_gemv1, rows.mlp_up_gemv16, ...).
 Every call reads a different copy of its compressed input (the copies rotate through > 1 GiB), so
 no launch finds its blocks in the 256 MB last-level cache.  Inputs are resident in HBM before
 the timed region.  The K timed steps are recorded into one HIP graph and replayed once, so the GPU
@@ -33,9 +36,13 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 BYTES_PER_GROUP = 68   # 64-byte payload + 4-byte meta word
-# HBM bytes per launch of the fused batch-1 kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs, scaled by
-# what the same counters read for an 8 MiB plain copy); the summary of those runs is under profiles/
-MEASURED_TRAFFIC_BYTES = {"proj7b": int((4465.2 * 1.994 + 16.0) * 1024)}
+# HBM bytes per launch of the fused batch-1 kernel.  These are NOT measured by this program: they come from two
+# rocprofv3 --pmc runs of it (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch, each scaled by what the same counter
+# reads for a plain copy of known size); the JSON line names the summary file beside the figure (roofline.traffic_from).
+MEASURED_TRAFFIC = {
+    "proj7b": {"bytes": int((4465.6 * 1.994 + 16.0) * 1024), "from": "profiles/bench_step_proj7b.md"},
+}
+WEIGHT_WORKLOADS = {"proj7b": ("proj7b", 0), "mlp_up": ("mlp", 0), "mlp_down": ("mlp", 1), "proj70b": ("proj70b", 0)}
 
 
 def cpu_baseline(m, blocks_np, meta_np, rows, cols, x_np, w_np=None, budget_s=12.0):
@@ -123,7 +130,11 @@ def main():
     ap.add_argument("--selector-quality", action="store_true",
                     help="add the reconstruction error of the min/max pattern selector against the least-squared-error search on the K and V caches")
     ap.add_argument("--kv-patterns", type=int, default=0, help="shared patterns of the K and V models (default: the KV workload's 64; the paper's online compressor uses 16)")
-    ap.add_argument("--workload", default="proj7b", choices=["proj7b", "mlp_up", "mlp_down", "proj70b"])
+    ap.add_argument("--workload", default="proj70b", choices=["proj7b", "mlp_up", "mlp_down", "proj70b"],
+                    help="the matrix of the step and of the headline value (default: the largest single-GPU configuration)")
+    ap.add_argument("--also", default="proj7b,mlp_up,mlp_down",
+                    help="comma list of further matrices whose fused GEMV is timed after the step and reported as extra rows "
+                         "(batch 1 on all, batch 8 and 16 on the MLP pair); empty for none")
     ap.add_argument("--sweep", action="store_true", help="add an ecco_decode sweep over block counts 2^14..2^22 (as far as the workload has blocks)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -143,7 +154,7 @@ def main():
         return not only or row in only
 
     # ---- weights --------------------------------------------------------------------------------
-    wname, which = {"proj7b": ("proj7b", 0), "mlp_up": ("mlp", 0), "mlp_down": ("mlp", 1), "proj70b": ("proj70b", 0)}[args.workload]
+    wname, which = WEIGHT_WORKLOADS[args.workload]
     cfg = W.CONFIGS[wname]
     rows, cols = cfg["shapes"][which]
     w = W.config_weight(wname, which)
@@ -476,6 +487,45 @@ def main():
                           "GBps_total_traffic": n * (BYTES_PER_GROUP + 256) / (t_ms * 1e-3) / 1e9,
                           "rotating_copies": sw_copies, "beyond_matrix": n > n_groups})
 
+    # ---- the fused GEMV on the other matrices: same rotation through > 1 GiB of copies, same graph timing ----------
+    also_rows = {}
+    if want("gemv1") and not args.eager:
+        for other in filter(None, args.also.split(",")):
+            if other == args.workload or other not in WEIGHT_WORKLOADS:
+                continue
+            oname, owhich = WEIGHT_WORKLOADS[other]
+            ocfg = W.CONFIGS[oname]
+            orows, ocols = ocfg["shapes"][owhich]
+            ow = W.config_weight(oname, owhich)
+            om_ = E.ecco_model_to_device(E.ecco_fit_patterns(ow, ocfg["S"], 12, ocfg["seeds"][owhich]), 0)
+            ob0, ome0 = E.ecco_encode(om_, torch.from_numpy(ow).to(dev))
+            del ow
+            o_groups = orows * ocols // 128
+            o_bytes = o_groups * BYTES_PER_GROUP
+            o_copies = max(2, min(256, int(np.ceil((1.25 * 2**30) / o_bytes))))
+            obs = [ob0] + [ob0.clone() for _ in range(o_copies - 1)]
+            oms = [ome0] + [ome0.clone() for _ in range(o_copies - 1)]
+            for b in ((1, 8, 16) if oname == "mlp" else (1,)):
+                ox = torch.from_numpy(W.activation(b, ocols, ocfg["x_seed"])).to(dev)
+                oy = torch.empty((b, orows), dtype=torch.float32, device=dev)
+                def one_round(b=b, ox=ox, oy=oy):
+                    for c in range(o_copies):
+                        E.ecco_decode_gemv(om_, obs[c], oms[c], orows, ocols, ox, oy)
+                for _ in range(2):
+                    one_round()
+                g = capture(one_round)
+                g.replay()
+                torch.cuda.synchronize()
+                replays = max(5, int(np.ceil(max(args.steps, 100) / o_copies)))
+                t_ms = timed_replays(g, replays) / (replays * o_copies)
+                del g
+                also_rows[f"{other}_gemv{b}"] = {
+                    "ms": t_ms, "GBps_compressed": o_bytes / (t_ms * 1e-3) / 1e9, "pct_hbm_peak": 100.0 * o_bytes / (t_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                    "gemv_tokens_per_s": b / (t_ms * 1e-3), "shape": [orows, ocols], "n_groups": o_groups, "rotating_copies": o_copies,
+                    "raw_block_fraction": float(((ome0 >> 22) & 1).float().mean())}
+            del obs, oms, ob0, ome0
+            torch.cuda.empty_cache()
+
     comp_bytes = n_groups * BYTES_PER_GROUP
     rows_out = {}
     for r in row_names:
@@ -518,6 +568,7 @@ def main():
             d["steps_per_s"] = 1.0 / (ms[r] * 1e-3)
             d["GBps_compressed"] = 2 * B * H * T * BYTES_PER_GROUP / (ms[r] * 1e-3) / 1e9
         rows_out[r] = d
+    rows_out.update(also_rows)
 
     metric_row = "gemv1" if want("gemv1") else row_names[0]
     achieved = rows_out[metric_row].get("GBps_compressed", 0.0)
@@ -542,8 +593,11 @@ def main():
                    "read_only_stream_GBps": (n_groups * 64 / (stream_ms * 1e-3) / 1e9) if stream_ms else None,
                    "frac_of_read_only_stream": (achieved / (n_groups * 64 / (stream_ms * 1e-3) / 1e9)) if stream_ms and metric_row == "gemv1" else None},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
-                     "kernel": "fused decode-GEMV, batch 1", "bytes_per_launch": comp_bytes,
+                     "frac": achieved / HBM_PEAK_GBS,
+                     # not measured by this run: counter traffic of the same launch from the named rocprofv3 summary
+                     "traffic": MEASURED_TRAFFIC.get(args.workload, {}).get("bytes"),
+                     "traffic_from": MEASURED_TRAFFIC.get(args.workload, {}).get("from"),
+                     "kernel": "gemv_kernel (fused decode-GEMV, batch 1)", "bytes_per_launch": comp_bytes,
                      "avg_launch_ms": ms.get(metric_row)},
         "rows": rows_out,
         "footprint": {"fp16_bytes": n_groups * 256, "compressed_bytes": comp_bytes, "ratio": 256.0 / BYTES_PER_GROUP,
