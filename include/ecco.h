@@ -226,6 +226,25 @@ int ecco_kv_attend_gqa(const ecco_model* mk, const ecco_model* mv, const uint16_
                        const int32_t* seq_len, int B, int Hq, int Hkv, int T_max, int n_splits, void* workspace,
                        float* out, void* stream);
 
+/* For callers that cannot allocate device memory or pass a workspace (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): ecco_kv_attend_gqa with the token splits' partial results kept in a static
+ * device array inside the library instead of a caller's workspace.  Same arguments (without `workspace`), same kernels,
+ * same results bit for bit.  The call allocates and frees nothing.
+ *   Limit: ecco_kv_attend_gqa_workspace(B, Hq, n_splits) = B * Hq * n_splits * 520 bytes must not exceed
+ *   ECCO_GQA_SCRATCH_BYTES (8 MiB: B * Hq * n_splits <= 16131); larger sizes return ESHAPE and launch nothing.
+ *   n_splits == 1 uses no scratch and has no limit.
+ *   The array exists once per GPU and is shared by every call on that GPU: calls that overlap on one GPU (different
+ *   streams, or host threads) race on it and must be serialised by the caller.  Nothing in it has to start at zero (every
+ *   word that is read was written by the same call), and its contents after a call are unspecified.
+ *   Its device address is looked up when a model is uploaded (ecco_model_to_device), so this call touches no runtime
+ *   service beyond the two kernel launches.
+ * Errors: as ecco_kv_attend_gqa; ESHAPE also for a size beyond the limit. */
+#define ECCO_GQA_SCRATCH_BYTES (8u << 20)
+int ecco_kv_attend_gqa_noalloc(const ecco_model* mk, const ecco_model* mv, const uint16_t* q,
+                               const void* k_blocks, const uint32_t* k_meta, const void* v_blocks, const uint32_t* v_meta,
+                               const int32_t* seq_len, int B, int Hq, int Hkv, int T_max, int n_splits,
+                               float* out, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -20,7 +20,7 @@ EXPORTS = [
     "ecco_model_S", "ecco_model_centroids", "ecco_model_code_lens", "ecco_model_to_device", "ecco_model_free",
     "ecco_encode", "ecco_decode", "ecco_decode_indices", "ecco_decode_gemv", "ecco_kv_append", "ecco_kv_attend",
     "ecco_encode_minmax", "ecco_kv_append_minmax", "ecco_act_encode", "ecco_act_decode",
-    "ecco_kv_attend_gqa", "ecco_kv_attend_gqa_workspace", "ecco_kv_attend_gqa_splits", "ecco_read_stream", "ecco_device_info",
+    "ecco_kv_attend_gqa", "ecco_kv_attend_gqa_workspace", "ecco_kv_attend_gqa_splits", "ecco_kv_attend_gqa_noalloc", "ecco_read_stream", "ecco_device_info",
     "ecco_pb_fit", "ecco_pb_model_create", "ecco_pb_model_S", "ecco_pb_model_texp", "ecco_pb_model_centroids",
     "ecco_pb_model_code_lens", "ecco_pb_model_kp_lens", "ecco_pb_model_to_device", "ecco_pb_model_free",
     "ecco_pb_encode", "ecco_pb_decode", "ecco_pb_decode_gemv", "ecco_pb_model_save", "ecco_pb_model_load",
@@ -63,6 +63,7 @@ def lib():
         L.ecco_act_encode.argtypes = [vp, sz, vp, vp]
         L.ecco_read_stream.argtypes = [vp, sz, vp, vp]
         L.ecco_kv_attend_gqa.argtypes = [vp] * 8 + [i32, i32, i32, i32, i32, vp, vp, vp]
+        L.ecco_kv_attend_gqa_noalloc.argtypes = [vp] * 8 + [i32, i32, i32, i32, i32, vp, vp]
         L.ecco_kv_attend_gqa_workspace.argtypes = [i32, i32, i32]
         L.ecco_kv_attend_gqa_workspace.restype = sz
         L.ecco_kv_attend_gqa_splits.argtypes = [i32, i32, i32, i32]
@@ -279,6 +280,18 @@ def ecco_kv_attend_gqa(mk: Model, mv: Model, q, k_blocks, k_meta, v_blocks, v_me
     _check(lib().ecco_kv_attend_gqa(mk.handle, mv.handle, _dp(q), _dp(k_blocks), _dp(k_meta), _dp(v_blocks), _dp(v_meta),
                                     _dp(seq_len), B, Hq, Hkv, T_max, n_splits, _dp(workspace), _dp(out), _stream()),
            "ecco_kv_attend_gqa")
+    return out
+
+
+GQA_SCRATCH_BYTES = 8 << 20  # ECCO_GQA_SCRATCH_BYTES of include/ecco.h
+
+
+def ecco_kv_attend_gqa_noalloc(mk: Model, mv: Model, q, k_blocks, k_meta, v_blocks, v_meta, seq_len, B, Hq, Hkv, T_max, n_splits, out):
+    """ecco_kv_attend_gqa with the splits' partial results in the library's static device array: the caller passes
+    every buffer (`out` included) and nothing is allocated, here or in the library."""
+    _check(lib().ecco_kv_attend_gqa_noalloc(mk.handle, mv.handle, _dp(q), _dp(k_blocks), _dp(k_meta), _dp(v_blocks), _dp(v_meta),
+                                            _dp(seq_len), B, Hq, Hkv, T_max, n_splits, _dp(out), _stream()),
+           "ecco_kv_attend_gqa_noalloc")
     return out
 
 

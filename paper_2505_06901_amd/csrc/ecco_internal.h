@@ -62,6 +62,10 @@ void derive_codes(ecco_model* m);
 // fills a host image of the device tables (DevLayout{S}.image_words() words; counters zero)
 void build_device_image(const ecco_model* m, uint32_t* img);
 
+// looks up, for `device` (which must be current), the device address of the static scratch array that
+// ecco_kv_attend_gqa_noalloc uses; defined beside that array in ecco_kernels.hip.  ECCO_OK or ECCO_EHIP.
+int init_device_scratch(int device);
+
 // host-side half conversion helpers (compiler-provided _Float16 arithmetic)
 inline float half_bits_to_float(uint16_t h) {
     _Float16 v;

@@ -1505,6 +1505,29 @@ __global__ __launch_bounds__(kGroup) void kv_attend_combine_kernel(const float* 
     out[bh * kGroup + threadIdx.x] = den > 0.0f ? num / den : 0.0f;
 }
 
+// ---- device scratch of the entry point that allocates nothing -----------------------------------------------
+// ecco_kv_attend_gqa_noalloc keeps the token splits' partial results here instead of in a caller's workspace.
+// Each GPU the library runs on holds its own copy of the array, at its own address, until the process ends.  In host
+// code the array's name is only a handle: the address kernels can use comes from hipGetSymbolAddress, asked once
+// per device with that device current, and is what every launch and every host call is given.
+static __device__ __align__(256) float scratch[ECCO_GQA_SCRATCH_BYTES / sizeof(float)];
+
+constexpr int kMaxDevices = 16;
+std::mutex scratch_lock;
+float* scratch_ptr[kMaxDevices] = {};  // device address of `scratch` on each device, once asked
+
+// The address of `scratch` on `device`, which must be the current device.  nullptr if the runtime refuses.
+float* scratch_on_current_device(int device) {
+    if (device < 0 || device >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> hold(scratch_lock);
+    if (!scratch_ptr[device]) {
+        float* p = nullptr;
+        if (hipGetSymbolAddress(reinterpret_cast<void**>(&p), HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        scratch_ptr[device] = p;
+    }
+    return scratch_ptr[device];
+}
+
 // ---- host side -----------------------------------------------------------------------------------------
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
@@ -1540,6 +1563,12 @@ int cu_count(int device) {
 }
 
 }  // namespace
+
+namespace ecco {
+// Called by ecco_model_to_device with `device` current: asks for the scratch array's address on that device, so that
+// the entry point that allocates nothing finds it ready (also under stream capture).
+int init_device_scratch(int device) { return scratch_on_current_device(device) ? ECCO_OK : ECCO_EHIP; }
+}  // namespace ecco
 
 extern "C" {
 
@@ -1732,6 +1761,34 @@ int ecco_kv_attend_gqa(const ecco_model* mk, const ecco_model* mv, const uint16_
     if (model_ready(mk) != ECCO_OK || model_ready(mv) != ECCO_OK || mk->device != mv->device) return ECCO_EINVAL;
     return gqa_launch(mk, mv, q, k_blocks, k_meta, v_blocks, v_meta, seq_len, B, Hq, Hkv, T_max, n_splits,
                       static_cast<float*>(workspace), out, stream);
+}
+
+int ecco_kv_attend_gqa_noalloc(const ecco_model* mk, const ecco_model* mv, const uint16_t* q,
+                               const void* k_blocks, const uint32_t* k_meta, const void* v_blocks, const uint32_t* v_meta,
+                               const int32_t* seq_len, int B, int Hq, int Hkv, int T_max, int n_splits,
+                               float* out, void* stream) {
+    const int rc = gqa_check(mk, mv, q, k_blocks, k_meta, v_blocks, v_meta, seq_len, B, Hq, Hkv, T_max, n_splits, out);
+    if (rc != ECCO_OK) return rc;
+    // the partial results of the splits must fit the static array
+    if (n_splits > 1 && ecco_kv_attend_gqa_workspace(B, Hq, n_splits) > (size_t)ECCO_GQA_SCRATCH_BYTES) return ECCO_ESHAPE;
+    if (!aligned(k_blocks, 64) || !aligned(v_blocks, 64) || !aligned(q, 16) || !aligned(out, 4)) return ECCO_EALIGN;
+    if (model_ready(mk) != ECCO_OK || model_ready(mv) != ECCO_OK || mk->device != mv->device) return ECCO_EINVAL;
+    float* ws = nullptr;
+    if (n_splits > 1) {
+        // this device's copy of the array: asked for when the model was uploaded; looked up here otherwise, which
+        // needs the model's device to be the current one
+        {
+            std::lock_guard<std::mutex> hold(scratch_lock);
+            ws = mk->device < kMaxDevices ? scratch_ptr[mk->device] : nullptr;
+        }
+        if (!ws) {
+            int cur = -1;
+            if (hipGetDevice(&cur) != hipSuccess || cur != mk->device) return ECCO_EINVAL;
+            ws = scratch_on_current_device(cur);
+            if (!ws) return ECCO_EHIP;
+        }
+    }
+    return gqa_launch(mk, mv, q, k_blocks, k_meta, v_blocks, v_meta, seq_len, B, Hq, Hkv, T_max, n_splits, ws, out, stream);
 }
 
 int ecco_kv_attend(const ecco_model* mk, const ecco_model* mv, const uint16_t* q,

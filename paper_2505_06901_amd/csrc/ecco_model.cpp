@@ -165,8 +165,9 @@ int ecco_model_to_device(ecco_model* m, int device) {
         return e == hipErrorOutOfMemory ? ECCO_ENOMEM : ECCO_EHIP;
     }
     e = hipMemcpy(d, img.data(), D.image_words() * 4, hipMemcpyHostToDevice);
+    const int scratch_rc = init_device_scratch(device);  // while `device` is current
     (void)hipSetDevice(prev);
-    if (e != hipSuccess) {
+    if (e != hipSuccess || scratch_rc != ECCO_OK) {
         (void)hipFree(d);
         return ECCO_EHIP;
     }

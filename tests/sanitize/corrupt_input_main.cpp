@@ -13,6 +13,12 @@
 #include "../../oracle/ecco_oracle.h"
 #include "../../oracle/ecco_paper_block.h"
 
+// the model source asks the kernel source for a device address when a model is uploaded; this program has no kernel
+// source and uploads nothing
+namespace ecco {
+int init_device_scratch(int) { return 0; }
+}  // namespace ecco
+
 namespace {
 
 struct Rng {
