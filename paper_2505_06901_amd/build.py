@@ -9,6 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libecco.so")
+PROBE = os.path.join(HERE, "probe_lds")  # stand-alone measurement program (csrc/probe_lds.hip), not part of the library
 SOURCES = ["ecco_fit.cpp", "ecco_model.cpp", "ecco_pb_model.cpp", "ecco_kernels.hip", "ecco_act.hip", "ecco_pb_kernels.hip"]
 
 
@@ -78,6 +79,14 @@ def build(verbose: bool = False) -> str:
     if verbose:
         print(" ".join(cmd))
     subprocess.check_call(cmd)
+    # the LDS / decode-loop probe: a program of its own, so that its figures can be reproduced without the library
+    cmd = [_hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           os.path.join(CSRC, "probe_lds.hip"), "-o", PROBE]
+    if verbose:
+        print(" ".join(cmd))
+    proc = subprocess.run(cmd, stderr=subprocess.PIPE, text=True)
+    if proc.returncode != 0:
+        raise RuntimeError("compiling probe_lds.hip failed:\n%s" % proc.stderr)
     return LIB
 
 
