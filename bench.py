@@ -41,6 +41,7 @@ BYTES_PER_GROUP = 68   # 64-byte payload + 4-byte meta word
 # reads for a plain copy of known size); the JSON line names the summary file beside the figure (roofline.traffic_from).
 MEASURED_TRAFFIC = {
     "proj7b": {"bytes": int((4465.6 * 1.994 + 16.0) * 1024), "from": "profiles/bench_step_proj7b.md"},
+    "proj70b": {"bytes": int((61376.5 * 1.9994 + 32.0) * 1024), "from": "profiles/bench_default_proj70b.md"},
 }
 WEIGHT_WORKLOADS = {"proj7b": ("proj7b", 0), "mlp_up": ("mlp", 0), "mlp_down": ("mlp", 1), "proj70b": ("proj70b", 0)}
 
