@@ -39,6 +39,8 @@
  *     synchronising.  Argument errors are detected on the host before anything is launched, in
  *     this order: null pointers (EINVAL), sizes (ESHAPE), alignment (EALIGN), and last whether the
  *     model is on a device (EINVAL) -- so the first three can be checked on a machine without a GPU.
+ *   - device work is launched on the calling thread's current device, which must be the device the
+ *     model was uploaded to; with another device current the call returns ECCO_EINVAL.
  *   - FP16 travels as uint16_t bit patterns.
  */
 #ifndef ECCO_H

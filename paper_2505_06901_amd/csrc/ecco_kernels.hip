@@ -1531,7 +1531,13 @@ float* scratch_on_current_device(int device) {
 // ---- host side -----------------------------------------------------------------------------------------
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
-inline int model_ready(const ecco_model* m) { return (m && m->dev && m->device >= 0) ? ECCO_OK : ECCO_EINVAL; }
+// a model can be used once it is on a device, and only while that device is the calling thread's current one: the
+// kernels are launched on the current device and read the model's tables through device pointers
+inline int model_ready(const ecco_model* m) {
+    if (!m || !m->dev || m->device < 0) return ECCO_EINVAL;
+    int cur = -1;
+    return (hipGetDevice(&cur) == hipSuccess && cur == m->device) ? ECCO_OK : ECCO_EINVAL;
+}
 
 // A kernel that needs more than 64 KB of LDS has to be told so; the attribute belongs to the kernel (on the
 // current device), not to a launch, so it is set the first time a kernel is launched on a device -- to the most

@@ -554,7 +554,13 @@ __global__ __launch_bounds__(kEncThreads) void pb_encode_kernel(const uint32_t* 
 }
 
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
-inline int model_ready(const ecco_pb_model* m) { return (m && m->dev && m->device >= 0) ? ECCO_OK : ECCO_EINVAL; }
+// a model can be used once it is on a device, and only while that device is the calling thread's current one: the
+// kernels are launched on the current device and read the model's tables through device pointers
+inline int model_ready(const ecco_pb_model* m) {
+    if (!m || !m->dev || m->device < 0) return ECCO_EINVAL;
+    int cur = -1;
+    return (hipGetDevice(&cur) == hipSuccess && cur == m->device) ? ECCO_OK : ECCO_EINVAL;
+}
 
 template <class K>
 int allow_lds(K kernel, size_t bytes) {

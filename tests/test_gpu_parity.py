@@ -794,6 +794,28 @@ def test_repeated_launches_are_identical(dev, oracle):
             assert torch.equal(first, again), batch
 
 
+@pytest.mark.parametrize("rows,cols", [(8192, 4096), (12288, 4352)])
+def test_batched_gemv_all_wavefronts_busy_repeatable(dev, oracle, rows, cols):
+    """The batched kernel where every one of its sixteen wavefronts has units and a workgroup has two or three row
+    blocks, under a 16-pattern model (the per-wavefront slices then straddle the 64 KB mark of the LDS): every row block
+    of every launch right against the decoded matrix (the decoder is checked against the oracle elsewhere), and twenty
+    launches bit for bit.  A timing-dependent slip in this regime shows as single wrong row blocks that move from launch
+    to launch."""
+    wt = W.config_weight("tiny")
+    m = E.ecco_model_to_device(E.ecco_fit_patterns(wt, 16, 12, 0), 0)
+    w = W.weight_matrix(rows, cols, 0.02, 1e-3, 10.0, 5)
+    blocks, meta = E.ecco_encode(m, t16(w, dev))
+    dec = E.ecco_decode(m, blocks, meta).float().reshape(rows, cols)
+    for batch in (4, 16):
+        xb = t16(W.activation(batch, cols, 60 + batch), dev)
+        ref = xb.float() @ dec.T
+        bound = xb.float().abs() @ dec.abs().T
+        first = E.ecco_decode_gemv(m, blocks, meta, rows, cols, xb)
+        assert bool(((first - ref).abs() <= REL_L2 * bound + 1e-30).all()), batch
+        for _ in range(20):
+            assert torch.equal(first, E.ecco_decode_gemv(m, blocks, meta, rows, cols, xb)), batch
+
+
 @pytest.mark.parametrize("rows,cols", [(37, 8192), (8200, 1024), (48, 4096), (16400, 256)])
 def test_batched_gemv_repeatable_with_long_codes(dev, oracle, rows, cols):
     """The batched kernel's long-code variant on shapes with several units per wavefront (37 x 8192), with three row
