@@ -43,6 +43,13 @@ MEASURED_TRAFFIC = {
     "proj7b": {"bytes": int((4465.6 * 1.994 + 16.0) * 1024), "from": "profiles/bench_step_proj7b.md"},
     "proj70b": {"bytes": int((61376.5 * 1.9994 + 32.0) * 1024), "from": "profiles/bench_default_proj70b.md"},
 }
+# Which resource the fused batch-1 kernel saturates on the headline workload, from the SQ counters of the same summary
+# (not measured by this program either): share of the kernel's cycles in which a compute unit's LDS pipeline is active,
+# and LDS / VALU issue cycles per wavefront and decoded value.
+OBSERVED_LIMIT = {
+    "proj70b": {"resource": "LDS gather rate (table reads with bank conflicts), not HBM", "lds_pipeline_active_frac": 0.827,
+                "lds_cycles_per_wave_value": 8.8, "valu_cycles_per_wave_value": 7.3, "from": "profiles/bench_default_proj70b.md"},
+}
 WEIGHT_WORKLOADS = {"proj7b": ("proj7b", 0), "mlp_up": ("mlp", 0), "mlp_down": ("mlp", 1), "proj70b": ("proj70b", 0)}
 
 
@@ -599,7 +606,12 @@ def main():
                      "traffic": MEASURED_TRAFFIC.get(args.workload, {}).get("bytes"),
                      "traffic_from": MEASURED_TRAFFIC.get(args.workload, {}).get("from"),
                      "kernel": "gemv_kernel (fused decode-GEMV, batch 1)", "bytes_per_launch": comp_bytes,
-                     "avg_launch_ms": ms.get(metric_row)},
+                     "avg_launch_ms": ms.get(metric_row),
+                     # this run's time in cycles (2.4 GHz) per wavefront and decoded value and compute unit, to set beside
+                     # the counter figures of observed_limit
+                     "cycles_per_wave_value": (ms[metric_row] * 1e-3 * 2.4e9 / (n_groups * 2.0 / torch.cuda.get_device_properties(dev).multi_processor_count))
+                                              if ms.get(metric_row) else None,
+                     "observed_limit": OBSERVED_LIMIT.get(args.workload)},
         "rows": rows_out,
         "footprint": {"fp16_bytes": n_groups * 256, "compressed_bytes": comp_bytes, "ratio": 256.0 / BYTES_PER_GROUP,
                       "payload_bytes": n_groups * 64, "meta_bytes": n_groups * 4, "model_blob_bytes": len(E.ecco_model_save(m))},

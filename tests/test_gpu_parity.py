@@ -896,11 +896,12 @@ def test_graph_replay_matches_eager(dev, oracle, tiny):
     y8 = torch.empty((8, rows), dtype=torch.float32, device=dev)
     att = torch.empty((B, H, 128), dtype=torch.float32, device=dev)
     gqa = torch.empty((B, H, 128), dtype=torch.float32, device=dev)
+    gqa_na = torch.empty((B, H, 128), dtype=torch.float32, device=dev)
     ws = torch.empty((B * H * 2 * 130 * 4,), dtype=torch.uint8, device=dev)  # ecco_kv_attend_gqa_workspace(B, Hq, 2) bytes
     ab = torch.empty((rows * cols // 64, 64), dtype=torch.uint8, device=dev)
     adec = torch.empty((rows, cols), dtype=torch.float16, device=dev)
 
-    outs = lambda: [t.clone() for t in (blocks, meta, dec, y1, y8, att, gqa, ab, adec, kb, km, vb, vm)]
+    outs = lambda: [t.clone() for t in (blocks, meta, dec, y1, y8, att, gqa, gqa_na, ab, adec, kb, km, vb, vm)]
     seq1 = seq + 1  # built outside the capture: the graph holds kernels of the library only
     def run_all():  # what is recorded: calls of the library only
         E.ecco_encode(m, w_in, blocks, meta)
@@ -910,6 +911,7 @@ def test_graph_replay_matches_eager(dev, oracle, tiny):
         E.ecco_kv_append(mk, mv, kn_in, vn_in, kb, km, vb, vm, seq, B, H, T)
         E.ecco_kv_attend(mk, mv, q_in, kb, km, vb, vm, seq1, B, H, T, att)
         E.ecco_kv_attend_gqa(mk, mv, q_in, kb, km, vb, vm, seq1, B, H, H // 2, T, 2, ws, gqa)
+        E.ecco_kv_attend_gqa_noalloc(mk, mv, q_in, kb, km, vb, vm, seq1, B, H, H // 2, T, 2, gqa_na)  # splits in the static array
         E.ecco_act_encode(w_in, ab)
         E.ecco_act_decode(ab, adec)
 
@@ -927,7 +929,7 @@ def test_graph_replay_matches_eager(dev, oracle, tiny):
         run_all()
         torch.cuda.synchronize()
         want = outs()
-        for t in (blocks, meta, dec, y1, y8, att, gqa, ab, adec):
+        for t in (blocks, meta, dec, y1, y8, att, gqa, gqa_na, ab, adec):
             t.zero_()
         for dst, src in zip((kb, km, vb, vm), (kb0, km0, vb0, vm0)):
             dst.copy_(src)
@@ -936,3 +938,4 @@ def test_graph_replay_matches_eager(dev, oracle, tiny):
         torch.cuda.synchronize()
         for i, (a, b) in enumerate(zip(outs(), want)):
             assert torch.equal(a.view(torch.uint8), b.view(torch.uint8)), (rep, i)
+        assert torch.equal(gqa, gqa_na), rep
