@@ -261,3 +261,24 @@ def test_bench_refuses_more_than_one_gpu():
     p = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
     assert p.returncode != 0
     assert "one GPU" in (p.stderr + p.stdout)
+
+
+def test_build_flags_a_64_bit_shift_by_the_last_allocated_register():
+    """The build's check of generated code: a 64-bit shift whose amount is the last register of its kernel's allocation
+    (next_free_vgpr rounded up to 8) is reported; the same shift by a lower register, by the top register of a kernel
+    whose allocation is larger, and a 32-bit shift are not."""
+    from paper_2505_06901_amd import build
+
+    def kernel(name, body, n):
+        return "\n".join(["\t.type\t%s,@function" % name, "%s:" % name, *["\t" + b for b in body], "\ts_endpgm",
+                          "\t.amdhsa_kernel %s" % name, "\t\t.amdhsa_next_free_vgpr %d" % n, "\t.end_amdhsa_kernel"])
+
+    asm = "\n".join([
+        kernel("k_hit", ["v_lshlrev_b64 v[2:3], v119, v[4:5]", ".LBB0_1:", "v_ashrrev_i64 v[6:7], v119, v[6:7] ; comment v119"], 120),
+        kernel("k_lower", ["v_lshlrev_b64 v[2:3], v118, v[4:5]", "v_lshlrev_b32_e32 v1, v119, v2", "v_add_u32_e32 v119, v1, v2"], 120),
+        kernel("k_room", ["v_lshrrev_b64 v[2:3], v112, v[4:5]"], 113),       # allocation 120, last register v119 unused
+        kernel("k_rounded", ["v_lshrrev_b64 v[2:3], v119, v[4:5]"], 118),    # would not assemble to 118, but the rule is the allocation's
+    ])
+    hits = build.last_register_shifts(asm)
+    assert [h[0] for h in hits] == ["k_hit", "k_hit", "k_rounded"]
+    assert hits[0][1].startswith("v_lshlrev_b64") and hits[1][1].startswith("v_ashrrev_i64")
