@@ -26,16 +26,19 @@ def _hipcc() -> str:
 _SGPR_SPILL_TOLERATED = ("kv_attend_gqa_kernelILb1ELb1E",)
 
 
-def _check_kernel_resources(remarks: str, verbose: bool) -> None:
+def _check_kernel_resources(remarks: str, verbose: bool) -> dict:
     """Every kernel must keep its working set in registers: a kernel that spills to scratch memory is
     far off its design point (the decode loops are sized for 1024-thread workgroups, 128 VGPRs), so
     a register spill is a build error rather than a silent slowdown."""
-    name, found = None, 0
+    name, found, vgprs = None, 0, {}
     for line in remarks.splitlines():
         m = re.search(r"remark:\s+Function Name: (\S+)", line)
         if m:
             name = m.group(1)
             continue
+        m = re.search(r"remark:\s+VGPRs: (\d+)", line)
+        if m and name:
+            vgprs[name] = int(m.group(1))
         m = re.search(r"remark:\s+ScratchSize \[bytes/lane\]: (\d+)", line)
         if m and name:
             found += 1
@@ -52,6 +55,7 @@ def _check_kernel_resources(remarks: str, verbose: bool) -> None:
                 raise RuntimeError("kernel %s spills %s %s" % (name, m.group(2), m.group(1)))
     if found == 0:
         raise RuntimeError("no kernel resource remarks found: cannot verify register use")
+    return vgprs
 
 
 # On the MI355X boxes this library was developed on, a 64-bit shift (v_lshlrev_b64, v_lshrrev_b64, v_ashrrev_i64) whose
@@ -99,13 +103,29 @@ def last_register_shifts(asm: str) -> list:
     return hits
 
 
-def _check_last_register_shift(path: str, flags: list, verbose: bool) -> None:
+def kernel_register_counts(asm: str) -> dict:
+    """kernel -> .amdhsa_next_free_vgpr of the assembly text `asm`."""
+    counts, pending = {}, None
+    for line in asm.splitlines():
+        m = re.match(r"\s*\.amdhsa_kernel\s+(\S+)", line)
+        if m:
+            pending = m.group(1)
+        m = re.match(r"\s*\.amdhsa_next_free_vgpr\s+(\d+)", line)
+        if m and pending:
+            counts[pending], pending = int(m.group(1)), None
+    return counts
+
+
+def _check_last_register_shift(path: str, flags: list, compiled_vgprs: dict, verbose: bool) -> None:
     proc = subprocess.run([_hipcc(), "--offload-arch=gfx950", *flags, "-S", "--cuda-device-only", path, "-o", "-"],
                           stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True)
     if proc.returncode != 0:
         raise RuntimeError("generating assembly for %s failed:\n%s" % (path, proc.stderr))
     if ".amdhsa_kernel" not in proc.stdout:
         raise RuntimeError("no kernel found in the assembly of %s: cannot check its shifts" % path)
+    # the assembly must be that of the object just compiled: same kernels, same register counts
+    if kernel_register_counts(proc.stdout) != compiled_vgprs:
+        raise RuntimeError("the assembly generated for %s does not match the compiled object (kernels or register counts differ)" % path)
     hits = last_register_shifts(proc.stdout)
     if verbose:
         print("  %s: %d 64-bit shifts by the last allocated register" % (os.path.basename(path), len(hits)))
@@ -134,8 +154,8 @@ def build(verbose: bool = False) -> str:
         if proc.returncode != 0:
             raise RuntimeError("compiling %s failed:\n%s" % (src, proc.stderr))
         if src.endswith(".hip"):
-            _check_kernel_resources(proc.stderr, verbose)
-            _check_last_register_shift(path, device_flags, verbose)
+            compiled_vgprs = _check_kernel_resources(proc.stderr, verbose)
+            _check_last_register_shift(path, device_flags, compiled_vgprs, verbose)
         objs.append(obj)
     cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB, "-lpthread"]
     if verbose:
